@@ -1,0 +1,241 @@
+"""Pins for the FP8 E4M3 codec and the per-row quantiser of the oracle (CPU only).
+
+Sources that are not the oracle itself: the format's named points
+(tests/golden/e4m3_format_points.txt), exact rational arithmetic with
+fractions.Fraction, torch.float8_e4m3fn casts (inside +-448 only: torch does
+not saturate above it), and invariants Algorithm 1 implies.
+"""
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import usp_oracle as orc
+from paper_2602_10940_amd import workloads as wlmod
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden", "e4m3_format_points.txt")
+
+
+def _golden_points():
+    pts = []
+    with open(GOLD) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            code, val = line.split()
+            pts.append((int(code, 16), float(val)))
+    return pts
+
+
+def test_decode_matches_named_format_points():
+    tab = orc.e4m3fn_decode_table()
+    for code, val in _golden_points():
+        if math.isnan(val):
+            assert math.isnan(tab[code])
+        else:
+            assert tab[code] == val
+            assert math.copysign(1.0, tab[code]) == math.copysign(1.0, val)
+
+
+def test_decode_table_structure():
+    tab = orc.e4m3fn_decode_table()
+    pos = tab[:0x7F]
+    assert np.all(np.diff(pos) > 0)                       # strictly increasing with the code
+    assert np.count_nonzero(np.isnan(tab)) == 2
+    assert not np.any(np.isinf(tab))
+    np.testing.assert_array_equal(tab[0x80:0xFF], -tab[0x00:0x7F])
+    # every binade [2^e, 2^(e+1)) for e=-6..8 holds 8 equally spaced values (7 in the top one)
+    for e in range(-6, 9):
+        inb = pos[(pos >= 2.0 ** e) & (pos < 2.0 ** (e + 1))]
+        assert len(inb) == (7 if e == 8 else 8)
+        np.testing.assert_array_equal(np.diff(inb), 2.0 ** (e - 3))
+    # subnormals are multiples of 2^-9
+    np.testing.assert_array_equal(pos[:8], np.arange(8) * 2.0 ** -9)
+
+
+def test_decode_against_torch():
+    codes = np.arange(256, dtype=np.uint8)
+    t = torch.from_numpy(codes.copy()).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    np.testing.assert_array_equal(orc.e4m3fn_decode(codes), t)   # NaN positions equal too
+
+
+def test_encode_inverts_decode():
+    codes = np.array([c for c in range(256) if c not in (0x7F, 0xFF)], dtype=np.uint8)
+    vals = orc.e4m3fn_decode(codes).astype(np.float32)
+    np.testing.assert_array_equal(orc.e4m3fn_encode(vals), codes)
+
+
+def _exact_nearest_even(x: float) -> int:
+    """Exact-rational nearest E4M3 magnitude code for 0 <= x <= 448, ties to even code."""
+    tab = orc.e4m3fn_decode_table()
+    fx = Fraction(x)
+    best, bestd = None, None
+    for c in range(0x7F):
+        dd = abs(Fraction(float(tab[c])) - fx)
+        if bestd is None or dd < bestd or (dd == bestd and c % 2 == 0 and best % 2 == 1):
+            best, bestd = c, dd
+    return best
+
+
+def test_encode_ties_and_neighbours_exact():
+    tab = orc.e4m3fn_decode_table()
+    xs = []
+    for c in range(0x7E):
+        mid = (tab[c] + tab[c + 1]) / 2            # exact in fp32: one extra mantissa bit
+        m32 = np.float32(mid)
+        assert float(m32) == mid
+        xs += [m32, np.nextafter(m32, np.float32(0)), np.nextafter(m32, np.float32(1e9))]
+    xs = np.array(xs, dtype=np.float32)
+    got = orc.e4m3fn_encode(xs)
+    exp = np.array([_exact_nearest_even(float(x)) for x in xs], dtype=np.uint8)
+    np.testing.assert_array_equal(got, exp)
+    np.testing.assert_array_equal(orc.e4m3fn_encode(-xs), exp | 0x80)
+
+
+def test_encode_saturation_and_specials():
+    f = np.float32
+    x = np.array([448, 448.0001, 463.9, 464, 464.1, 480, 1e6, 3e38, np.inf], dtype=f)
+    np.testing.assert_array_equal(orc.e4m3fn_encode(x), 0x7E)
+    np.testing.assert_array_equal(orc.e4m3fn_encode(-x), 0xFE)
+    assert orc.e4m3fn_encode(np.array([0.0], f))[0] == 0x00
+    assert orc.e4m3fn_encode(np.array([-0.0], f))[0] == 0x80
+    assert orc.e4m3fn_encode(np.array([np.nan], f))[0] & 0x7F == 0x7F
+    # below half the smallest subnormal -> 0 ; exactly half (2^-10) ties to even code 0
+    assert orc.e4m3fn_encode(np.array([2.0 ** -10], f))[0] == 0x00
+    assert orc.e4m3fn_encode(np.array([np.nextafter(f(2.0 ** -10), f(1))], f))[0] == 0x01
+    assert orc.e4m3fn_encode(np.array([3 * 2.0 ** -10], f))[0] == 0x02     # tie 1.5 -> even 2
+
+
+def test_encode_against_torch_cast_inside_range():
+    rng = np.random.default_rng(7)
+    x = np.concatenate([
+        rng.standard_normal(200000).astype(np.float32) * 100,
+        (rng.standard_normal(100000) * 0.01).astype(np.float32),
+        np.exp2(rng.uniform(-12, 8.8, 100000)).astype(np.float32)])
+    x = x[np.abs(x) <= 448]
+    t = torch.from_numpy(x).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    np.testing.assert_array_equal(orc.e4m3fn_encode(x), t)
+
+
+# ---------------------------------------------------------------------------
+# per-row quantiser, Algorithm 1
+# ---------------------------------------------------------------------------
+def test_quant_invariants_tiny_payload():
+    x = wlmod.make_payload(wlmod.WORKLOADS["tiny"])
+    codes, s = orc.fp8_quant(x)
+    assert codes.shape == x.shape and codes.dtype == np.uint8
+    assert s.shape == (x.shape[0],) and s.dtype == np.float32
+    assert codes.nbytes * 4 == x.nbytes                      # 1 byte per fp32 element
+    a = np.abs(x).max(1)
+    # the row's absmax element encodes to +-448 and scale*448 recovers absmax to 1 ulp
+    am = np.abs(x).argmax(1)
+    top = codes[np.arange(x.shape[0]), am] & 0x7F
+    np.testing.assert_array_equal(top, 0x7E)
+    assert np.all(np.abs(s.astype(np.float64) * 448 - a) <= np.spacing(a))
+    # sign bits follow the input
+    np.testing.assert_array_equal((codes >> 7).astype(bool), np.signbit(x))
+
+
+def test_quant_scale_is_fp32_division():
+    x = wlmod.make_matrix(11, 64, 40, "f32", "wide")
+    _, s = orc.fp8_quant(x)
+    a = np.abs(x).max(1).astype(np.float64)
+    exact = [Fraction(float(v)) / 448 for v in a]
+    for sv, ex in zip(s, exact):
+        # correctly rounded: no other fp32 is closer to the exact quotient
+        lo, hi = np.nextafter(sv, np.float32(0)), np.nextafter(sv, np.float32(np.inf))
+        err = abs(Fraction(float(sv)) - ex)
+        assert err <= abs(Fraction(float(lo)) - ex) and err <= abs(Fraction(float(hi)) - ex)
+
+
+def test_quant_codes_equal_exact_double_rounding():
+    """codes == RNE8(RNE32(x / s)) with the inner quotient taken in exact rationals."""
+    x = wlmod.make_matrix(12, 8, 24, "bf16", "wide")
+    codes, s = orc.fp8_quant(x)
+    for r in range(x.shape[0]):
+        for c in range(x.shape[1]):
+            quo = Fraction(float(x[r, c])) / Fraction(float(s[r]))
+            t = np.float32(float(quo))          # float(Fraction) rounds correctly to fp64; fp64->fp32
+            # guard double rounding fp64->fp32: recheck nearest fp32 against the rational
+            for cand in (np.nextafter(t, np.float32(-np.inf)), np.nextafter(t, np.float32(np.inf))):
+                if abs(Fraction(float(cand)) - quo) < abs(Fraction(float(t)) - quo):
+                    t = cand
+            mag = min(abs(float(t)), 448.0)
+            exp = _exact_nearest_even(mag) | (0x80 if x[r, c] < 0 or
+                                              (x[r, c] == 0 and math.copysign(1, x[r, c]) < 0) else 0)
+            assert codes[r, c] == exp
+
+
+def test_roundtrip_error_bounds_and_aggregates():
+    x = wlmod.make_payload(wlmod.WORKLOADS["tiny"])
+    codes, s = orc.fp8_quant(x)
+    y = orc.fp8_dequant(codes, s).astype(np.float64)
+    xd = x.astype(np.float64)
+    t = np.abs(xd) / s[:, None]
+    err = np.abs(y - xd)
+    normal = t >= 2.0 ** -6
+    # provable: relative 2^-4 in the normal range (+ fp32 slop), absolute 2^-10 * s below it
+    assert np.all(err[normal] <= (2.0 ** -4 + 1e-6) * np.abs(xd[normal]))
+    sub = ~normal
+    assert np.all(err[sub] <= (2.0 ** -10 + 1e-9) * np.broadcast_to(s[:, None], x.shape)[sub])
+    # aggregate readings of the paper's "<0.1%" figure
+    assert abs(np.linalg.norm(y) - np.linalg.norm(xd)) / np.linalg.norm(xd) < 1e-3
+    assert abs(np.mean(y - xd)) / np.mean(np.abs(xd)) < 1e-3
+    # honest rel-L2 of e4m3 on N(0,1) rows is a few percent, not 0.1%
+    rel = np.linalg.norm(y - xd) / np.linalg.norm(xd)
+    assert 0.01 < rel < 0.04
+
+
+def test_quant_idempotent_on_its_own_output():
+    x = wlmod.make_matrix(13, 32, 128, "bf16")
+    c1, s1 = orc.fp8_quant(x)
+    y = orc.fp8_dequant(c1, s1)
+    c2, s2 = orc.fp8_quant(y)
+    np.testing.assert_array_equal(c1, c2)
+    np.testing.assert_array_equal(s1, s2)
+
+
+def test_zero_rows_and_negative_zero():
+    x = wlmod.make_matrix(14, 9, 16, "f32", "zero_rows")
+    x[0, 3] = -0.0
+    codes, s = orc.fp8_quant(x)
+    assert np.all(s[::3] == 1.0)
+    assert codes[0, 3] == 0x80 and np.all(np.delete(codes[0], 3) == 0)
+    y = orc.fp8_dequant(codes, s)
+    assert np.all(y[::3] == 0)
+    e, sc = orc.fp8_quant(np.zeros((4, 0), np.float32))
+    assert e.shape == (4, 0) and np.all(sc == 1)
+
+
+def test_per_tensor_is_the_one_row_case():
+    x = wlmod.make_matrix(15, 6, 10, "bf16")
+    c_row, s_row = orc.fp8_quant(x.reshape(1, -1))
+    a = np.float32(np.abs(x).max())
+    assert s_row[0] == np.float32(a / np.float32(448))
+    assert (c_row & 0x7F).max() == 0x7E
+
+
+def test_dequant_bf16_rounding_is_nearest_even():
+    f = np.float32
+    # bf16 keeps 8 significant bits: 1 + 2^-8 is a tie between 1 and 1+2^-7 -> even (1.0)
+    y = np.array([1 + 2.0 ** -8, 1 + 3 * 2.0 ** -8, 1 + 2.0 ** -8 + 2.0 ** -20, -1 - 2.0 ** -8], f)
+    b = orc.round_to_bf16(y)
+    back = orc.bf16_bits_to_f64(b)
+    np.testing.assert_array_equal(back, [1.0, 1 + 2.0 ** -6, 1 + 2.0 ** -7, -1.0])
+    # against torch's own fp32->bf16 cast on many values
+    rng = np.random.default_rng(8)
+    z = (rng.standard_normal(100000) * np.exp2(rng.integers(-30, 30, 100000))).astype(f)
+    tb = torch.from_numpy(z).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    np.testing.assert_array_equal(orc.round_to_bf16(z), tb)
+
+
+def test_dequant_values():
+    codes = np.array([[0x38, 0xB8, 0x7E, 0x01]], np.uint8)     # 1, -1, 448, 2^-9
+    y = orc.fp8_dequant(codes, np.array([0.5], np.float32))
+    np.testing.assert_array_equal(y, [[0.5, -0.5, 224.0, 2.0 ** -10]])
+    ex = orc.dequant_exact_f64(codes, np.array([0.1], np.float32))
+    np.testing.assert_array_equal(ex, orc.e4m3fn_decode(codes) * np.float64(np.float32(0.1)))
