@@ -1,0 +1,158 @@
+/*
+ * usp.h - C ABI of the MI355X (gfx950) hot path of Unified Sequence Parallel
+ * attention: one rank's blockwise ring attention with log-sum-exp merging, and
+ * the FP8 (E4M3) pack/unpack of the All-to-All and ring payloads.
+ *
+ * Paper: FastUSP (arXiv 2602.10940).  Each entry point names the passage that
+ * defines what it computes.
+ *
+ * Conventions for every call
+ *   - All data pointers are DEVICE pointers unless a parameter says "host".
+ *   - `stream` parameters are hipStream_t values passed as void* (NULL = the
+ *     default stream).  Calls only enqueue work; results are valid once the
+ *     compute stream has completed.  The host never blocks inside a call.
+ *   - The caller owns every buffer.  The library allocates no device memory
+ *     and frees nothing; it keeps a small pool of HIP events per process.
+ *   - Return value is a usp_status; on failure nothing has been enqueued
+ *     unless the status is USP_ERR_HIP (a launch or event call failed midway).
+ *     usp_last_error() gives a thread-local message for the last failure.
+ *   - Inputs are assumed finite; NaN/Inf inputs are not checked.
+ *   - Calls on different streams may run concurrently, except that two
+ *     usp_ring_attn_fwd calls sharing a workspace must not overlap.
+ */
+#ifndef USP_H
+#define USP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  USP_OK = 0,
+  USP_ERR_INVALID_ARG = -1, /* null pointer, bad size, misaligned pointer or stride */
+  USP_ERR_UNSUPPORTED = -2, /* a combination this build has no kernel for */
+  USP_ERR_WORKSPACE = -3,   /* workspace missing or smaller than required */
+  USP_ERR_HIP = -4          /* a HIP runtime call failed */
+} usp_status;
+
+typedef enum {
+  USP_F32 = 0,
+  USP_BF16 = 1,
+  USP_FP8_E4M3FN = 2 /* 1 byte per element; only valid as kv_dtype */
+} usp_dtype;
+
+/* usp_attn_desc.flags */
+#define USP_ATTN_DOUBLE_BUFFER 1u /* stage chunks 1..W-1 through two internal buffers on copy_stream */
+#define USP_ATTN_UNFUSED_MERGE 2u /* per-chunk (O_i, lse_i) then usp_lse_merge, as Algorithm 2 is written;
+                                     default folds the merge into the attention kernel's epilogue */
+
+/*
+ * Shape of one ring-attention call (paper section 2.2: Q, K, V are [B, H, S, D]).
+ * Strides are in ELEMENTS for the (B, H, token) axes; the head dimension d is
+ * always contiguous (stride 1).  Every KV chunk shares kv_stride; chunk r holds
+ * chunk_len[r] tokens.  kv_stride = {0,0,0} means "each chunk is a dense
+ * [B,H,chunk_len[r],d] array" (the only way to describe dense chunks of unequal length).
+ */
+typedef struct usp_attn_desc {
+  int32_t B, H, d;          /* d: 64 or 128 for bf16 (MFMA path), any multiple of 4 up to 256 for f32 */
+  int32_t Sq;               /* tokens of the local Q shard */
+  int32_t n_chunks;         /* ring degree W >= 1 */
+  const int32_t* chunk_len; /* HOST array [n_chunks] */
+  int32_t qo_dtype;         /* usp_dtype of q and out: USP_BF16 or USP_F32 */
+  int32_t kv_dtype;         /* USP_BF16 / USP_F32 (must equal qo_dtype) or USP_FP8_E4M3FN (with qo BF16) */
+  int64_t q_stride[3];      /* elements, (B, H, token) */
+  int64_t kv_stride[3];
+  int64_t o_stride[3];
+  float softmax_scale;      /* multiplies q.k; 0 selects 1/sqrt(d) */
+  uint32_t flags;           /* USP_ATTN_* */
+} usp_attn_desc;
+
+/*
+ * Bytes of device workspace usp_ring_attn_fwd needs for this descriptor
+ * (0 is possible: one bf16/f32 chunk, no staging).  Returns (size_t)-1 if the
+ * descriptor is invalid.
+ */
+size_t usp_ring_attn_workspace_bytes(const usp_attn_desc* desc);
+
+/*
+ * Ring attention of the local Q shard over W KV chunks (section 2.2.2 and
+ * Algorithm 2, "Pipelined Ring Attention"): for every chunk r in order,
+ *   O_r, lse_r = attn(Q, K_r, V_r)          softmax(Q K_r^T * scale) V_r, lse_r = log sum exp
+ *   O, lse     = merge(O, lse, O_r, lse_r)  the two merge equations of section 3.4
+ * so that the result equals full attention over the concatenated keys.
+ *
+ *   q          [B,H,Sq,d] by q_stride, dtype qo_dtype
+ *   k_chunks   HOST array of n_chunks device pointers; chunk r is [B,H,chunk_len[r],d]
+ *              by kv_stride, dtype kv_dtype.  With FP8 the bytes are dense E4M3 codes.
+ *   v_chunks   same for V
+ *   k_scales / v_scales   NULL unless kv_dtype is FP8: HOST arrays of device pointers,
+ *              chunk r -> float [B,H,chunk_len[r]] dense, one scale per (b,h,token)
+ *              (value = code * scale, as produced by usp_fp8_quant on the
+ *              [B*H*chunk_len, d] view when the chunk is dense)
+ *   key_mask   NULL, or HOST array of n_chunks device pointers (entries may be NULL):
+ *              uint8 [B,chunk_len[r]], nonzero = key takes part.  A query whose keys
+ *              are all masked gets O = 0, lse = -inf.
+ *   out        [B,H,Sq,d] by o_stride, dtype qo_dtype
+ *   lse        float [B,H,Sq] dense, natural log
+ *   workspace  device memory, >= usp_ring_attn_workspace_bytes(desc), 256-byte aligned
+ *   compute_stream   all kernels run here
+ *   copy_stream      used only with USP_ATTN_DOUBLE_BUFFER: chunk r+1 is copied into an
+ *              internal buffer here while chunk r is computed (the one-GPU stand-in for
+ *              the ring's recv; Algorithm 2 lines 3, 6, 7).  Must differ from compute_stream.
+ * Pointers must be 16-byte aligned, strides multiples of 8 elements (bf16) / 4 (f32).
+ */
+usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q,
+                             const void* const* k_chunks, const void* const* v_chunks,
+                             const float* const* k_scales, const float* const* v_scales,
+                             const uint8_t* const* key_mask,
+                             void* out, float* lse,
+                             void* workspace, size_t workspace_bytes,
+                             void* compute_stream, void* copy_stream);
+
+/*
+ * Merge two partial attention results (section 3.4, the two equations under
+ * Algorithm 2; same as the pair in section 2.2.2):
+ *   lse = log(exp(lse1) + exp(lse2))
+ *   O   = exp(lse1 - lse) * O1 + exp(lse2 - lse) * O2
+ * o1, o2, o_out: [rows, d] dense, dtype dt (USP_BF16 or USP_F32); lse*: float [rows].
+ * o_out may alias o1 or o2, lse_out may alias lse1 or lse2.  lse = -inf on both
+ * sides gives lse = -inf, O = 0.  d must be a multiple of 8.
+ */
+usp_status usp_lse_merge(int64_t rows, int32_t d, int32_t dt,
+                         const void* o1, const float* lse1,
+                         const void* o2, const float* lse2,
+                         void* o_out, float* lse_out, void* stream);
+
+/*
+ * FP8 pack (Algorithm 1 lines 1-2, "FP8 Quantized All-to-All"), one scale per
+ * row of the [rows, cols] view (per token; rows = 1 is the per-tensor scale of
+ * the algorithm as printed):
+ *   a = max_c |x[r,c]|;  s[r] = a / 448 (IEEE float32; a zero quotient is replaced by 1)
+ *   q[r,c] = e4m3( x[r,c] / s[r] )   true float32 division, round to nearest even,
+ *                                    saturating at +-448, sign of zero kept
+ * x: [rows, cols] dense row-major, in_dt USP_BF16 or USP_F32; q: uint8 [rows, cols];
+ * scales: float [rows].  cols must be a multiple of 8; rows or cols may be 0.
+ */
+usp_status usp_fp8_quant(int64_t rows, int64_t cols, int32_t in_dt, const void* x,
+                         uint8_t* q, float* scales, void* stream);
+
+/*
+ * FP8 unpack (Algorithm 1 line 4):  y[r,c] = float32(decode(q[r,c])) * scales[r],
+ * stored as out_dt (USP_F32, or USP_BF16 rounded to nearest even).
+ */
+usp_status usp_fp8_dequant(int64_t rows, int64_t cols, int32_t out_dt, const uint8_t* q,
+                           const float* scales, void* y, void* stream);
+
+/* Thread-local, statically stored description of the last failure ("" if none). */
+const char* usp_last_error(void);
+
+/* Library version string, e.g. "usp-gfx950 0.1". */
+const char* usp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* USP_H */

@@ -1,0 +1,237 @@
+// FP8 (E4M3, OCP "fn": max 448, no infinities) pack / unpack of the All-to-All and ring
+// payloads: FastUSP Algorithm 1 lines 1-2 (quantise) and line 4 (dequantise), with one
+// scale per row of the [rows, cols] view.
+//
+// Both kernels are single streaming passes: the quantiser keeps a row in registers
+// between the absmax reduction and the cast, so every input byte is read from HBM
+// once.  All HBM accesses are 16-byte (or 8-byte) vectors, consecutive lanes touching
+// consecutive addresses.
+#include "usp_common.h"
+
+namespace usp {
+namespace {
+
+constexpr float kFp8Max = 448.0f;
+
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+// ---- loads of 8 consecutive elements as fp32 --------------------------------------------
+__device__ __forceinline__ void load8(const bf16_t* p, float (&v)[8]) {
+  uint4 r = *reinterpret_cast<const uint4*>(p);
+  v[0] = __uint_as_float(r.x << 16); v[1] = __uint_as_float(r.x & 0xffff0000u);
+  v[2] = __uint_as_float(r.y << 16); v[3] = __uint_as_float(r.y & 0xffff0000u);
+  v[4] = __uint_as_float(r.z << 16); v[5] = __uint_as_float(r.z & 0xffff0000u);
+  v[6] = __uint_as_float(r.w << 16); v[7] = __uint_as_float(r.w & 0xffff0000u);
+}
+__device__ __forceinline__ void load8(const float* p, float (&v)[8]) {
+  float4 a = *reinterpret_cast<const float4*>(p);
+  float4 b = *reinterpret_cast<const float4*>(p + 4);
+  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+  v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+
+// E4M3 code of t (round to nearest even, saturating): the hardware convert after a clamp
+// to the finite range, so an out-of-range quotient never turns into the NaN code.
+__device__ __forceinline__ uint2 encode8(const float (&v)[8], float s) {
+  float t[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    float quo = v[i] / s;  // IEEE-correct fp32 division (compiled without fast-math)
+    t[i] = __builtin_amdgcn_fmed3f(quo, -kFp8Max, kFp8Max);
+  }
+  int lo = __builtin_amdgcn_cvt_pk_fp8_f32(t[0], t[1], 0, false);
+  lo = __builtin_amdgcn_cvt_pk_fp8_f32(t[2], t[3], lo, true);
+  int hi = __builtin_amdgcn_cvt_pk_fp8_f32(t[4], t[5], 0, false);
+  hi = __builtin_amdgcn_cvt_pk_fp8_f32(t[6], t[7], hi, true);
+  return make_uint2((uint32_t)lo, (uint32_t)hi);
+}
+
+__device__ __forceinline__ float absmax8(const float (&v)[8], float a) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i) a = fmaxf(a, fabsf(v[i]));
+  return a;
+}
+
+__device__ __forceinline__ float scale_from_absmax(float a) {
+  float s = a / kFp8Max;
+  return s == 0.0f ? 1.0f : s;
+}
+
+// ---- rows that fit one wave: LPR lanes per row, up to NV 8-element units per lane ---------
+template <typename T, int LPR, int NV>
+__global__ __launch_bounds__(256) void fp8_quant_rows_kernel(const T* __restrict__ x,
+                                                             uint8_t* __restrict__ q,
+                                                             float* __restrict__ scales,
+                                                             int64_t rows, int units) {
+  constexpr int RPW = 64 / LPR;
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int64_t row = ((int64_t)blockIdx.x * 4 + wave) * RPW + lane / LPR;
+  const int l = lane % LPR;
+  const bool row_ok = row < rows;
+  const int64_t base = row * (int64_t)units * 8;
+
+  float v[NV][8];
+  float a = 0.0f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int u = l + i * LPR;
+    if (row_ok && u < units) {
+      load8(x + base + (int64_t)u * 8, v[i]);
+      a = absmax8(v[i], a);
+    }
+  }
+#pragma unroll
+  for (int off = LPR / 2; off > 0; off >>= 1) a = fmaxf(a, __shfl_xor(a, off, 64));
+  const float s = scale_from_absmax(a);
+  if (row_ok && l == 0) scales[row] = s;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int u = l + i * LPR;
+    if (row_ok && u < units) *reinterpret_cast<uint2*>(q + base + (int64_t)u * 8) = encode8(v[i], s);
+  }
+}
+
+// ---- long rows: one 256-thread block per row, two passes over the row ----------------------
+template <typename T>
+__global__ __launch_bounds__(256) void fp8_quant_longrow_kernel(const T* __restrict__ x,
+                                                                uint8_t* __restrict__ q,
+                                                                float* __restrict__ scales,
+                                                                int64_t units) {
+  __shared__ float red[4];
+  const int64_t row = blockIdx.x;
+  const int64_t base = row * units * 8;
+  float a = 0.0f;
+  for (int64_t u = threadIdx.x; u < units; u += 256) {
+    float v[8];
+    load8(x + base + u * 8, v);
+    a = absmax8(v, a);
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) a = fmaxf(a, __shfl_xor(a, off, 64));
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = a;
+  __syncthreads();
+  a = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  const float s = scale_from_absmax(a);
+  if (threadIdx.x == 0) scales[row] = s;
+  for (int64_t u = threadIdx.x; u < units; u += 256) {
+    float v[8];
+    load8(x + base + u * 8, v);
+    *reinterpret_cast<uint2*>(q + base + u * 8) = encode8(v, s);
+  }
+}
+
+// all-zero-column case: scales still have to be defined
+__global__ void fp8_fill_scales_kernel(float* scales, int64_t rows) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < rows) scales[i] = 1.0f;
+}
+
+// ---- dequantise: VEC codes per thread -----------------------------------------------------
+__device__ __forceinline__ void decode4(uint32_t w, float s, float (&o)[4]) {
+  f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, false);
+  f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, true);
+  o[0] = lo.x * s; o[1] = lo.y * s; o[2] = hi.x * s; o[3] = hi.y * s;
+}
+
+__device__ __forceinline__ void store4(float* y, const float (&o)[4]) {
+  *reinterpret_cast<float4*>(y) = make_float4(o[0], o[1], o[2], o[3]);
+}
+__device__ __forceinline__ void store4(bf16_t* y, const float (&o)[4]) {
+  *reinterpret_cast<uint2*>(y) = make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
+}
+__device__ __forceinline__ void store8(float* y, const float (&a)[4], const float (&b)[4]) {
+  store4(y, a);
+  store4(y + 4, b);
+}
+__device__ __forceinline__ void store8(bf16_t* y, const float (&a)[4], const float (&b)[4]) {
+  *reinterpret_cast<uint4*>(y) = make_uint4(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]),
+                                            pack_bf16x2(b[0], b[1]), pack_bf16x2(b[2], b[3]));
+}
+
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void fp8_dequant_kernel(const uint8_t* __restrict__ q,
+                                                          const float* __restrict__ scales,
+                                                          T* __restrict__ y, int64_t total_units,
+                                                          uint32_t units_per_row) {
+  const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (g >= total_units) return;
+  const int64_t row = g / units_per_row;
+  const float s = scales ? scales[row] : 1.0f;   // no scales: exact widening of the codes
+  const int64_t e = g * VEC;
+  if constexpr (VEC == 16) {
+    uint4 w = *reinterpret_cast<const uint4*>(q + e);
+    float a[4], b[4];
+    decode4(w.x, s, a); decode4(w.y, s, b); store8(y + e, a, b);
+    decode4(w.z, s, a); decode4(w.w, s, b); store8(y + e + 8, a, b);
+  } else {
+    uint2 w = *reinterpret_cast<const uint2*>(q + e);
+    float a[4], b[4];
+    decode4(w.x, s, a); decode4(w.y, s, b); store8(y + e, a, b);
+  }
+}
+
+template <typename T>
+usp_status quant_dispatch(int64_t rows, int64_t cols, const T* x, uint8_t* q, float* scales,
+                          hipStream_t st) {
+  const int64_t units = cols / 8;
+  auto blocks = [&](int rpw) { return (unsigned)((rows + 4 * rpw - 1) / (4 * rpw)); };
+  if (units <= 16) {
+    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 16, 1>), dim3(blocks(4)), dim3(256), 0, st, x, q, scales, rows, (int)units);
+  } else if (units <= 32) {
+    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 16, 2>), dim3(blocks(4)), dim3(256), 0, st, x, q, scales, rows, (int)units);
+  } else if (units <= 64) {
+    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 64, 1>), dim3(blocks(1)), dim3(256), 0, st, x, q, scales, rows, (int)units);
+  } else if (units <= 128) {
+    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 64, 2>), dim3(blocks(1)), dim3(256), 0, st, x, q, scales, rows, (int)units);
+  } else if (units <= 256) {
+    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 64, 4>), dim3(blocks(1)), dim3(256), 0, st, x, q, scales, rows, (int)units);
+  } else if (units <= 384) {
+    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 64, 6>), dim3(blocks(1)), dim3(256), 0, st, x, q, scales, rows, (int)units);
+  } else if (units <= 512) {
+    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 64, 8>), dim3(blocks(1)), dim3(256), 0, st, x, q, scales, rows, (int)units);
+  } else {
+    hipLaunchKernelGGL((fp8_quant_longrow_kernel<T>), dim3((unsigned)rows), dim3(256), 0, st, x, q, scales, units);
+  }
+  USP_CHECK_HIP(hipGetLastError());
+  return USP_OK;
+}
+
+template <typename T>
+usp_status dequant_dispatch(int64_t rows, int64_t cols, const uint8_t* q, const float* scales, T* y,
+                            hipStream_t st) {
+  if (cols % 16 == 0) {
+    const int64_t upr = cols / 16, total = rows * upr;
+    hipLaunchKernelGGL((fp8_dequant_kernel<T, 16>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                       q, scales, y, total, (uint32_t)upr);
+  } else {
+    const int64_t upr = cols / 8, total = rows * upr;
+    hipLaunchKernelGGL((fp8_dequant_kernel<T, 8>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                       q, scales, y, total, (uint32_t)upr);
+  }
+  USP_CHECK_HIP(hipGetLastError());
+  return USP_OK;
+}
+
+}  // namespace
+
+usp_status launch_fp8_quant(int64_t rows, int64_t cols, int in_dt, const void* x, uint8_t* q,
+                            float* scales, hipStream_t st) {
+  if (rows == 0) return USP_OK;
+  if (cols == 0) {
+    hipLaunchKernelGGL(fp8_fill_scales_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, st, scales, rows);
+    USP_CHECK_HIP(hipGetLastError());
+    return USP_OK;
+  }
+  if (in_dt == USP_BF16) return quant_dispatch<bf16_t>(rows, cols, (const bf16_t*)x, q, scales, st);
+  return quant_dispatch<float>(rows, cols, (const float*)x, q, scales, st);
+}
+
+usp_status launch_fp8_dequant(int64_t rows, int64_t cols, int out_dt, const uint8_t* q,
+                              const float* scales, void* y, hipStream_t st) {
+  if (rows == 0 || cols == 0) return USP_OK;
+  if (out_dt == USP_BF16) return dequant_dispatch<bf16_t>(rows, cols, q, scales, (bf16_t*)y, st);
+  return dequant_dispatch<float>(rows, cols, q, scales, (float*)y, st);
+}
+
+}  // namespace usp

@@ -1,0 +1,336 @@
+// C ABI entry points: argument validation, workspace carving, and the stream / event
+// schedule of pipelined ring attention (FastUSP Algorithm 2).  No device memory is
+// allocated here and the host never blocks.
+#include <mutex>
+#include <vector>
+#include <math.h>
+#include <string.h>
+
+#include "usp_common.h"
+
+namespace usp {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+void clear_error() { g_err[0] = 0; }
+
+namespace {
+
+size_t elt_size(int dt) { return dt == USP_F32 ? 4 : dt == USP_BF16 ? 2 : 1; }
+size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+// Per-thread, per-device pool of timing-free events used to order the two streams.
+struct EventPool {
+  int device = -1;
+  std::vector<hipEvent_t> ev;
+  size_t next = 0;
+  hipError_t get(hipEvent_t* out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev != device) { ev.clear(); next = 0; device = dev; }  // events of another device are abandoned
+    if (ev.size() < 64) {
+      hipEvent_t x;
+      e = hipEventCreateWithFlags(&x, hipEventDisableTiming);
+      if (e != hipSuccess) return e;
+      ev.push_back(x);
+      *out = x;
+      return hipSuccess;
+    }
+    *out = ev[next++ % ev.size()];
+    return hipSuccess;
+  }
+};
+thread_local EventPool g_events;
+
+struct Plan {
+  bool valid = false;
+  int W = 0;
+  int max_len = 0;
+  bool fp8 = false, dbuf = false, unfused = false, mfma = false, dequant_stage = false;
+  size_t rows_q = 0;          // B*H*Sq
+  size_t off_acc = 0;         // fp32 carried O            (fused, W > 1)
+  size_t off_tmp_o = 0;       // per-chunk O_i             (unfused, W > 1)
+  size_t off_tmp_lse = 0;     // per-chunk lse_i           (unfused, W > 1)
+  size_t off_buf[2] = {0, 0}; // staged chunk: K | V | k_scale | v_scale
+  size_t buf_k = 0, buf_v = 0, buf_ks = 0, buf_vs = 0;  // offsets inside a staging buffer
+  size_t off_deq_k = 0, off_deq_v = 0;  // bf16 K/V after dequantisation (FP8 + MFMA kernel)
+  size_t total = 0;
+};
+
+bool kv_auto(const usp_attn_desc* d) {  // all-zero kv_stride: every chunk is dense for its own length
+  return d->kv_stride[0] == 0 && d->kv_stride[1] == 0 && d->kv_stride[2] == 0;
+}
+bool kv_dense(const usp_attn_desc* d, int len) {
+  if (kv_auto(d)) return true;
+  return d->kv_stride[2] == d->d && d->kv_stride[1] == (int64_t)len * d->d &&
+         d->kv_stride[0] == (int64_t)d->H * len * d->d;
+}
+bool o_dense(const usp_attn_desc* d) {
+  return d->o_stride[2] == d->d && d->o_stride[1] == (int64_t)d->Sq * d->d &&
+         d->o_stride[0] == (int64_t)d->H * d->Sq * d->d;
+}
+
+usp_status make_plan(const usp_attn_desc* d, Plan* p) {
+  USP_CHECK_ARG(d != nullptr, "desc is NULL");
+  USP_CHECK_ARG(d->B > 0 && d->H > 0 && d->Sq > 0, "B, H, Sq must be positive (B=%d H=%d Sq=%d)", d->B, d->H, d->Sq);
+  USP_CHECK_ARG(d->d > 0 && d->d % 8 == 0 && d->d <= 256, "d must be a multiple of 8 in [8, 256] (got %d)", d->d);
+  USP_CHECK_ARG(d->n_chunks >= 1 && d->chunk_len != nullptr, "n_chunks must be >= 1 with chunk_len set");
+  USP_CHECK_ARG(d->qo_dtype == USP_F32 || d->qo_dtype == USP_BF16, "qo_dtype must be USP_F32 or USP_BF16");
+  USP_CHECK_ARG(d->kv_dtype == d->qo_dtype || d->kv_dtype == USP_FP8_E4M3FN,
+                "kv_dtype must equal qo_dtype or be USP_FP8_E4M3FN");
+  USP_CHECK_ARG(d->softmax_scale >= 0.0f && isfinite(d->softmax_scale), "softmax_scale must be finite and >= 0");
+  const int64_t al = d->qo_dtype == USP_F32 ? 4 : 8;
+  for (int i = 0; i < 3; ++i) {
+    USP_CHECK_ARG(d->q_stride[i] >= 0 && d->q_stride[i] % al == 0, "q_stride[%d]=%lld must be a non-negative multiple of %lld", i, (long long)d->q_stride[i], (long long)al);
+    USP_CHECK_ARG(d->o_stride[i] >= 0 && d->o_stride[i] % al == 0, "o_stride[%d]=%lld must be a non-negative multiple of %lld", i, (long long)d->o_stride[i], (long long)al);
+    const int64_t kal = d->kv_dtype == USP_F32 ? 4 : d->kv_dtype == USP_BF16 ? 8 : 16;
+    USP_CHECK_ARG(d->kv_stride[i] >= 0 && d->kv_stride[i] % kal == 0, "kv_stride[%d]=%lld must be a non-negative multiple of %lld", i, (long long)d->kv_stride[i], (long long)kal);
+  }
+  USP_CHECK_ARG(d->q_stride[2] >= d->d && d->o_stride[2] >= d->d && (kv_auto(d) || d->kv_stride[2] >= d->d),
+                "token strides must be >= d");
+  p->W = d->n_chunks;
+  p->max_len = 0;
+  for (int r = 0; r < p->W; ++r) {
+    USP_CHECK_ARG(d->chunk_len[r] >= 0, "chunk_len[%d]=%d is negative", r, d->chunk_len[r]);
+    if (d->chunk_len[r] > p->max_len) p->max_len = d->chunk_len[r];
+  }
+  p->fp8 = d->kv_dtype == USP_FP8_E4M3FN;
+  p->dbuf = (d->flags & USP_ATTN_DOUBLE_BUFFER) != 0 && p->W > 1;
+  p->unfused = (d->flags & USP_ATTN_UNFUSED_MERGE) != 0 && p->W > 1;
+  p->mfma = d->qo_dtype == USP_BF16 && d->d == 128;
+  p->dequant_stage = p->fp8 && p->mfma;
+  if (p->fp8 || p->dbuf) {
+    for (int r = 0; r < p->W; ++r)
+      if (d->chunk_len[r] > 0 && !kv_dense(d, d->chunk_len[r])) {
+        set_error("FP8 K/V and USP_ATTN_DOUBLE_BUFFER need dense [B,H,chunk_len,d] chunks (chunk %d is strided)", r);
+        return USP_ERR_UNSUPPORTED;
+      }
+  }
+  if (p->unfused && !o_dense(d)) {
+    set_error("USP_ATTN_UNFUSED_MERGE needs a dense [B,H,Sq,d] out");
+    return USP_ERR_UNSUPPORTED;
+  }
+  p->rows_q = (size_t)d->B * d->H * d->Sq;
+  size_t off = 0;
+  if (p->W > 1 && !p->unfused) { p->off_acc = off; off += align_up(p->rows_q * d->d * 4); }
+  if (p->unfused) {
+    p->off_tmp_o = off; off += align_up(p->rows_q * d->d * elt_size(d->qo_dtype));
+    p->off_tmp_lse = off; off += align_up(p->rows_q * 4);
+  }
+  const size_t chunk_elems = (size_t)d->B * d->H * p->max_len * d->d;
+  const size_t chunk_tok = (size_t)d->B * d->H * p->max_len;
+  if (p->dbuf) {
+    size_t b = 0;
+    p->buf_k = b; b += align_up(chunk_elems * elt_size(d->kv_dtype));
+    p->buf_v = b; b += align_up(chunk_elems * elt_size(d->kv_dtype));
+    if (p->fp8) {
+      p->buf_ks = b; b += align_up(chunk_tok * 4);
+      p->buf_vs = b; b += align_up(chunk_tok * 4);
+    }
+    p->off_buf[0] = off; off += b;
+    p->off_buf[1] = off; off += b;
+  }
+  if (p->dequant_stage) {
+    p->off_deq_k = off; off += align_up(chunk_elems * 2);
+    p->off_deq_v = off; off += align_up(chunk_elems * 2);
+  }
+  p->total = off;
+  p->valid = true;
+  return USP_OK;
+}
+
+}  // namespace
+}  // namespace usp
+
+using namespace usp;
+
+extern "C" {
+
+const char* usp_last_error(void) { return g_err; }
+const char* usp_version(void) { return "usp-gfx950 0.1"; }
+
+size_t usp_ring_attn_workspace_bytes(const usp_attn_desc* desc) {
+  Plan p;
+  if (make_plan(desc, &p) != USP_OK) return (size_t)-1;
+  return p.total;
+}
+
+usp_status usp_fp8_quant(int64_t rows, int64_t cols, int32_t in_dt, const void* x, uint8_t* q,
+                         float* scales, void* stream) {
+  clear_error();
+  USP_CHECK_ARG(rows >= 0 && cols >= 0, "rows and cols must be >= 0");
+  USP_CHECK_ARG(in_dt == USP_F32 || in_dt == USP_BF16, "in_dt must be USP_F32 or USP_BF16");
+  USP_CHECK_ARG(cols % 8 == 0, "cols=%lld must be a multiple of 8", (long long)cols);
+  USP_CHECK_ARG(rows <= (int64_t)1 << 31, "rows=%lld too large", (long long)rows);
+  if (rows == 0) return USP_OK;
+  USP_CHECK_ARG(scales != nullptr, "scales is NULL");
+  if (cols > 0) {
+    USP_CHECK_ARG(x != nullptr && q != nullptr, "x or q is NULL");
+    USP_CHECK_ARG(aligned16(x) && aligned16(q), "x and q must be 16-byte aligned");
+  }
+  return launch_fp8_quant(rows, cols, in_dt, x, q, scales, (hipStream_t)stream);
+}
+
+usp_status usp_fp8_dequant(int64_t rows, int64_t cols, int32_t out_dt, const uint8_t* q,
+                           const float* scales, void* y, void* stream) {
+  clear_error();
+  USP_CHECK_ARG(rows >= 0 && cols >= 0, "rows and cols must be >= 0");
+  USP_CHECK_ARG(out_dt == USP_F32 || out_dt == USP_BF16, "out_dt must be USP_F32 or USP_BF16");
+  USP_CHECK_ARG(cols % 8 == 0, "cols=%lld must be a multiple of 8", (long long)cols);
+  if (rows == 0 || cols == 0) return USP_OK;
+  USP_CHECK_ARG(rows * (cols / 8) < ((int64_t)1 << 39), "tensor too large");
+  USP_CHECK_ARG(q != nullptr && scales != nullptr && y != nullptr, "q, scales or y is NULL");
+  USP_CHECK_ARG(aligned16(q) && aligned16(y), "q and y must be 16-byte aligned");
+  return launch_fp8_dequant(rows, cols, out_dt, q, scales, y, (hipStream_t)stream);
+}
+
+usp_status usp_lse_merge(int64_t rows, int32_t d, int32_t dt, const void* o1, const float* lse1,
+                         const void* o2, const float* lse2, void* o_out, float* lse_out, void* stream) {
+  clear_error();
+  USP_CHECK_ARG(rows >= 0, "rows must be >= 0");
+  USP_CHECK_ARG(d > 0 && d % 8 == 0 && d <= 512, "d must be a multiple of 8 in [8, 512] (got %d)", d);
+  USP_CHECK_ARG(dt == USP_F32 || dt == USP_BF16, "dt must be USP_F32 or USP_BF16");
+  USP_CHECK_ARG(rows <= (int64_t)1 << 31, "rows=%lld too large", (long long)rows);
+  if (rows == 0) return USP_OK;
+  USP_CHECK_ARG(o1 && o2 && o_out && lse1 && lse2 && lse_out, "a required pointer is NULL");
+  USP_CHECK_ARG(aligned16(o1) && aligned16(o2) && aligned16(o_out), "o1, o2 and o_out must be 16-byte aligned");
+  return launch_lse_merge(rows, d, dt, o1, lse1, o2, lse2, o_out, lse_out, (hipStream_t)stream);
+}
+
+usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const void* const* k_chunks,
+                             const void* const* v_chunks, const float* const* k_scales,
+                             const float* const* v_scales, const uint8_t* const* key_mask, void* out,
+                             float* lse, void* workspace, size_t workspace_bytes, void* compute_stream,
+                             void* copy_stream) {
+  clear_error();
+  Plan p;
+  usp_status st = make_plan(desc, &p);
+  if (st != USP_OK) return st;
+  USP_CHECK_ARG(q && out && lse && k_chunks && v_chunks, "q, out, lse, k_chunks or v_chunks is NULL");
+  USP_CHECK_ARG(aligned16(q) && aligned16(out), "q and out must be 16-byte aligned");
+  USP_CHECK_ARG(!p.fp8 || (k_scales && v_scales), "FP8 K/V needs k_scales and v_scales");
+  for (int r = 0; r < p.W; ++r) {
+    if (desc->chunk_len[r] == 0) continue;
+    USP_CHECK_ARG(k_chunks[r] && v_chunks[r], "K or V pointer of chunk %d is NULL", r);
+    USP_CHECK_ARG(aligned16(k_chunks[r]) && aligned16(v_chunks[r]), "K/V of chunk %d must be 16-byte aligned", r);
+    USP_CHECK_ARG(!p.fp8 || (k_scales[r] && v_scales[r]), "scale pointer of chunk %d is NULL", r);
+  }
+  if (p.total > 0) {
+    if (workspace == nullptr || workspace_bytes < p.total) {
+      set_error("workspace of %zu bytes needed, %zu given", p.total, workspace ? workspace_bytes : (size_t)0);
+      return USP_ERR_WORKSPACE;
+    }
+    USP_CHECK_ARG((reinterpret_cast<uintptr_t>(workspace) & 255u) == 0, "workspace must be 256-byte aligned");
+  }
+  hipStream_t cs = (hipStream_t)compute_stream, xs = (hipStream_t)copy_stream;
+  if (p.dbuf) USP_CHECK_ARG(xs != cs, "USP_ATTN_DOUBLE_BUFFER needs a copy_stream different from compute_stream");
+
+  char* ws = (char*)workspace;
+  const int d = desc->d;
+  const float scale = desc->softmax_scale > 0.0f ? desc->softmax_scale : 1.0f / sqrtf((float)d);
+  const size_t kv_es = elt_size(desc->kv_dtype);
+
+  // ---- Algorithm 2, lines 1-3: the first prefetch is issued before the local chunk is computed
+  std::vector<hipEvent_t> copied(p.W, nullptr), computed(p.W, nullptr);
+  auto stage_chunk = [&](int r) -> usp_status {  // "recv" chunk r (r >= 1) into buffer (r-1)%2 on xs
+    const int len = desc->chunk_len[r];
+    char* buf = ws + p.off_buf[(r - 1) & 1];
+    if (len > 0) {
+      const size_t bytes = (size_t)desc->B * desc->H * len * d * kv_es;
+      USP_CHECK_HIP(hipMemcpyAsync(buf + p.buf_k, k_chunks[r], bytes, hipMemcpyDeviceToDevice, xs));
+      USP_CHECK_HIP(hipMemcpyAsync(buf + p.buf_v, v_chunks[r], bytes, hipMemcpyDeviceToDevice, xs));
+      if (p.fp8) {
+        const size_t sb = (size_t)desc->B * desc->H * len * 4;
+        USP_CHECK_HIP(hipMemcpyAsync(buf + p.buf_ks, k_scales[r], sb, hipMemcpyDeviceToDevice, xs));
+        USP_CHECK_HIP(hipMemcpyAsync(buf + p.buf_vs, v_scales[r], sb, hipMemcpyDeviceToDevice, xs));
+      }
+    }
+    USP_CHECK_HIP(g_events.get(&copied[r]));
+    USP_CHECK_HIP(hipEventRecord(copied[r], xs));
+    return USP_OK;
+  };
+  if (p.dbuf) {
+    hipEvent_t entry;
+    USP_CHECK_HIP(g_events.get(&entry));
+    USP_CHECK_HIP(hipEventRecord(entry, cs));            // inputs were produced on the compute stream
+    USP_CHECK_HIP(hipStreamWaitEvent(xs, entry, 0));     // ... and earlier calls are done with the buffers
+    if ((st = stage_chunk(1)) != USP_OK) return st;
+  }
+
+  for (int r = 0; r < p.W; ++r) {
+    const int len = desc->chunk_len[r];
+    const void* kp = k_chunks[r];
+    const void* vp = v_chunks[r];
+    const float* ksp = p.fp8 ? k_scales[r] : nullptr;
+    const float* vsp = p.fp8 ? v_scales[r] : nullptr;
+    if (p.dbuf && r >= 1) {
+      // line 6: the chunk must have arrived; line 7: start the next transfer, which may only
+      // overwrite the other buffer once the step that read it (r-1) has finished.
+      USP_CHECK_HIP(hipStreamWaitEvent(cs, copied[r], 0));
+      if (r + 1 < p.W) {
+        if (r >= 2) USP_CHECK_HIP(hipStreamWaitEvent(xs, computed[r - 1], 0));
+        if ((st = stage_chunk(r + 1)) != USP_OK) return st;
+      }
+      char* buf = ws + p.off_buf[(r - 1) & 1];
+      kp = buf + p.buf_k;
+      vp = buf + p.buf_v;
+      if (p.fp8) { ksp = (const float*)(buf + p.buf_ks); vsp = (const float*)(buf + p.buf_vs); }
+    }
+
+    AttnStep a;
+    memset(&a, 0, sizeof(a));
+    a.B = desc->B; a.H = desc->H; a.d = d; a.Sq = desc->Sq; a.Sc = len;
+    a.qo_dtype = desc->qo_dtype; a.kv_dtype = desc->kv_dtype;
+    a.q = q; a.k = kp; a.v = vp; a.k_scale = ksp; a.v_scale = vsp;
+    a.key_mask = key_mask ? key_mask[r] : nullptr;
+    for (int i = 0; i < 3; ++i) { a.qs[i] = desc->q_stride[i]; a.ks[i] = desc->kv_stride[i]; a.os[i] = desc->o_stride[i]; }
+    if (p.fp8 || (p.dbuf && r >= 1) || kv_auto(desc)) {  // dense chunk
+      a.ks[2] = d; a.ks[1] = (int64_t)len * d; a.ks[0] = (int64_t)desc->H * len * d;
+    }
+    a.scale = scale;
+    a.lse = lse;
+    a.out = out;
+    a.acc = p.W > 1 && !p.unfused ? (float*)(ws + p.off_acc) : nullptr;
+    if (p.W == 1) a.mode = 0;
+    else if (p.unfused) {
+      a.mode = 0;
+      if (r > 0) {
+        a.out = ws + p.off_tmp_o;
+        a.lse = (float*)(ws + p.off_tmp_lse);
+        a.os[2] = d; a.os[1] = (int64_t)desc->Sq * d; a.os[0] = (int64_t)desc->H * desc->Sq * d;
+      }
+    } else a.mode = r == 0 ? 1 : (r == p.W - 1 ? 3 : 2);
+
+    if (p.dequant_stage && len > 0) {
+      // Algorithm 1 line 4, split in two so that no rounding is added: the codes are widened to
+      // bf16 exactly here (scale 1), and the MFMA kernel multiplies the fp32 scores and P by the
+      // per-token scales.
+      const int64_t rows = (int64_t)desc->B * desc->H * len;
+      if ((st = launch_fp8_dequant(rows, d, USP_BF16, (const uint8_t*)kp, nullptr, ws + p.off_deq_k, cs)) != USP_OK) return st;
+      if ((st = launch_fp8_dequant(rows, d, USP_BF16, (const uint8_t*)vp, nullptr, ws + p.off_deq_v, cs)) != USP_OK) return st;
+      a.k = ws + p.off_deq_k; a.v = ws + p.off_deq_v;
+      a.kv_dtype = USP_BF16;
+    }
+    st = attn_mfma_supported(a) ? launch_attn_mfma(a, cs) : launch_attn_generic(a, cs);
+    if (st != USP_OK) return st;
+    if (p.unfused && r > 0) {
+      st = launch_lse_merge((int64_t)p.rows_q, d, desc->qo_dtype, out, lse, ws + p.off_tmp_o,
+                            (const float*)(ws + p.off_tmp_lse), out, lse, cs);
+      if (st != USP_OK) return st;
+    }
+    if (p.dbuf && r >= 1 && r + 2 < p.W) {  // a later transfer will reuse this step's buffer
+      USP_CHECK_HIP(g_events.get(&computed[r]));
+      USP_CHECK_HIP(hipEventRecord(computed[r], cs));
+    }
+  }
+  return USP_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,91 @@
+// Internal helpers shared by the library's translation units (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <stdarg.h>
+#include "usp.h"
+
+namespace usp {
+
+// thread-local message behind usp_last_error()
+void set_error(const char* fmt, ...);
+void clear_error();
+
+#define USP_CHECK_ARG(cond, ...)                       \
+  do {                                                 \
+    if (!(cond)) {                                     \
+      ::usp::set_error(__VA_ARGS__);                   \
+      return USP_ERR_INVALID_ARG;                      \
+    }                                                  \
+  } while (0)
+
+#define USP_CHECK_HIP(expr)                                                    \
+  do {                                                                         \
+    hipError_t e_ = (expr);                                                    \
+    if (e_ != hipSuccess) {                                                    \
+      ::usp::set_error("%s failed: %s", #expr, hipGetErrorString(e_));         \
+      return USP_ERR_HIP;                                                      \
+    }                                                                          \
+  } while (0)
+
+static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// ---- device-side scalar type helpers ---------------------------------------------------
+typedef uint16_t bf16_t;  // raw bf16 bits
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// fp32 -> bf16, round to nearest even (finite inputs; NaN stays NaN via the quiet bit)
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+// two fp32 -> packed bf16x2 (low half = a), hardware RNE convert
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+  typedef __bf16 bf16x2_v __attribute__((ext_vector_type(2)));
+  typedef float f32x2_v __attribute__((ext_vector_type(2)));
+  f32x2_v f = {a, b};
+  bf16x2_v r = __builtin_convertvector(f, bf16x2_v);
+  return *reinterpret_cast<uint32_t*>(&r);
+}
+
+// ---- kernel launchers implemented in the .hip files ------------------------------------
+usp_status launch_fp8_quant(int64_t rows, int64_t cols, int in_dt, const void* x, uint8_t* q,
+                            float* scales, hipStream_t st);
+usp_status launch_fp8_dequant(int64_t rows, int64_t cols, int out_dt, const uint8_t* q,
+                              const float* scales, void* y, hipStream_t st);
+usp_status launch_lse_merge(int64_t rows, int d, int dt, const void* o1, const float* lse1,
+                            const void* o2, const float* lse2, void* o_out, float* lse_out,
+                            hipStream_t st);
+
+// One attention step over one KV chunk.
+struct AttnStep {
+  int B, H, d, Sq, Sc;
+  int qo_dtype;              // USP_F32 / USP_BF16
+  int kv_dtype;              // USP_F32 / USP_BF16 / USP_FP8_E4M3FN
+  const void* q;
+  const void* k;
+  const void* v;
+  const float* k_scale;      // FP8 only: [B,H,Sc]
+  const float* v_scale;
+  const uint8_t* key_mask;   // [B,Sc] or null
+  int64_t qs[3], ks[3], os[3];
+  float scale;
+  // merge-in-epilogue: mode 0 = write (O_r, lse_r) to out/lse in qo_dtype (single chunk or unfused)
+  //                    mode 1 = first of several chunks: write fp32 O to acc, lse to lse
+  //                    mode 2 = middle chunk: merge with (acc, lse), write back fp32
+  //                    mode 3 = last chunk: merge with (acc, lse), write out in qo_dtype and lse
+  int mode;
+  float* acc;                // fp32 [B,H,Sq,d] dense carried O (modes 1-3)
+  void* out;                 // qo_dtype by os strides (modes 0, 3)
+  float* lse;                // fp32 [B,H,Sq] dense
+};
+usp_status launch_attn_generic(const AttnStep& s, hipStream_t st);
+usp_status launch_attn_mfma(const AttnStep& s, hipStream_t st);
+bool attn_mfma_supported(const AttnStep& s);
+
+}  // namespace usp

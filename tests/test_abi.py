@@ -1,0 +1,76 @@
+"""The C ABI library loads and exports every function include/usp.h declares; argument
+validation that needs no GPU rejects bad calls with the documented status."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    src = open(os.path.join(ROOT, "include", "usp.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(usp_[a-z0-9_]+)\s*\(", src)))
+
+
+def _lib():
+    path = os.path.join(ROOT, "paper_2602_10940_amd", "libusp.so")
+    if not os.path.exists(path):
+        from paper_2602_10940_amd import build
+        build.build()
+    return ctypes.CDLL(path)
+
+
+def test_header_symbols_exported():
+    lib = _lib()
+    names = _declared()
+    assert {"usp_ring_attn_fwd", "usp_lse_merge", "usp_fp8_quant", "usp_fp8_dequant",
+            "usp_ring_attn_workspace_bytes", "usp_last_error", "usp_version"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_binding_declares_same_exports():
+    from paper_2602_10940_amd import binding
+    assert sorted(binding.EXPORTS) == _declared()
+
+
+def test_validation_without_gpu():
+    lib = _lib()
+    lib.usp_last_error.restype = ctypes.c_char_p
+    i64, i32, vp = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p
+    lib.usp_fp8_quant.argtypes = [i64, i64, i32, vp, vp, vp, vp]
+    assert lib.usp_fp8_quant(4, 12, 1, None, None, None, None) == -1        # cols % 8
+    assert b"multiple of 8" in lib.usp_last_error()
+    assert lib.usp_fp8_quant(4, 16, 7, None, None, None, None) == -1        # dtype
+    assert lib.usp_fp8_quant(4, 16, 1, None, None, None, None) == -1        # null pointers
+    assert lib.usp_fp8_quant(0, 16, 1, None, None, None, None) == 0         # empty: nothing to do
+    lib.usp_lse_merge.argtypes = [i64, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+    assert lib.usp_lse_merge(8, 12, 1, None, None, None, None, None, None, None) == -1
+    assert lib.usp_lse_merge(0, 128, 1, None, None, None, None, None, None, None) == 0
+
+
+def test_workspace_sizes_and_descriptor_checks():
+    from paper_2602_10940_amd import binding as b
+    lib = b.load_library()
+    lens = (ctypes.c_int32 * 4)(1152, 1152, 1152, 1152)
+    d = b.AttnDesc()
+    d.B, d.H, d.d, d.Sq, d.n_chunks = 1, 24, 128, 1152, 4
+    d.chunk_len = ctypes.cast(lens, ctypes.POINTER(ctypes.c_int32))
+    d.qo_dtype = d.kv_dtype = b.USP_BF16
+    for i, s in enumerate((24 * 1152 * 128, 1152 * 128, 128)):
+        d.q_stride[i] = d.o_stride[i] = s
+    rows = 24 * 1152
+    assert b.usp_ring_attn_workspace_bytes(d) == rows * 128 * 4            # fp32 carried O
+    d.flags = b.USP_ATTN_DOUBLE_BUFFER
+    assert b.usp_ring_attn_workspace_bytes(d) == rows * 128 * 4 + 4 * rows * 128 * 2
+    d.kv_dtype = b.USP_FP8_E4M3FN
+    fp8 = b.usp_ring_attn_workspace_bytes(d)
+    assert fp8 == rows * 128 * 4 + 2 * (2 * rows * 128 + 2 * rows * 4) + 2 * rows * 128 * 2
+    d.n_chunks = 1; d.flags = 0; d.kv_dtype = b.USP_BF16
+    assert b.usp_ring_attn_workspace_bytes(d) == 0
+    d.d = 100
+    with pytest.raises(b.UspError):
+        b.usp_ring_attn_workspace_bytes(d)

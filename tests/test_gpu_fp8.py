@@ -1,0 +1,133 @@
+"""FP8 pack/unpack parity: HIP kernels (through the C ABI) vs the oracle, bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import usp_oracle as orc
+from paper_2602_10940_amd import workloads as W
+from tests.gpu_util import DEV, dev_bf16, dev_f32, host_bits_bf16
+
+pytestmark = pytest.mark.gpu
+
+
+def _usp():
+    import paper_2602_10940_amd as P
+    return P
+
+
+def _check_quant(x32, dtype):
+    P = _usp()
+    xd = dev_bf16(x32) if dtype == "bf16" else dev_f32(x32)
+    q, s = P.usp_fp8_quant(xd)
+    torch.cuda.synchronize()
+    eq, es = orc.fp8_quant(x32)
+    np.testing.assert_array_equal(s.cpu().numpy().view(np.uint32), es.view(np.uint32))
+    gq = q.cpu().numpy()
+    bad = np.argwhere(gq != eq)
+    assert bad.size == 0, "first mismatches %s got %s exp %s x %s s %s" % (
+        bad[:5], gq[tuple(bad[:5].T)], eq[tuple(bad[:5].T)], x32[tuple(bad[:5].T)], es[bad[:5, 0]])
+    return q, s, eq, es
+
+
+@pytest.mark.parametrize("rows,cols,dtype", [
+    (256, 128, "f32"),        # tiny config payload
+    (256, 128, "bf16"),
+    (37, 8, "bf16"), (5, 64, "f32"), (129, 136, "bf16"), (3, 256, "bf16"), (66, 520, "f32"),
+    (19, 1000, "bf16"), (7, 2048, "bf16"), (50, 3072, "bf16"), (9, 4096, "f32"),
+    (3, 4104, "bf16"), (2, 20000, "bf16"),      # long-row kernel
+    (1, 65536, "bf16"),                          # per-tensor scale = one row
+    (1001, 128, "bf16"),                         # ring K/V view, ragged row count
+])
+def test_quant_bit_exact(rows, cols, dtype):
+    x = W.make_matrix(100 + rows + cols, rows, cols, dtype, "wide" if rows % 2 else "normal")
+    _check_quant(x, dtype)
+
+
+def test_quant_tiny_workload_payload():
+    x = W.make_payload(W.WORKLOADS["tiny"])
+    _check_quant(x, "f32")
+
+
+def test_quant_zero_rows_negative_zero_and_empty():
+    P = _usp()
+    x = W.make_matrix(5, 12, 64, "f32", "zero_rows")
+    x[0, 5] = -0.0
+    q, s, eq, es = _check_quant(x, "f32")
+    assert q[0, 5].item() == 0x80
+    q0, s0 = P.usp_fp8_quant(torch.empty((0, 64), dtype=torch.bfloat16, device=DEV))
+    assert q0.shape == (0, 64)
+    q1, s1 = P.usp_fp8_quant(torch.empty((5, 0), dtype=torch.bfloat16, device=DEV))
+    torch.cuda.synchronize()
+    assert torch.all(s1 == 1.0)
+
+
+def test_quant_denormal_scales():
+    # absmax so small that absmax/448 is a float32 denormal: the division must stay IEEE
+    x = W.make_matrix(6, 64, 32, "f32")
+    x *= np.float32(1e-37)
+    x[::4] *= np.float32(1e-5)
+    _check_quant(x, "f32")
+
+
+def test_converter_every_rounding_boundary():
+    """Row absmax exactly 448 makes the scale 1.0, so the cast sees x itself: sweep every
+    float32 whose low 16 bits are at / next to a tie, for all high halves with |x| <= 448."""
+    hi = np.arange(0, 0x43E0 + 1, dtype=np.uint32)
+    lows = np.array([0x0000, 0x0001, 0x7FFF, 0x8000, 0x8001, 0xFFFF], dtype=np.uint32)
+    bits = ((hi[:, None] << 16) | lows[None, :]).reshape(-1)
+    vals = bits.view(np.float32)
+    vals = vals[np.abs(vals) <= 448.0]
+    vals = np.concatenate([vals, -vals])
+    pad = (-len(vals)) % 7
+    vals = np.concatenate([vals, np.zeros(pad, np.float32)])
+    x = np.empty((len(vals) // 7, 8), np.float32)
+    x[:, 0] = 448.0
+    x[:, 1:] = vals.reshape(-1, 7)
+    q, s, eq, es = _check_quant(x, "f32")
+    assert np.all(es == 1.0)
+
+
+def test_dequant_all_codes_and_bit_exact():
+    P = _usp()
+    codes = np.arange(256, dtype=np.uint8).reshape(1, 256).repeat(4, 0)
+    codes[:, 0x7F] = 0x7E     # NaN codes never come out of the quantiser
+    codes[:, 0xFF] = 0xFE
+    scales = np.array([1.0, 0.37, 3.1e-3, 1.7e4], np.float32)
+    qd = torch.from_numpy(codes).to(DEV)
+    sd = torch.from_numpy(scales).to(DEV)
+    y32 = P.usp_fp8_dequant(qd, sd, torch.float32)
+    y16 = P.usp_fp8_dequant(qd, sd, torch.bfloat16)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(y32.cpu().numpy().view(np.uint32), orc.fp8_dequant(codes, scales).view(np.uint32))
+    np.testing.assert_array_equal(host_bits_bf16(y16), orc.fp8_dequant_bf16(codes, scales))
+
+
+@pytest.mark.parametrize("rows,cols", [(256, 128), (33, 8), (17, 24), (64, 3072), (1001, 128), (2, 20000)])
+def test_roundtrip_bit_exact(rows, cols):
+    P = _usp()
+    x = W.make_matrix(7 + rows, rows, cols, "bf16", "wide")
+    q, s = P.usp_fp8_quant(dev_bf16(x))
+    y16 = P.usp_fp8_dequant(q, s, torch.bfloat16)
+    y32 = P.usp_fp8_dequant(q, s, torch.float32)
+    torch.cuda.synchronize()
+    eq, es = orc.fp8_quant(x)
+    np.testing.assert_array_equal(q.cpu().numpy(), eq)
+    np.testing.assert_array_equal(host_bits_bf16(y16), orc.fp8_dequant_bf16(eq, es))
+    np.testing.assert_array_equal(y32.cpu().numpy().view(np.uint32), orc.fp8_dequant(eq, es).view(np.uint32))
+
+
+def test_full_size_flux_payload_sampled_rows():
+    """FLUX-1024 All-to-All payload [4608, 3072] bf16 in the launch configuration the bench
+    times; every row's scale and 512 seeded rows' bytes are checked against the oracle."""
+    P = _usp()
+    wl = W.WORKLOADS["flux1024_u"]
+    x = W.make_payload(wl)
+    q, s = P.usp_fp8_quant(dev_bf16(x))
+    y = P.usp_fp8_dequant(q, s, torch.bfloat16)
+    torch.cuda.synchronize()
+    rows = W.sample_rows(11, x.shape[0], 512)
+    eq, es = orc.fp8_quant(x)
+    np.testing.assert_array_equal(s.cpu().numpy().view(np.uint32), es.view(np.uint32))
+    np.testing.assert_array_equal(q.cpu().numpy()[rows], eq[rows])
+    np.testing.assert_array_equal(host_bits_bf16(y)[rows], orc.fp8_dequant_bf16(eq[rows], es[rows]))
+    assert q.numel() * 2 == x.size * 2 and q.element_size() == 1   # half the bf16 volume
