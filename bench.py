@@ -1,0 +1,231 @@
+#!/usr/bin/env python3
+"""Benchmark of the USP hot path on one MI355X.
+
+One "step" = one pass of the hot path on the FLUX-1024 Ulysses shard (workload
+`flux1024_u`): FP8 pack of the [4608, 3072] bf16 All-to-All payload (usp_fp8_quant),
+its unpack (usp_fp8_dequant), and attention of the [1, 24, 4608, 128] bf16 shard
+(usp_ring_attn_fwd, one KV chunk).  All inputs are seeded synthetic data already
+resident in HBM.  `value` is attention TFLOP/s over the whole step time (the FP8
+pack/unpack time is inside the step); per-kernel figures follow in the same JSON line.
+
+Prints ONE JSON line.  Extra legs outside the timed region: the ring-degree-4 shard
+(`flux1024_r4`, merge + side-stream double buffering, hidden fraction), and the
+fp64 oracle timed on the host cores as `cpu_baseline`.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6   # 256 CU x 4096 flop/clk x 2.4 GHz (dense, no sparsity)
+PEAK_HBM_GBS = 8000.0
+
+
+def _events(n):
+    import torch
+    return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ring", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is a one-GPU hot path (one rank's share of USP attention); "
+              "--gpus %d is not supported, run with --gpus 1" % args.gpus, file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2602_10940_amd as P
+    from paper_2602_10940_amd import workloads as W
+
+    P.load_library()                      # fails loudly if the HIP library is not built
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    def up_bf16(x32):
+        bits = W.f32_to_bf16_bits(x32)
+        return torch.from_numpy(bits.view(np.int16).copy()).to(dev).view(torch.bfloat16).reshape(x32.shape)
+
+    # ---------------- workload: FLUX-1024 shard, Ulysses only --------------------------------
+    wl = W.WORKLOADS["flux1024_u"]
+    inp = W.make_attention_inputs(wl)
+    q, k, v = up_bf16(inp.q), up_bf16(inp.k[0]), up_bf16(inp.v[0])
+    out = torch.empty_like(q)
+    lse = torch.empty((wl.B, wl.H, wl.Sq), dtype=torch.float32, device=dev)
+    scale = float(inp.softmax_scale)
+    x0 = up_bf16(W.make_payload(wl))
+    R, C = x0.shape
+    NBUF = 24                              # 24 x (28.3 + 14.2 + 28.3) MB > 512 MB: FP8 kernels cannot live in cache
+    xs = [x0] + [torch.roll(x0, i, 0).contiguous() for i in range(1, NBUF)]
+    qs = [torch.empty((R, C), dtype=torch.uint8, device=dev) for _ in range(NBUF)]
+    ss = [torch.empty((R,), dtype=torch.float32, device=dev) for _ in range(NBUF)]
+    ys = [torch.empty((R, C), dtype=torch.bfloat16, device=dev) for _ in range(NBUF)]
+
+    def step(i, ev=None):
+        j = i % NBUF
+        if ev: ev[0].record()
+        P.usp_fp8_quant(xs[j], qs[j], ss[j])
+        if ev: ev[1].record()
+        P.usp_fp8_dequant(qs[j], ss[j], y=ys[j])
+        if ev: ev[2].record()
+        P.usp_ring_attn_fwd(q, [k], [v], softmax_scale=scale, out=out, lse=lse)
+        if ev: ev[3].record()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    evs = [_events(4) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, evs[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    t_quant = float(np.mean([e[0].elapsed_time(e[1]) for e in evs]))
+    t_deq = float(np.mean([e[1].elapsed_time(e[2]) for e in evs]))
+    t_attn = float(np.mean([e[2].elapsed_time(e[3]) for e in evs]))
+
+    flops = wl.attn_flops()
+    value = flops / (ms_per_step * 1e-3) * 1e-12
+    attn_tflops = flops / (t_attn * 1e-3) * 1e-12
+    fp8_bytes = R * C * 3 + R * 4          # quant: 2 B in + 1 B out per element + scales; dequant mirrored
+    quant_gbs = fp8_bytes / (t_quant * 1e-3) * 1e-9
+    deq_gbs = fp8_bytes / (t_deq * 1e-3) * 1e-9
+
+    result = {
+        "metric": "ring-attn TFLOP/s + FP8 quant GB/s, % of MI355X peak, FLUX-1024 shard",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "flux1024_u: B=1 H=24 d=128 S=4608 bf16, one KV chunk; FP8 payload [4608,3072] bf16",
+                   "step": "fp8_quant + fp8_dequant + ring_attn_fwd"},
+        "attn": {"ms": round(t_attn, 4), "tflops": round(attn_tflops, 1),
+                 "frac_of_bf16_peak": round(attn_tflops / PEAK_BF16_TFLOPS, 4)},
+        "fp8_quant": {"us": round(t_quant * 1e3, 2), "gbs": round(quant_gbs, 1),
+                      "frac_of_hbm_peak": round(quant_gbs / PEAK_HBM_GBS, 4), "bytes": fp8_bytes},
+        "fp8_dequant": {"us": round(t_deq * 1e3, 2), "gbs": round(deq_gbs, 1),
+                        "frac_of_hbm_peak": round(deq_gbs / PEAK_HBM_GBS, 4), "bytes": fp8_bytes},
+        "roofline": {"bound": "mfma", "achieved": round(attn_tflops, 1), "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "kernel": "attn_mfma_kernel", "flops_per_launch": flops},
+    }
+
+    # ---------------- ring degree 4: merge + double buffering (not part of `value`) -----------
+    if not args.no_ring:
+        result["ring"] = ring_leg(P, W, torch, dev, up_bf16)
+
+    # ---------------- oracle on the host cores ------------------------------------------------
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(W, wl)
+
+    print(json.dumps(result))
+    return 0
+
+
+def ring_leg(P, W, torch, dev, up_bf16, reps=50):
+    """FLUX-1024 ring-degree-4 shard: all chunks resident (T_c), side-stream copies alone (T_m),
+    Algorithm 2 pipelined (T_p), copy-then-compute on one stream (T_s)."""
+    wl = W.WORKLOADS["flux1024_r4"]
+    inp = W.make_attention_inputs(wl)
+    q = up_bf16(inp.q)
+    ks = [up_bf16(x) for x in inp.k]
+    vs = [up_bf16(x) for x in inp.v]
+    out = torch.empty_like(q)
+    lse = torch.empty((wl.B, wl.H, wl.Sq), dtype=torch.float32, device=dev)
+    scale = float(inp.softmax_scale)
+    side = torch.cuda.Stream()
+    cur = torch.cuda.current_stream()
+    desc = P.make_attn_desc(q, ks, out, scale, P.USP_ATTN_DOUBLE_BUFFER)
+    ws = torch.empty((P.usp_ring_attn_workspace_bytes(desc),), dtype=torch.uint8, device=dev)
+    stage = [torch.empty_like(ks[0]) for _ in range(4)]
+
+    def timed(fn):
+        for _ in range(5):
+            fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    def resident():
+        P.usp_ring_attn_fwd(q, ks, vs, softmax_scale=scale, out=out, lse=lse, workspace=ws)
+
+    def pipelined():
+        P.usp_ring_attn_fwd(q, ks, vs, softmax_scale=scale, flags=P.USP_ATTN_DOUBLE_BUFFER, out=out, lse=lse,
+                            workspace=ws, copy_stream=side)
+
+    def copies_only():
+        for r in range(1, wl.W):
+            stage[0].copy_(ks[r], non_blocking=True)
+            stage[1].copy_(vs[r], non_blocking=True)
+
+    def serial():
+        # copy-then-compute on one stream: a ring step that waits for its chunk before computing
+        kk, vv = [ks[0]], [vs[0]]
+        for r in range(1, wl.W):
+            stage[2 * (r & 1)].copy_(ks[r], non_blocking=True)
+            stage[2 * (r & 1) + 1].copy_(vs[r], non_blocking=True)
+            kk.append(stage[2 * (r & 1)]); vv.append(stage[2 * (r & 1) + 1])
+        P.usp_ring_attn_fwd(q, kk, vv, softmax_scale=scale, out=out, lse=lse, workspace=ws)
+
+    t_c, t_m, t_p, t_s = timed(resident), timed(copies_only), timed(pipelined), timed(serial)
+    hidden = max(0.0, min(1.0, 1.0 - (t_p - t_c) / t_m)) if t_m > 0 else None
+    flops = wl.attn_flops()
+    return {"workload": "flux1024_r4: Sq=1152, 4 chunks of 1152, H=24 d=128 bf16",
+            "t_compute_ms": round(t_c, 4), "t_copies_ms": round(t_m, 4), "t_pipelined_ms": round(t_p, 4),
+            "t_serial_ms": round(t_s, 4), "hidden_fraction": None if hidden is None else round(hidden, 3),
+            "serial_over_pipelined": round(t_s / t_p, 3),
+            "tflops_resident": round(flops / (t_c * 1e-3) * 1e-12, 1),
+            "tflops_pipelined": round(flops / (t_p * 1e-3) * 1e-12, 1),
+            "note": "on-device copies stand in for ring recv; an xGMI link is ~50x slower"}
+
+
+def cpu_baseline(W, wl, heads=8):
+    """The fp64 oracle, untuned, on a bounded sample: `heads` of the 24 heads of the shard's
+    attention (all queries, all keys) plus the whole FP8 payload pack/unpack."""
+    from oracle import usp_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info() if p.get("user_api") == "blas"] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    inp = W.make_attention_inputs(wl, heads=heads)
+    x = W.make_payload(wl)
+    t0 = time.perf_counter()
+    orc.attention(inp.q, inp.k[0], inp.v[0], float(inp.softmax_scale))
+    t_attn = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    codes, s = orc.fp8_quant(x)
+    orc.fp8_dequant_bf16(codes, s)
+    t_fp8 = time.perf_counter() - t0
+    step_s = t_attn * (wl.H / heads) + t_fp8       # scaled to one whole step
+    return {"value": round(wl.attn_flops() / step_s * 1e-12, 5), "unit": "TFLOP/s", "cores": int(cores),
+            "kind": "oracle",
+            "sample": "%d of %d heads of flux1024_u attention (%.1f s) scaled x%g, plus the full "
+                      "[4608,3072] FP8 pack+unpack (%.1f s); fp64 numpy reference, not a tuned CPU baseline"
+                      % (heads, wl.H, t_attn, wl.H / heads, t_fp8)}
+
+
+if __name__ == "__main__":
+    sys.exit(main())
