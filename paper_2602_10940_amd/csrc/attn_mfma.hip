@@ -11,8 +11,9 @@
 //     reductions plus one exchange between lane l and lane l^32.
 //   * The exponentiated tile P^T, already in registers in the accumulator layout, is cast to
 //     bf16 and used directly as the B operand of O^T += V^T P^T; it never touches LDS.
-//   * K tiles (64 keys) sit in LDS row-major; V tiles sit in LDS transposed ([d][key], keys
-//     permuted inside blocks of 16 so that the 8 keys a lane needs are one 16-byte read).
+//   * K and V tiles (64 keys) sit in LDS row-major, XOR-swizzled instead of padded; the V^T
+//     operand (8 keys of one head-dim column per lane) comes from the LDS transposing read.
+//   * O and l are rescaled lazily: only when a row max has outgrown the exponent reference.
 //   * exp is taken in base 2 with scale * log2(e) folded into one FMA.
 #include "usp_common.h"
 
@@ -22,6 +23,7 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kD = 128;          // head dimension
 constexpr int kWaves = 8;
@@ -29,22 +31,22 @@ constexpr int kThreads = kWaves * 64;
 constexpr int kQPerWave = 32;
 constexpr int kQPerWG = kWaves * kQPerWave;   // 256
 constexpr int kTile = 64;        // keys per LDS tile
-constexpr int kKPitch = kD + 8;  // bf16 elements per K row in LDS (272 B: conflict-free 16 B reads)
-constexpr int kVPitch = kTile + 8;  // bf16 elements per V^T row in LDS (144 B)
+constexpr int kRowB = kD * 2;    // bytes per K / V row in LDS (256, unpadded)
+constexpr int kTileB = kTile * kRowB;          // 16 KB
+constexpr float kLazyTau = 8.0f; // the exponent reference is only moved when the max grows by > 2^8
 
+// K and V tiles are row-major [key][128 bf16] in LDS without padding; bank conflicts are
+// avoided by XOR-swizzling the sixteen 16-byte pieces of a row:
+//   K: piece c of key r sits at piece c ^ (r & 15)       (16-byte MFMA operand reads of 16 rows)
+//   V: piece c of key r sits at piece c ^ ((r & 3) << 2) (transposing 8-byte reads of 4 rows)
 struct Smem {
-  bf16_t k[2][kTile * kKPitch];
-  bf16_t vt[2][kD * kVPitch];
+  unsigned char k[2][kTileB];
+  unsigned char v[2][kTileB];
   float bias[2][kTile];   // 0 for a live key, -inf for a masked / out-of-range key
-  float kmul[2][kTile];   // per-key score multiplier: softmax scale * log2(e) [* FP8 scale of the key]
+  float kmul[2][kTile];   // per-key score multiplier: softmax scale * log2(e) * FP8 scale of the key
   float vmul[2][kTile];   // per-key FP8 scale of the V row (only read when K/V came from FP8 codes)
   int any_masked[2];
 };
-
-// position of key offset o (0..15) inside its block of 16 in the V^T rows: the B operand of
-// the P.V MFMA holds, for lane group g, accumulator registers 8*half + j, i.e. key offsets
-// 8*(j/4) + 4*g + j%4; storing offset o at 8*g + j makes those 8 keys contiguous.
-__device__ __forceinline__ int vpos(int o) { return 8 * ((o >> 2) & 1) + 4 * (o >> 3) + (o & 3); }
 
 __device__ __forceinline__ float xlane32_max(float x) {
   auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
@@ -53,6 +55,15 @@ __device__ __forceinline__ float xlane32_max(float x) {
 __device__ __forceinline__ float xlane32_sum(float x) {
   auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// LDS transposing read: the 16 lanes of a group each name 8 bytes; seen as a 4 x 16 matrix of
+// bf16 (row i = the data of lanes 4i..4i+3), lane j of the group receives column j.
+__device__ __forceinline__ u32x2 lds_read_tr(const unsigned char* p) {
+  typedef short s16x4 __attribute__((ext_vector_type(4)));
+  s16x4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (s16x4 __attribute__((address_space(3)))*)(p));
+  return __builtin_bit_cast(u32x2, r);
 }
 
 __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(AttnStep s) {
@@ -90,33 +101,30 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(AttnStep s) {
   for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
     for (int i = 0; i < 16; ++i) oacc[dt][i] = 0.0f;
-  float m = -INFINITY;   // running max, in log2 units (score * scale * log2 e)
+  float m = -INFINITY;   // exponent reference (>= running max - tau), log2 units
   float lsum = 0.0f;     // this lane's share of the running sum (its 32 of every 64 keys)
   const float scale2 = s.scale * 1.44269504088896340736f;
 
   // ---- tile loader: global -> registers -> LDS ------------------------------------------
-  // thread tid moves 16-byte pieces c = tid and tid + 512 of the 64 x 256-byte K and V tiles
+  // thread tid moves 16-byte pieces tid and tid + 512 of the 64 x 256-byte K and V tiles
   uint4 kst0, kst1, vst0, vst1;
-  const int ld_key0 = tid >> 4, ld_key1 = (tid + kThreads) >> 4, ld_dc = tid & 15;
+  const int ld_key0 = tid >> 4, ld_key1 = (tid + kThreads) >> 4, ld_c = tid & 15;
+  const int k_dst0 = ld_key0 * kRowB + ((ld_c ^ (ld_key0 & 15)) << 4);
+  const int k_dst1 = ld_key1 * kRowB + ((ld_c ^ (ld_key1 & 15)) << 4);
+  const int v_dst0 = ld_key0 * kRowB + ((ld_c ^ ((ld_key0 & 3) << 2)) << 4);
+  const int v_dst1 = ld_key1 * kRowB + ((ld_c ^ ((ld_key1 & 3) << 2)) << 4);
   auto load_tile = [&](int t) {
     const int ka = min(t * kTile + ld_key0, Sc - 1), kc = min(t * kTile + ld_key1, Sc - 1);
-    kst0 = *reinterpret_cast<const uint4*>(kb + (int64_t)ka * s.ks[2] + ld_dc * 8);
-    vst0 = *reinterpret_cast<const uint4*>(vb + (int64_t)ka * s.ks[2] + ld_dc * 8);
-    kst1 = *reinterpret_cast<const uint4*>(kb + (int64_t)kc * s.ks[2] + ld_dc * 8);
-    vst1 = *reinterpret_cast<const uint4*>(vb + (int64_t)kc * s.ks[2] + ld_dc * 8);
-  };
-  auto store_piece = [&](int buf, int kk, const uint4& kq, const uint4& vq) {
-    *reinterpret_cast<uint4*>(&sm.k[buf][kk * kKPitch + ld_dc * 8]) = kq;
-    const int col = (kk & ~15) + vpos(kk & 15);
-    bf16_t* dst = &sm.vt[buf][(ld_dc * 8) * kVPitch + col];
-    dst[0 * kVPitch] = (bf16_t)(vq.x); dst[1 * kVPitch] = (bf16_t)(vq.x >> 16);
-    dst[2 * kVPitch] = (bf16_t)(vq.y); dst[3 * kVPitch] = (bf16_t)(vq.y >> 16);
-    dst[4 * kVPitch] = (bf16_t)(vq.z); dst[5 * kVPitch] = (bf16_t)(vq.z >> 16);
-    dst[6 * kVPitch] = (bf16_t)(vq.w); dst[7 * kVPitch] = (bf16_t)(vq.w >> 16);
+    kst0 = *reinterpret_cast<const uint4*>(kb + (int64_t)ka * s.ks[2] + ld_c * 8);
+    vst0 = *reinterpret_cast<const uint4*>(vb + (int64_t)ka * s.ks[2] + ld_c * 8);
+    kst1 = *reinterpret_cast<const uint4*>(kb + (int64_t)kc * s.ks[2] + ld_c * 8);
+    vst1 = *reinterpret_cast<const uint4*>(vb + (int64_t)kc * s.ks[2] + ld_c * 8);
   };
   auto store_tile = [&](int t, int buf) {
-    store_piece(buf, ld_key0, kst0, vst0);
-    store_piece(buf, ld_key1, kst1, vst1);
+    *reinterpret_cast<uint4*>(&sm.k[buf][k_dst0]) = kst0;
+    *reinterpret_cast<uint4*>(&sm.k[buf][k_dst1]) = kst1;
+    *reinterpret_cast<uint4*>(&sm.v[buf][v_dst0]) = vst0;
+    *reinterpret_cast<uint4*>(&sm.v[buf][v_dst1]) = vst1;
     if (wave == 0) {
       const int key = t * kTile + lane;
       const bool live = key < Sc && (!mask || mask[key] != 0);
@@ -130,6 +138,16 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(AttnStep s) {
       if (lane == 0) sm.any_masked[buf] = dead != 0ull;
     }
   };
+
+  // ---- per-lane LDS read offsets ------------------------------------------------------------
+  // K operand (S^T = K Q^T): lane (n, g) reads key 32*kt + n, piece 2*ks + g, swizzled by n & 15
+  const int k_rd_row = n * kRowB;
+  const int k_rd_x = (g ^ (n & 15)) << 4;            // piece (2ks+g) ^ (n&15) = (2ks) ^ (g ^ (n&15))
+  // V^T operand (O^T += V^T P^T), transposing read: lane l = 16*grp + 4*i + cc supplies the 8 bytes
+  // of key (16*blk + 4*g + i [+8]), head-dim 32*dt + 16*(grp&1) + 4*cc .. +3
+  const int tr_i = (lane >> 2) & 3, tr_cc = lane & 3, tr_dh = (lane >> 4) & 1;
+  const int v_rd_row = (4 * g + tr_i) * kRowB + ((2 * tr_dh + (tr_cc >> 1)) << 4) + 8 * (tr_cc & 1);
+  const int v_rd_x = tr_i << 6;                        // piece swizzle (key & 3) << 2, in bytes
 
   if (ntiles > 0) {
     load_tile(0);
@@ -147,10 +165,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(AttnStep s) {
     for (int kt = 0; kt < 2; ++kt) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) sacc[kt][i] = 0.0f;
-      const bf16_t* kr = &sm.k[buf][(32 * kt + n) * kKPitch + 8 * g];
+      const unsigned char* kr = &sm.k[buf][32 * kt * kRowB + k_rd_row];
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(kr + 16 * ks);
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(kr + ((32 * ks) ^ k_rd_x));
         sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], sacc[kt], 0, 0, 0);
       }
     }
@@ -184,10 +202,19 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(AttnStep s) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, sacc[kt][i]);
     tmax = xlane32_max(tmax) * mul;              // mul > 0: max commutes with the scaling
-    const float m_new = fmaxf(m, tmax);
-    const float m_use = (m_new == -INFINITY) ? 0.0f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f(m - m_use);
-    m = m_new;
+    // Lazy rescaling: the reference m only moves when some query's max outgrew it by more than
+    // tau (P then stays below 2^tau, harmless in fp32 / bf16); otherwise O and l are left alone.
+    if (__builtin_amdgcn_ballot_w64(tmax > m + kLazyTau) != 0ull) {
+      const float m_new = fmaxf(m, tmax);
+      const float alpha = __builtin_amdgcn_exp2f(m - ((m_new == -INFINITY) ? 0.0f : m_new));
+      m = m_new;
+      lsum *= alpha;
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) oacc[dt][i] *= alpha;
+    }
+    const float m_use = (m == -INFINITY) ? 0.0f : m;
     float psum = 0.0f;
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
@@ -197,7 +224,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(AttnStep s) {
         sacc[kt][i] = p;
         psum += p;
       }
-    lsum = lsum * alpha + psum;
+    lsum += psum;
     if (scaled) {   // P.V on codes: fold the V row scale into P
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt)
@@ -208,12 +235,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(AttnStep s) {
           sacc[kt][4 * i4 + 2] *= cz.z; sacc[kt][4 * i4 + 3] *= cz.w;
         }
     }
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) oacc[dt][i] *= alpha;
 
     // ---- O^T += V^T P^T ---------------------------------------------------------------------
+    // P^T block (kt, half) = accumulator registers 8*half .. 8*half+7 of sacc[kt]; for lane group g
+    // register j is key 32*kt + 16*half + 8*(j/4) + 4*g + j%4, which is exactly the order the two
+    // transposing reads below deliver V in (keys +0..3 then +8..11 of the 16-key block, offset 4*g).
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
@@ -223,11 +249,14 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(AttnStep s) {
         for (int j = 0; j < 4; ++j)
           pu[j] = pack_bf16x2(sacc[kt][8 * half + 2 * j], sacc[kt][8 * half + 2 * j + 1]);
         const bf16x8 pb = __builtin_bit_cast(bf16x8, pu);
-        const int col = 32 * kt + 16 * half + 8 * g;
+        const unsigned char* vr = &sm.v[buf][(32 * kt + 16 * half) * kRowB + v_rd_row];
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt) {
-          const bf16x8 a = *reinterpret_cast<const bf16x8*>(&sm.vt[buf][(32 * dt + n) * kVPitch + col]);
-          oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, oacc[dt], 0, 0, 0);
+          const int off = (dt << 6) ^ v_rd_x;
+          const u32x2 lo = lds_read_tr(vr + off);
+          const u32x2 hi = lds_read_tr(vr + 8 * kRowB + off);
+          const u32x4 av = {lo[0], lo[1], hi[0], hi[1]};
+          oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pb, oacc[dt], 0, 0, 0);
         }
       }
 
