@@ -17,6 +17,17 @@
 //   * exp is taken in base 2 with scale * log2(e) folded into one FMA.
 #include "usp_common.h"
 
+#ifndef LAB_STAMP
+#define LAB_STAMP(slot)
+#endif
+#ifndef LAB_COUNT_SLOW
+#define LAB_COUNT_SLOW()
+#endif
+#ifndef LAB_WG_START
+#define LAB_WG_START()
+#define LAB_WG_END()
+#endif
+
 namespace usp {
 namespace {
 
@@ -66,6 +77,52 @@ __device__ __forceinline__ u32x2 lds_read_tr(const unsigned char* p) {
   return __builtin_bit_cast(u32x2, r);
 }
 
+// Chunk result from the running state (O~ = oacc, reference m in log2 units, this lane's part of l),
+// merged with the carried (O, lse) of earlier chunks by the section 3.4 equations, and stored.
+__device__ __forceinline__ void finish_and_store(const AttnStep& s, f32x16 (&oacc)[4], float m, float lsum,
+                                                 int b, int h, int q0, int n, int g) {
+  // ---- chunk result, merge with carried state, store ------------------------------------
+  const float l = xlane32_sum(lsum);
+  const int qi = q0 + n;
+  const bool valid = qi < s.Sq;
+  const int64_t row = ((int64_t)b * s.H + h) * s.Sq + (valid ? qi : s.Sq - 1);
+  float lse_r = -INFINITY, c_cur = 0.0f;
+  if (l > 0.0f) { lse_r = (m + log2f(l)) * 0.69314718055994530942f; c_cur = 1.0f / l; }
+  float w_prev = 0.0f, lse_new = lse_r;
+  if (s.mode >= 2) {
+    const float lse_p = s.lse[row];
+    const float mm = fmaxf(lse_p, lse_r);
+    if (mm == -INFINITY) { w_prev = 0.0f; c_cur = 0.0f; lse_new = -INFINITY; }
+    else {
+      lse_new = mm + logf(expf(lse_p - mm) + expf(lse_r - mm));
+      w_prev = expf(lse_p - lse_new);
+      c_cur *= expf(lse_r - lse_new);
+    }
+  }
+  if (!valid) return;
+  float* accp = s.acc ? s.acc + row * kD : nullptr;
+  bf16_t* outp = (bf16_t*)s.out + b * s.os[0] + h * s.os[1] + (int64_t)qi * s.os[2];
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int i4 = 0; i4 < 4; ++i4) {
+      const int dcol = 32 * dt + 8 * i4 + 4 * g;
+      float o[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = oacc[dt][4 * i4 + e] * c_cur;
+      if (s.mode >= 2) {
+        const float4 p = *reinterpret_cast<const float4*>(accp + dcol);
+        o[0] = fmaf(w_prev, p.x, o[0]); o[1] = fmaf(w_prev, p.y, o[1]);
+        o[2] = fmaf(w_prev, p.z, o[2]); o[3] = fmaf(w_prev, p.w, o[3]);
+      }
+      if (s.mode == 1 || s.mode == 2)
+        *reinterpret_cast<float4*>(accp + dcol) = make_float4(o[0], o[1], o[2], o[3]);
+      else
+        *reinterpret_cast<uint2*>(outp + dcol) = make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
+    }
+  if (g == 0) s.lse[row] = lse_new;
+}
+
 __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(AttnStep s) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   Smem& sm = *reinterpret_cast<Smem*>(smem_raw);
@@ -94,6 +151,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(AttnStep s) {
     const bf16_t* qr = qb + (int64_t)qi * s.qs[2] + 8 * g;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8*>(qr + 16 * ks);
+    // pin Q in registers here: otherwise the waits for these loads sink into the key loop, where
+    // they would also wait for the next tile's prefetch
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qreg[ks]));
   }
 
   f32x16 oacc[4];
@@ -264,46 +325,341 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(AttnStep s) {
     __syncthreads();
   }
 
-  // ---- chunk result, merge with carried state, store ------------------------------------
-  const float l = xlane32_sum(lsum);
-  const int qi = q0 + n;
-  const bool valid = qi < s.Sq;
-  const int64_t row = ((int64_t)b * s.H + h) * s.Sq + (valid ? qi : s.Sq - 1);
-  float lse_r = -INFINITY, c_cur = 0.0f;
-  if (l > 0.0f) { lse_r = (m + log2f(l)) * 0.69314718055994530942f; c_cur = 1.0f / l; }
-  float w_prev = 0.0f, lse_new = lse_r;
-  if (s.mode >= 2) {
-    const float lse_p = s.lse[row];
-    const float mm = fmaxf(lse_p, lse_r);
-    if (mm == -INFINITY) { w_prev = 0.0f; c_cur = 0.0f; lse_new = -INFINITY; }
-    else {
-      lse_new = mm + logf(expf(lse_p - mm) + expf(lse_r - mm));
-      w_prev = expf(lse_p - lse_new);
-      c_cur *= expf(lse_r - lse_new);
-    }
+  finish_and_store(s, oacc, m, lsum, b, h, q0, n, g);
+}
+
+
+// =============================================================================================
+// Ping-pong kernel (fast path: no key mask, chunk length a multiple of 64, plain bf16 K/V).
+//
+// The 8 waves form two groups (waves 0-3 = A, 4-7 = B; each SIMD hosts one wave of each).  A
+// wave alternates between a softmax phase SM(t) (VALU only: scores of tile t -> bf16 P) and a
+// matrix phase MM(t) (MFMA only: O += P(t) V(t), then the scores of tile t+1).  Group B runs
+// one phase behind group A and a work-group barrier separates the phases, so in every phase
+// one wave of each SIMD feeds the matrix core while the other does the exponentials.
+//   phase 2j   : A does SM(j),  B does MM(j-1)
+//   phase 2j+1 : A does MM(j),  B does SM(j)
+// K and V tiles are double-buffered in LDS and written by direct global->LDS loads, issued at
+// the start of every odd phase for K(j+2) and V(j+1): each has two full phases to land.
+// =============================================================================================
+__device__ __forceinline__ void lds_dma16(const void* gbase, uint32_t lane_off, uint32_t lds_base) {
+  // 64 lanes x 16 bytes from gbase (wave-uniform) + lane_off (per lane): lane i's 16 bytes land at
+  // lds_base + 16*i.  Issued through inline asm so the compiler does not serialise later LDS reads
+  // behind it; completion is awaited with an explicit vmcnt wait before the barrier that
+  // publishes the tile.
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :: "s"(lds_base), "v"(lane_off), "s"(gbase) : "memory", "m0");
+}
+constexpr int kStages = 3;   // LDS tile buffers per tensor
+
+struct SmemPP {
+  unsigned char k[kStages][kTileB];
+  unsigned char v[kStages][kTileB];
+};
+
+__device__ __forceinline__ u32x2 lds_read_tr3(const __attribute__((address_space(3))) unsigned char* p) {
+  typedef short s16x4 __attribute__((ext_vector_type(4)));
+  s16x4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p));
+  return __builtin_bit_cast(u32x2, r);
+}
+
+template <int N> struct IC { static constexpr int value = N; };
+#ifndef USP_PREFETCH_READS
+#define USP_PREFETCH_READS 12
+#endif
+constexpr int kPrefetchReads = USP_PREFETCH_READS;   // LDS reads in flight ahead of the first MFMA (8 or 12)
+
+__global__ __launch_bounds__(kThreads, 2) void attn_mfma_pp_kernel(AttnStep s) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  SmemPP& sm = *reinterpret_cast<SmemPP*>(smem_raw);
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it in an SGPR
+  const int n = lane & 31, g = lane >> 5;
+  const int h = blockIdx.y, b = blockIdx.z;
+  const int q0 = blockIdx.x * kQPerWG + wave * kQPerWave;
+  const bool grpA = wave < 4;
+  LAB_WG_START();
+
+  const bf16_t* qb = (const bf16_t*)s.q + b * s.qs[0] + h * s.qs[1];
+  const unsigned char* kb = (const unsigned char*)((const bf16_t*)s.k + b * s.ks[0] + h * s.ks[1]);
+  const unsigned char* vb = (const unsigned char*)((const bf16_t*)s.v + b * s.ks[0] + h * s.ks[1]);
+  const int nt = s.Sc / kTile;          // host guarantees Sc % 64 == 0 and Sc > 0
+  const float scale2 = s.scale * 1.44269504088896340736f;
+
+  // ---- direct global->LDS tile loads: wave w moves rows 8w..8w+7 of a tile, 4 rows per instruction.
+  // Per-lane byte offsets inside a tile are fixed; the tile base pointers advance as scalars.
+  const int dma_r0 = 8 * wave + (lane >> 4), dma_r1 = dma_r0 + 4;
+  const int dma_p = lane & 15;
+  const uint32_t rowB = (uint32_t)(s.ks[2] * 2);   // bytes between keys in global memory
+  const int64_t tileB = (int64_t)kTile * rowB;
+  const uint32_t kg0 = dma_r0 * rowB + ((dma_p ^ (dma_r0 & 15)) << 4);
+  const uint32_t kg1 = dma_r1 * rowB + ((dma_p ^ (dma_r1 & 15)) << 4);
+  const uint32_t vg0 = dma_r0 * rowB + ((dma_p ^ ((dma_r0 & 3) << 2)) << 4);
+  const uint32_t vg1 = dma_r1 * rowB + ((dma_p ^ ((dma_r1 & 3) << 2)) << 4);
+  const uint32_t lds_k = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)&sm.k[0][0] + 8 * wave * kRowB);
+  const uint32_t lds_v = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)&sm.v[0][0] + 8 * wave * kRowB);
+  auto issue_k_half = [&](const unsigned char* tile, int stage, int half) {
+    lds_dma16(tile, half ? kg1 : kg0, lds_k + stage * kTileB + half * 4 * kRowB);
+  };
+  auto issue_v_half = [&](const unsigned char* tile, int stage, int half) {
+    lds_dma16(tile, half ? vg1 : vg0, lds_v + stage * kTileB + half * 4 * kRowB);
+  };
+
+  // Tile loads are issued from the softmax phases (the phase whose critical resource, the VALU,
+  // is not the matrix core): group A's SM(j) prefetches K(j+2) and V(j+1), group B's SM(j), one
+  // phase later, K(j+3) and V(j+2).  Tiles needed before the first of those land are fetched here.
+  issue_k_half(kb, 0, 0); issue_k_half(kb, 0, 1);
+  issue_v_half(vb, 0, 0); issue_v_half(vb, 0, 1);
+  if (nt > 1) { issue_k_half(kb + tileB, 1, 0); issue_k_half(kb + tileB, 1, 1); }
+  if (!grpA) {
+    if (nt > 1) { issue_v_half(vb + tileB, 1, 0); issue_v_half(vb + tileB, 1, 1); }
+    if (nt > 2) { issue_k_half(kb + 2 * tileB, 2, 0); issue_k_half(kb + 2 * tileB, 2, 1); }
   }
-  if (!valid) return;
-  float* accp = s.acc ? s.acc + row * kD : nullptr;
-  bf16_t* outp = (bf16_t*)s.out + b * s.os[0] + h * s.os[1] + (int64_t)qi * s.os[2];
+  const unsigned char* kpre = kb + (grpA ? 2 : 3) * tileB;   // next K / V tile this wave prefetches
+  const unsigned char* vpre = vb + (grpA ? 1 : 2) * tileB;
+
+  // Q^T operand: lane (n, g) holds Q[q0+n][16*ks + 8*g .. +7] for ks = 0..7
+  bf16x8 qreg[8];
+  {
+    const int qi = min(q0 + n, s.Sq - 1);
+    const bf16_t* qr = qb + (int64_t)qi * s.qs[2] + 8 * g;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8*>(qr + 16 * ks);
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qreg[ks]));
+  }
+
+  f32x16 oacc[4];
 #pragma unroll
   for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-    for (int i4 = 0; i4 < 4; ++i4) {
-      const int dcol = 32 * dt + 8 * i4 + 4 * g;
-      float o[4];
+    for (int i = 0; i < 16; ++i) oacc[dt][i] = 0.0f;
+  f32x16 sacc[2];
+  u32x4 pk[4];
+  float m = -INFINITY, lsum = 0.0f;
+
+  // per-lane LDS read addresses (see the layout notes at Smem): 8 for the K operand (one per 16-wide
+  // slice of the head dimension), 4 for the V^T operand (one per 32-wide slice); stage, key block
+  // and row offsets are compile-time immediates on top of these
+  typedef const __attribute__((address_space(3))) unsigned char* lds_cptr;
+  lds_cptr k_rd[8], v_rd[4];
+  {
+    const int k_rd_row = n * kRowB;
+    const int k_rd_x = (g ^ (n & 15)) << 4;
+    const int tr_i = (lane >> 2) & 3, tr_cc = lane & 3, tr_dh = (lane >> 4) & 1;
+    const int v_rd_row = (4 * g + tr_i) * kRowB + ((2 * tr_dh + (tr_cc >> 1)) << 4) + 8 * (tr_cc & 1);
+    const int v_rd_x = tr_i << 6;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) o[e] = oacc[dt][4 * i4 + e] * c_cur;
-      if (s.mode >= 2) {
-        const float4 p = *reinterpret_cast<const float4*>(accp + dcol);
-        o[0] = fmaf(w_prev, p.x, o[0]); o[1] = fmaf(w_prev, p.y, o[1]);
-        o[2] = fmaf(w_prev, p.z, o[2]); o[3] = fmaf(w_prev, p.w, o[3]);
-      }
-      if (s.mode == 1 || s.mode == 2)
-        *reinterpret_cast<float4*>(accp + dcol) = make_float4(o[0], o[1], o[2], o[3]);
-      else
-        *reinterpret_cast<uint2*>(outp + dcol) = make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
+    for (int ks = 0; ks < 8; ++ks)
+      k_rd[ks] = (lds_cptr)(uintptr_t)((uint32_t)(uintptr_t)&sm.k[0][0] + k_rd_row + ((32 * ks) ^ k_rd_x));
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+      v_rd[dt] = (lds_cptr)(uintptr_t)((uint32_t)(uintptr_t)&sm.v[0][0] + v_rd_row + ((dt << 6) ^ v_rd_x));
+  }
+
+  // scores of the tile in LDS stage `stage`: sacc[kt] += K Q^T over head-dim slices ks_lo..ks_lo+3
+  auto qk_block = [&](int stage, int kt, int ks_lo) {
+#pragma unroll
+    for (int ks = ks_lo; ks < ks_lo + 4; ++ks) {
+      const bf16x8 a = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(
+          k_rd[ks] + stage * kTileB + 32 * kt * kRowB);
+      sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], sacc[kt], 0, 0, 0);
     }
-  if (g == 0) s.lse[row] = lse_new;
+  };
+  // O^T += V^T P^T for the 16 keys of block blk of the tile in LDS stage `stage`
+  auto pv_block = [&](int stage, int blk) {
+    const bf16x8 pb = __builtin_bit_cast(bf16x8, pk[blk]);
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) {
+      const u32x2 lo = lds_read_tr3(v_rd[dt] + stage * kTileB + 16 * blk * kRowB);
+      const u32x2 hi = lds_read_tr3(v_rd[dt] + stage * kTileB + (16 * blk + 8) * kRowB);
+      const u32x4 av = {lo[0], lo[1], hi[0], hi[1]};
+      oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pb, oacc[dt], 0, 0, 0);
+    }
+  };
+  // matrix phase: O += P V (V tile in stage SV) interleaved with the scores of the next tile (K in
+  // stage SK).  Only this wave feeds the SIMD's matrix core during the phase, so its LDS operand
+  // reads are scheduled eight MFMAs ahead of their use (sched_group_barrier: 0x008 MFMA, 0x100 LDS read).
+  auto MM_full = [&](int sv, int sk) {
+    __builtin_amdgcn_s_setprio(2);
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) sacc[kt][i] = 0.0f;
+#pragma unroll
+    for (int blk = 0; blk < 4; ++blk) {
+      pv_block(sv, blk);
+      qk_block(sk, blk >> 1, 4 * (blk & 1));
+    }
+    __builtin_amdgcn_sched_group_barrier(0x100, kPrefetchReads, 0);
+#pragma unroll
+    for (int blk = 0; blk < 4; ++blk) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {   // P.V group
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, kPrefetchReads == 12 ? 2 : 1, 0);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {   // score group
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, kPrefetchReads == 12 ? 1 : 2, 0);
+      }
+    }
+    __builtin_amdgcn_s_setprio(0);
+  };
+  auto MM_last = [&](int sv) {   // last tile: no further scores
+    __builtin_amdgcn_s_setprio(2);
+#pragma unroll
+    for (int blk = 0; blk < 4; ++blk) pv_block(sv, blk);
+    __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    }
+    __builtin_amdgcn_s_setprio(0);
+  };
+  // softmax phase: sacc (scores of one tile) -> pk (bf16 P), running reference m and sum l.
+  // Fast path: exponentials are taken against the current reference m without first looking for
+  // the tile's maximum; the row sum then certifies the result: if this lane's sum of P is at most
+  // 2^16, no P exceeded 2^16, which fp32 accumulators and bf16 operands hold comfortably.  Only
+  // when some lane fails that test (always on the first tile, where m = -inf makes every P inf)
+  // does the wave find the true maximum, move m, rescale O and l, and redo the exponentials.
+  // While it runs, the wave also issues its four tile loads (K into stage sk if do_k, V into stage
+  // sv if do_v), spread between the exponential blocks so that the eight waves do not hit the
+  // load path at once.
+  auto exp_block = [&](int kt, int half, float& psum) {
+    float p[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      p[j] = __builtin_amdgcn_exp2f(fmaf(sacc[kt][8 * half + j], scale2, -m));
+      psum += p[j];
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) pk[2 * kt + half][j] = pack_bf16x2(p[2 * j], p[2 * j + 1]);
+    // anchor the block here, between the tile loads that surround it in program order
+    asm volatile("" : "+v"(pk[2 * kt + half]));
+  };
+  auto SM = [&](int sk, int sv, bool do_k, bool do_v) {
+    float psum = 0.0f;
+    // sched_barrier: keep each load between two blocks of arithmetic (the scheduler would
+    // otherwise hoist all four to the top, where they queue behind one another)
+    if (do_k) issue_k_half(kpre, sk, 0);
+    exp_block(0, 0, psum);
+    __builtin_amdgcn_sched_barrier(0);
+    if (do_k) issue_k_half(kpre, sk, 1);
+    exp_block(0, 1, psum);
+    __builtin_amdgcn_sched_barrier(0);
+    if (do_v) issue_v_half(vpre, sv, 0);
+    exp_block(1, 0, psum);
+    __builtin_amdgcn_sched_barrier(0);
+    if (do_v) issue_v_half(vpre, sv, 1);
+    exp_block(1, 1, psum);
+    __builtin_amdgcn_sched_barrier(0);
+    kpre += tileB;
+    vpre += tileB;
+    if (__builtin_amdgcn_ballot_w64(!(psum <= 65536.0f)) != 0ull) {
+      LAB_COUNT_SLOW();
+      float tmax = -INFINITY;
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, sacc[kt][i]);
+      const float m_new = fmaxf(m, xlane32_max(tmax) * scale2);
+      const float alpha = __builtin_amdgcn_exp2f(m - m_new);   // m = -inf (first tile) gives 0
+      m = m_new;
+      lsum *= alpha;
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) oacc[dt][i] *= alpha;
+      psum = 0.0f;
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int half = 0; half < 2; ++half) exp_block(kt, half, psum);
+    }
+    lsum += psum;
+    // pin the results here: without a use in this phase the optimiser sinks the exponentials past
+    // the barrier, next to their first use in the matrix phase
+#pragma unroll
+    for (int blk = 0; blk < 4; ++blk) asm volatile("" : "+v"(pk[blk]));
+    asm volatile("" : "+v"(lsum));
+  };
+
+  // prologue: the first tiles have landed -> scores of tile 0 in both groups
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+  __builtin_amdgcn_s_barrier();
+#pragma unroll
+  for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sacc[kt][i] = 0.0f;
+    qk_block(0, kt, 0);
+    qk_block(0, kt, 4);
+  }
+
+  // Both groups execute the same barrier sequence (two per tile index j = 0..nt); the steady-state
+  // bodies are straight-line code so the accumulators stay in place.
+  // sched_barrier(0): nothing may be moved across a phase boundary (the compiler would otherwise
+  // sink the softmax arithmetic below the barrier, into the matrix phase of the same wave).
+  // A wave waits for its own tile loads at the end of its softmax phases: the batch issued one
+  // softmax phase earlier must have landed, the batch just issued (4 loads if full) may be in flight.
+  auto phase_barrier = [&](int wait_mode) {   // 0: no wait, 1: vmcnt(4), 2: vmcnt(0)
+    __builtin_amdgcn_sched_barrier(0);
+    if (wait_mode == 1) __builtin_amdgcn_s_waitcnt(0x0F74);
+    else if (wait_mode == 2) __builtin_amdgcn_s_waitcnt(0x0F70);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto nxt = [](int x) { return x == 2 ? 0 : x + 1; };
+  int st = 0;                            // LDS stage of tile j, j % 3
+  if (grpA) {
+    // tile j: phase 2j = SM(j), prefetching K(j+2) -> stage st+2, V(j+1) -> stage st+1;
+    //         phase 2j+1 = MM(j) with V(j) in stage st, K(j+1) in stage st+1
+    for (int j = 0; j < nt - 1; ++j) {
+      const int s1 = nxt(st), s2 = nxt(s1);
+      LAB_STAMP(6 * j);
+      SM(s2, s1, j + 2 < nt, true);
+      LAB_STAMP(6 * j + 1);
+      phase_barrier(j + 2 < nt ? 1 : 2);
+      LAB_STAMP(6 * j + 3);
+      MM_full(st, s1);
+      LAB_STAMP(6 * j + 5);
+      phase_barrier(0);
+      st = s1;
+    }
+    SM(0, 0, false, false);
+    phase_barrier(2);
+    MM_last(st);
+    phase_barrier(0);
+    phase_barrier(0);
+    phase_barrier(0);
+  } else {
+    // tile j: phase 2j = MM(j-1) with V(j-1) in stage st-1, K(j) in stage st;
+    //         phase 2j+1 = SM(j), prefetching K(j+3) -> stage st, V(j+2) -> stage st+2
+    phase_barrier(0);                                 // phase 0: nothing to do yet
+    SM(0, 2, 3 < nt, 2 < nt);                         // phase 1 (tile 0)
+    phase_barrier(3 < nt ? 1 : 2);
+    for (int j = 1; j < nt; ++j) {
+      const int sp = st;                              // stage of tile j-1
+      st = nxt(st);
+      LAB_STAMP(6 * j);
+      MM_full(sp, st);
+      LAB_STAMP(6 * j + 1);
+      phase_barrier(0);
+      LAB_STAMP(6 * j + 3);
+      SM(st, sp, j + 3 < nt, j + 2 < nt);             // st+2 == sp (mod 3)
+      LAB_STAMP(6 * j + 5);
+      phase_barrier(j + 3 < nt ? 1 : 2);
+    }
+    MM_last(st);
+    phase_barrier(0);
+    phase_barrier(0);
+  }
+  LAB_WG_END();
+
+  finish_and_store(s, oacc, m, lsum, b, h, q0, n, g);
 }
 
 }  // namespace
@@ -317,7 +673,12 @@ usp_status launch_attn_mfma(const AttnStep& s, hipStream_t st) {
   static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(Smem));
   USP_CHECK_HIP(attr);
-  hipLaunchKernelGGL(attn_mfma_kernel, grid, block, sizeof(Smem), st, s);
+  static const hipError_t attr_pp = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_pp_kernel),
+                                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(SmemPP));
+  USP_CHECK_HIP(attr_pp);
+  const bool fast = s.Sc > 0 && s.Sc % kTile == 0 && !s.key_mask && !s.k_scale;
+  if (fast) hipLaunchKernelGGL(attn_mfma_pp_kernel, grid, block, sizeof(SmemPP), st, s);
+  else hipLaunchKernelGGL(attn_mfma_kernel, grid, block, sizeof(Smem), st, s);
   USP_CHECK_HIP(hipGetLastError());
   return USP_OK;
 }
