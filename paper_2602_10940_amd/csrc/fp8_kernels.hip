@@ -30,15 +30,46 @@ __device__ __forceinline__ void load8(const float* p, float (&v)[8]) {
   v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
 }
 
-// E4M3 code of t (round to nearest even, saturating): the hardware convert after a clamp
-// to the finite range, so an out-of-range quotient never turns into the NaN code.
-__device__ __forceinline__ uint2 encode8(const float (&v)[8], float s) {
+// x / s for many x and one s.  The compiler's IEEE-correct fp32 division is: reciprocal estimate,
+// one Newton step on the reciprocal, then two residual corrections of the quotient (plus operand
+// pre-scaling that only engages for extreme exponents).  Everything that depends on s alone is
+// hoisted here; quotient() is the per-element remainder of that same sequence and returns the
+// correctly rounded quotient whenever the pre-scaling would have been a no-op, which `fast`
+// guarantees for the divisor (|x| <= 448 s bounds the quotient).  Quotients too small to be
+// normal fp32 can differ in their last bits, but they are far below 2^-10 and encode to +-0
+// either way.  Rows outside the fast range use the plain division.
+struct RowDiv {
+  float s, rcp;
+  bool fast;
+};
+__device__ __forceinline__ RowDiv make_rowdiv(float s) {
+  RowDiv d;
+  d.s = s;
+  d.fast = s > 0x1p-60f && s < 0x1p+60f;
+  const float r0 = __builtin_amdgcn_rcpf(s);
+  const float e0 = fmaf(-s, r0, 1.0f);
+  d.rcp = fmaf(e0, r0, r0);
+  return d;
+}
+__device__ __forceinline__ float quotient(float x, const RowDiv& d) {
+  const float q0 = x * d.rcp;
+  const float r0 = fmaf(-d.s, q0, x);
+  const float q1 = fmaf(r0, d.rcp, q0);
+  const float r1 = fmaf(-d.s, q1, x);
+  // s > 0, so the quotient has the sign of x; restoring it keeps -0 (the corrections turn it into +0)
+  return __builtin_copysignf(fmaf(r1, d.rcp, q1), x);
+}
+
+// E4M3 codes of v[i] / s (round to nearest even, saturating).  In the fast range s is a normal
+// number, |v[i]| <= 448 s up to one rounding, so the quotient never reaches the overflow threshold
+// 464 and the hardware convert needs no clamp (inputs are assumed finite).  A denormal s can be
+// far from absmax / 448 in relative terms; that path clamps to +-448 before converting.
+template <bool kFast>
+__device__ __forceinline__ uint2 encode8(const float (&v)[8], const RowDiv& d) {
   float t[8];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    float quo = v[i] / s;  // IEEE-correct fp32 division (compiled without fast-math)
-    t[i] = __builtin_amdgcn_fmed3f(quo, -kFp8Max, kFp8Max);
-  }
+  for (int i = 0; i < 8; ++i)
+    t[i] = kFast ? quotient(v[i], d) : __builtin_amdgcn_fmed3f(v[i] / d.s, -kFp8Max, kFp8Max);
   int lo = __builtin_amdgcn_cvt_pk_fp8_f32(t[0], t[1], 0, false);
   lo = __builtin_amdgcn_cvt_pk_fp8_f32(t[2], t[3], lo, true);
   int hi = __builtin_amdgcn_cvt_pk_fp8_f32(t[4], t[5], 0, false);
@@ -85,10 +116,19 @@ __global__ __launch_bounds__(256) void fp8_quant_rows_kernel(const T* __restrict
   for (int off = LPR / 2; off > 0; off >>= 1) a = fmaxf(a, __shfl_xor(a, off, 64));
   const float s = scale_from_absmax(a);
   if (row_ok && l == 0) scales[row] = s;
+  const RowDiv d = make_rowdiv(s);
+  if (__builtin_amdgcn_ballot_w64(!d.fast) == 0ull) {
 #pragma unroll
-  for (int i = 0; i < NV; ++i) {
-    const int u = l + i * LPR;
-    if (row_ok && u < units) *reinterpret_cast<uint2*>(q + base + (int64_t)u * 8) = encode8(v[i], s);
+    for (int i = 0; i < NV; ++i) {
+      const int u = l + i * LPR;
+      if (row_ok && u < units) *reinterpret_cast<uint2*>(q + base + (int64_t)u * 8) = encode8<true>(v[i], d);
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int u = l + i * LPR;
+      if (row_ok && u < units) *reinterpret_cast<uint2*>(q + base + (int64_t)u * 8) = encode8<false>(v[i], d);
+    }
   }
 }
 
@@ -114,10 +154,11 @@ __global__ __launch_bounds__(256) void fp8_quant_longrow_kernel(const T* __restr
   a = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
   const float s = scale_from_absmax(a);
   if (threadIdx.x == 0) scales[row] = s;
+  const RowDiv d = make_rowdiv(s);
   for (int64_t u = threadIdx.x; u < units; u += 256) {
     float v[8];
     load8(x + base + u * 8, v);
-    *reinterpret_cast<uint2*>(q + base + u * 8) = encode8(v, s);
+    *reinterpret_cast<uint2*>(q + base + u * 8) = d.fast ? encode8<true>(v, d) : encode8<false>(v, d);
   }
 }
 

@@ -87,6 +87,29 @@ def test_converter_every_rounding_boundary():
     assert np.all(es == 1.0)
 
 
+def test_division_exact_next_to_every_rounding_boundary():
+    """Arbitrary scales: for 256 seeded absmax values, every row holds x = fl(mid * s) shifted by
+    -2..+2 ulps for each of the 126 midpoints between adjacent E4M3 magnitudes, so x / s lands on
+    or next to every rounding boundary and a quotient off by one ulp would flip a code."""
+    rng = np.random.Generator(np.random.PCG64(77))
+    tab = orc.e4m3fn_decode_table()[:0x7F]
+    mids = ((tab[:-1] + tab[1:]) / 2).astype(np.float32)            # 126 boundaries, exact in fp32
+    amax = (rng.uniform(1.0, 2.0, 256) * np.exp2(rng.integers(-40, 40, 256))).astype(np.float32)
+    s = (amax / np.float32(448)).astype(np.float32)
+    base = (mids[None, :] * s[:, None]).astype(np.float32)          # [256, 126]
+    cols = [amax[:, None]]
+    for k in (-2, -1, 0, 1, 2):
+        v = base.copy()
+        for _ in range(abs(k)):
+            v = np.nextafter(v, np.float32(np.inf) if k > 0 else np.float32(0))
+        cols += [v, -v]
+    x = np.concatenate(cols, axis=1)
+    pad = (-x.shape[1]) % 8
+    x = np.concatenate([x, np.zeros((x.shape[0], pad), np.float32)], axis=1).astype(np.float32)
+    assert np.all(np.abs(x[:, 1:]) < amax[:, None])
+    _check_quant(x, "f32")
+
+
 def test_dequant_all_codes_and_bit_exact():
     P = _usp()
     codes = np.arange(256, dtype=np.uint8).reshape(1, 256).repeat(4, 0)
