@@ -190,16 +190,16 @@ __device__ __forceinline__ void store8(bf16_t* y, const float (&a)[4], const flo
                                             pack_bf16x2(b[0], b[1]), pack_bf16x2(b[2], b[3]));
 }
 
-template <typename T, int VEC>
+template <typename T, int VEC, typename IDX>
 __global__ __launch_bounds__(256) void fp8_dequant_kernel(const uint8_t* __restrict__ q,
                                                           const float* __restrict__ scales,
-                                                          T* __restrict__ y, int64_t total_units,
+                                                          T* __restrict__ y, IDX total_units,
                                                           uint32_t units_per_row) {
-  const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const IDX g = (IDX)blockIdx.x * 256 + threadIdx.x;
   if (g >= total_units) return;
-  const int64_t row = g / units_per_row;
+  const IDX row = g / units_per_row;   // 32-bit arithmetic whenever the tensor allows it
   const float s = scales ? scales[row] : 1.0f;   // no scales: exact widening of the codes
-  const int64_t e = g * VEC;
+  const int64_t e = (int64_t)g * VEC;
   if constexpr (VEC == 16) {
     uint4 w = *reinterpret_cast<const uint4*>(q + e);
     float a[4], b[4];
@@ -238,20 +238,24 @@ usp_status quant_dispatch(int64_t rows, int64_t cols, const T* x, uint8_t* q, fl
   return USP_OK;
 }
 
+template <typename T, int VEC>
+usp_status dequant_launch(int64_t rows, int64_t cols, const uint8_t* q, const float* scales, T* y,
+                          hipStream_t st) {
+  const int64_t upr = cols / VEC, total = rows * upr;
+  const dim3 grid((unsigned)((total + 255) / 256)), block(256);
+  if (total < ((int64_t)1 << 31))
+    hipLaunchKernelGGL((fp8_dequant_kernel<T, VEC, uint32_t>), grid, block, 0, st, q, scales, y, (uint32_t)total, (uint32_t)upr);
+  else
+    hipLaunchKernelGGL((fp8_dequant_kernel<T, VEC, int64_t>), grid, block, 0, st, q, scales, y, total, (uint32_t)upr);
+  USP_CHECK_HIP(hipGetLastError());
+  return USP_OK;
+}
+
 template <typename T>
 usp_status dequant_dispatch(int64_t rows, int64_t cols, const uint8_t* q, const float* scales, T* y,
                             hipStream_t st) {
-  if (cols % 16 == 0) {
-    const int64_t upr = cols / 16, total = rows * upr;
-    hipLaunchKernelGGL((fp8_dequant_kernel<T, 16>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                       q, scales, y, total, (uint32_t)upr);
-  } else {
-    const int64_t upr = cols / 8, total = rows * upr;
-    hipLaunchKernelGGL((fp8_dequant_kernel<T, 8>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                       q, scales, y, total, (uint32_t)upr);
-  }
-  USP_CHECK_HIP(hipGetLastError());
-  return USP_OK;
+  if (cols % 16 == 0) return dequant_launch<T, 16>(rows, cols, q, scales, y, st);
+  return dequant_launch<T, 8>(rows, cols, q, scales, y, st);
 }
 
 }  // namespace
