@@ -37,10 +37,16 @@ def _events(n):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    # the GPU needs a few hundred ms of sustained load before its clocks settle; the defaults
+    # warm up for ~1 s and time ~1.5 s
+    ap.add_argument("--steps", type=int, default=2500)
+    ap.add_argument("--warmup", type=int, default=1500)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-ring", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain elementwise kernel that reads 256 MiB and writes 256 MiB "
+                         "(torch.add on int32), as the known-traffic reference for rocprofv3 --pmc "
+                         "FETCH_SIZE / WRITE_SIZE runs")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is a one-GPU hot path (one rank's share of USP attention); "
@@ -79,18 +85,16 @@ def main() -> int:
 
     def step(i, ev=None):
         j = i % NBUF
-        if ev: ev[0].record()
         P.usp_fp8_quant(xs[j], qs[j], ss[j])
-        if ev: ev[1].record()
         P.usp_fp8_dequant(qs[j], ss[j], y=ys[j])
-        if ev: ev[2].record()
+        if ev: ev[0].record()
         P.usp_ring_attn_fwd(q, [k], [v], softmax_scale=scale, out=out, lse=lse)
-        if ev: ev[3].record()
+        if ev: ev[1].record()
 
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
-    evs = [_events(4) for _ in range(args.steps)]
+    evs = [_events(2) for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
@@ -98,9 +102,29 @@ def main() -> int:
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    t_quant = float(np.mean([e[0].elapsed_time(e[1]) for e in evs]))
-    t_deq = float(np.mean([e[1].elapsed_time(e[2]) for e in evs]))
-    t_attn = float(np.mean([e[2].elapsed_time(e[3]) for e in evs]))
+    t_attn = float(np.mean([e[0].elapsed_time(e[1]) for e in evs]))   # per launch, on the launch stream
+
+    # FP8 kernels: back-to-back launches over the rotating buffers between two events
+    def per_launch(fn, reps=480):
+        for i in range(48):
+            fn(i)
+        a, b = _events(2)
+        a.record()
+        for i in range(reps):
+            fn(i)
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+    t_quant = per_launch(lambda i: P.usp_fp8_quant(xs[i % NBUF], qs[i % NBUF], ss[i % NBUF]))
+    t_deq = per_launch(lambda i: P.usp_fp8_dequant(qs[i % NBUF], ss[i % NBUF], y=ys[i % NBUF]))
+    # the same kernels on 8 payloads stacked into one [36864, 3072] call: launch overhead amortised
+    xb = torch.cat(xs[:8], 0)
+    qb = torch.empty((8 * R, C), dtype=torch.uint8, device=dev)
+    sb = torch.empty((8 * R,), dtype=torch.float32, device=dev)
+    yb = torch.empty((8 * R, C), dtype=torch.bfloat16, device=dev)
+    t_quant8 = per_launch(lambda i: P.usp_fp8_quant(xb, qb, sb), reps=100)
+    t_deq8 = per_launch(lambda i: P.usp_fp8_dequant(qb, sb, y=yb), reps=100)
+    del xb, qb, sb, yb
 
     flops = wl.attn_flops()
     value = flops / (ms_per_step * 1e-3) * 1e-12
@@ -122,10 +146,24 @@ def main() -> int:
                       "frac_of_hbm_peak": round(quant_gbs / PEAK_HBM_GBS, 4), "bytes": fp8_bytes},
         "fp8_dequant": {"us": round(t_deq * 1e3, 2), "gbs": round(deq_gbs, 1),
                         "frac_of_hbm_peak": round(deq_gbs / PEAK_HBM_GBS, 4), "bytes": fp8_bytes},
+        "fp8_x8_payload": {"quant_us": round(t_quant8 * 1e3, 2), "dequant_us": round(t_deq8 * 1e3, 2),
+                           "quant_gbs": round(8 * fp8_bytes / (t_quant8 * 1e-3) * 1e-9, 1),
+                           "dequant_gbs": round(8 * fp8_bytes / (t_deq8 * 1e-3) * 1e-9, 1),
+                           "note": "[36864,3072] in one call; a plain copy kernel reaches ~6.0 TB/s on this GPU"},
         "roofline": {"bound": "mfma", "achieved": round(attn_tflops, 1), "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
                      "kernel": "attn_mfma_kernel", "flops_per_launch": flops},
     }
+
+    if args.calibrate_copy:
+        ca = torch.ones((64 << 20,), dtype=torch.int32, device=dev)
+        cb = torch.empty_like(ca)
+        for _ in range(5):
+            torch.add(ca, 1, out=cb)
+        torch.cuda.synchronize()
+        result["calibrate_copy"] = {"kernel": "torch.add int32", "read_bytes": ca.numel() * 4,
+                                    "write_bytes": cb.numel() * 4, "launches": 5}
+        del ca, cb
 
     # ---------------- ring degree 4: merge + double buffering (not part of `value`) -----------
     if not args.no_ring:
@@ -201,7 +239,7 @@ def ring_leg(P, W, torch, dev, up_bf16, reps=50):
             "note": "on-device copies stand in for ring recv; an xGMI link is ~50x slower"}
 
 
-def cpu_baseline(W, wl, heads=8):
+def cpu_baseline(W, wl, heads=24):
     """The fp64 oracle, untuned, on a bounded sample: `heads` of the 24 heads of the shard's
     attention (all queries, all keys) plus the whole FP8 payload pack/unpack."""
     from oracle import usp_oracle as orc

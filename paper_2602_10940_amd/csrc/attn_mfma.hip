@@ -59,6 +59,23 @@ struct Smem {
   int any_masked[2];
 };
 
+// Work-group -> (batch*head, query block) with the 8 XCDs of the chip in mind: consecutive
+// work-group ids go to consecutive XCDs (id % 8), each with its own L2, so the query blocks of one
+// head are all given to the same XCD (head index % 8) and that head's K/V is fetched from HBM
+// once instead of once per XCD.  The grid holds 8 * ceil(BH / 8) * nqb ids; ids past the last
+// head return false.
+constexpr int kXcds = 8;
+__device__ __forceinline__ bool wg_to_tile(int nqb, int bh_total, int& bh, int& qb) {
+  const int id = blockIdx.x;
+  const int xcd = id % kXcds, slot = id / kXcds;
+  bh = xcd + kXcds * (slot / nqb);
+  qb = slot % nqb;
+  return bh < bh_total;
+}
+static inline unsigned wg_grid_size(int nqb, int bh_total) {
+  return (unsigned)(kXcds * ((bh_total + kXcds - 1) / kXcds) * nqb);
+}
+
 __device__ __forceinline__ float xlane32_max(float x) {
   auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
   return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
@@ -129,8 +146,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(AttnStep s) {
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, g = lane >> 5;
-  const int h = blockIdx.y, b = blockIdx.z;
-  const int q0 = blockIdx.x * kQPerWG + wave * kQPerWave;
+  int bh_, qb_;
+  if (!wg_to_tile((s.Sq + kQPerWG - 1) / kQPerWG, s.B * s.H, bh_, qb_)) return;   // whole work-group
+  const int h = bh_ % s.H, b = bh_ / s.H;
+  const int q0 = qb_ * kQPerWG + wave * kQPerWave;
 
   const bf16_t* qb = (const bf16_t*)s.q + b * s.qs[0] + h * s.qs[1];
   const bf16_t* kb = (const bf16_t*)s.k + b * s.ks[0] + h * s.ks[1];
@@ -376,8 +395,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_pp_kernel(AttnStep s) {
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it in an SGPR
   const int n = lane & 31, g = lane >> 5;
-  const int h = blockIdx.y, b = blockIdx.z;
-  const int q0 = blockIdx.x * kQPerWG + wave * kQPerWave;
+  int bh_, qb_;
+  if (!wg_to_tile((s.Sq + kQPerWG - 1) / kQPerWG, s.B * s.H, bh_, qb_)) return;   // whole work-group
+  const int h = bh_ % s.H, b = bh_ / s.H;
+  const int q0 = qb_ * kQPerWG + wave * kQPerWave;
   const bool grpA = wave < 4;
   LAB_WG_START();
 
@@ -669,7 +690,7 @@ bool attn_mfma_supported(const AttnStep& s) {
 }
 
 usp_status launch_attn_mfma(const AttnStep& s, hipStream_t st) {
-  dim3 grid((unsigned)((s.Sq + kQPerWG - 1) / kQPerWG), (unsigned)s.H, (unsigned)s.B), block(kThreads);
+  dim3 grid(wg_grid_size((s.Sq + kQPerWG - 1) / kQPerWG, s.B * s.H)), block(kThreads);
   static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(Smem));
   USP_CHECK_HIP(attr);
