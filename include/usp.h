@@ -48,6 +48,12 @@ typedef enum {
 #define USP_ATTN_DOUBLE_BUFFER 1u /* stage chunks 1..W-1 through two internal buffers on copy_stream */
 #define USP_ATTN_UNFUSED_MERGE 2u /* per-chunk (O_i, lse_i) then usp_lse_merge, as Algorithm 2 is written;
                                      default folds the merge into the attention kernel's epilogue */
+/* Work decomposition of the bf16 d=128 matrix-core kernel on unmasked chunks whose length is a
+ * multiple of 64.  Default (neither bit): chosen from the number of work-groups the Q shard gives.
+ * Both variants meet the same accuracy bar; the bits exist for tuning and for tests. */
+#define USP_ATTN_KERNEL_WIDE 4u   /* 256 queries per work-group, every wave visits every key */
+#define USP_ATTN_KERNEL_SPLIT 8u  /* 128 queries per work-group, the two wave groups take alternate
+                                     64-key tiles and combine their partial results at the end */
 
 /*
  * Shape of one ring-attention call (paper section 2.2: Q, K, V are [B, H, S, D]).

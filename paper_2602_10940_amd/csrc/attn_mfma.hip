@@ -41,6 +41,7 @@ constexpr int kWaves = 8;
 constexpr int kThreads = kWaves * 64;
 constexpr int kQPerWave = 32;
 constexpr int kQPerWG = kWaves * kQPerWave;   // 256
+constexpr int kQPerWGSplit = 4 * kQPerWave;     // 128: split kernel, two waves per 32 queries
 constexpr int kTile = 64;        // keys per LDS tile
 constexpr int kRowB = kD * 2;    // bytes per K / V row in LDS (256, unpadded)
 constexpr int kTileB = kTile * kRowB;          // 16 KB
@@ -60,20 +61,24 @@ struct Smem {
 };
 
 // Work-group -> (batch*head, query block) with the 8 XCDs of the chip in mind: consecutive
-// work-group ids go to consecutive XCDs (id % 8), each with its own L2, so the query blocks of one
-// head are all given to the same XCD (head index % 8) and that head's K/V is fetched from HBM
-// once instead of once per XCD.  The grid holds 8 * ceil(BH / 8) * nqb ids; ids past the last
-// head return false.
+// work-group ids go to consecutive XCDs (id % 8), each with its own L2.  The (head, query block)
+// items, head-major, are cut into 8 contiguous ranges of equal length, one per XCD: the query
+// blocks of a head stay on one XCD (two where a range boundary falls inside a head), so its K/V
+// is fetched from HBM once or twice instead of once per XCD, and every XCD gets the same number
+// of work-groups whatever the head count.  The grid holds 8 * ceil(items / 8) ids; ids past the
+// last item return false.
 constexpr int kXcds = 8;
+constexpr int kSplitBelowWGs = 128;   // use the key-split kernel when 256-query work-groups number at most this
 __device__ __forceinline__ bool wg_to_tile(int nqb, int bh_total, int& bh, int& qb) {
   const int id = blockIdx.x;
-  const int xcd = id % kXcds, slot = id / kXcds;
-  bh = xcd + kXcds * (slot / nqb);
-  qb = slot % nqb;
+  const int per_xcd = (int)gridDim.x / kXcds;
+  const int item = (id % kXcds) * per_xcd + id / kXcds;
+  bh = item / nqb;
+  qb = item - bh * nqb;
   return bh < bh_total;
 }
 static inline unsigned wg_grid_size(int nqb, int bh_total) {
-  return (unsigned)(kXcds * ((bh_total + kXcds - 1) / kXcds) * nqb);
+  return (unsigned)(kXcds * ((bh_total * nqb + kXcds - 1) / kXcds));
 }
 
 __device__ __forceinline__ float xlane32_max(float x) {
@@ -683,6 +688,326 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_pp_kernel(AttnStep s) {
   finish_and_store(s, oacc, m, lsum, b, h, q0, n, g);
 }
 
+__global__ __launch_bounds__(kThreads, 2) void attn_mfma_pp_split_kernel(AttnStep s) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  SmemPP& sm = *reinterpret_cast<SmemPP*>(smem_raw);
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it in an SGPR
+  const int n = lane & 31, g = lane >> 5;
+  int bh_, qb_;
+  if (!wg_to_tile((s.Sq + kQPerWGSplit - 1) / kQPerWGSplit, s.B * s.H, bh_, qb_)) return;   // whole work-group
+  const int h = bh_ % s.H, b = bh_ / s.H;
+  const int q0 = qb_ * kQPerWGSplit + (wave & 3) * kQPerWave;   // waves w and w+4 share their 32 queries
+  const bool grpA = wave < 4;
+  LAB_WG_START();
+
+  const bf16_t* qb = (const bf16_t*)s.q + b * s.qs[0] + h * s.qs[1];
+  const unsigned char* kb = (const unsigned char*)((const bf16_t*)s.k + b * s.ks[0] + h * s.ks[1]);
+  const unsigned char* vb = (const unsigned char*)((const bf16_t*)s.v + b * s.ks[0] + h * s.ks[1]);
+  const int nt = s.Sc / kTile;          // host guarantees Sc % 64 == 0 and Sc > 0
+  const float scale2 = s.scale * 1.44269504088896340736f;
+
+  // ---- direct global->LDS tile loads: wave w moves rows 8w..8w+7 of a tile, 4 rows per instruction.
+  // Per-lane byte offsets inside a tile are fixed; the tile base pointers advance as scalars.
+  const int dma_r0 = 8 * wave + (lane >> 4), dma_r1 = dma_r0 + 4;
+  const int dma_p = lane & 15;
+  const uint32_t rowB = (uint32_t)(s.ks[2] * 2);   // bytes between keys in global memory
+  const int64_t tileB = (int64_t)kTile * rowB;
+  const uint32_t kg0 = dma_r0 * rowB + ((dma_p ^ (dma_r0 & 15)) << 4);
+  const uint32_t kg1 = dma_r1 * rowB + ((dma_p ^ (dma_r1 & 15)) << 4);
+  const uint32_t vg0 = dma_r0 * rowB + ((dma_p ^ ((dma_r0 & 3) << 2)) << 4);
+  const uint32_t vg1 = dma_r1 * rowB + ((dma_p ^ ((dma_r1 & 3) << 2)) << 4);
+  const uint32_t lds_k = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)&sm.k[0][0] + 8 * wave * kRowB);
+  const uint32_t lds_v = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)&sm.v[0][0] + 8 * wave * kRowB);
+  auto issue_k_half = [&](const unsigned char* tile, int stage, int half) {
+    lds_dma16(tile, half ? kg1 : kg0, lds_k + stage * kTileB + half * 4 * kRowB);
+  };
+  auto issue_v_half = [&](const unsigned char* tile, int stage, int half) {
+    lds_dma16(tile, half ? vg1 : vg0, lds_v + stage * kTileB + half * 4 * kRowB);
+  };
+
+  // Every wave issues one batch of tile loads per phase p: its rows of K(p+3) and V(p+1), both
+  // first read in phase p+2.  Tiles needed before the first batches land are fetched here.
+  issue_k_half(kb, 0, 0); issue_k_half(kb, 0, 1);
+  issue_v_half(vb, 0, 0); issue_v_half(vb, 0, 1);
+  if (nt > 1) { issue_k_half(kb + tileB, 1, 0); issue_k_half(kb + tileB, 1, 1); }
+  if (nt > 2) { issue_k_half(kb + 2 * tileB, 2, 0); issue_k_half(kb + 2 * tileB, 2, 1); }
+  const unsigned char* kpre = kb + 3 * tileB;   // K(p+3) / V(p+1) for the batch of phase p = 0
+  const unsigned char* vpre = vb + tileB;
+
+  // Q^T operand: lane (n, g) holds Q[q0+n][16*ks + 8*g .. +7] for ks = 0..7
+  bf16x8 qreg[8];
+  {
+    const int qi = min(q0 + n, s.Sq - 1);
+    const bf16_t* qr = qb + (int64_t)qi * s.qs[2] + 8 * g;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8*>(qr + 16 * ks);
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qreg[ks]));
+  }
+
+  f32x16 oacc[4];
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) oacc[dt][i] = 0.0f;
+  f32x16 sacc[2];
+  u32x4 pk[4];
+  float m = -INFINITY, lsum = 0.0f;
+
+  // per-lane LDS read addresses (see the layout notes at Smem): 8 for the K operand (one per 16-wide
+  // slice of the head dimension), 4 for the V^T operand (one per 32-wide slice); stage, key block
+  // and row offsets are compile-time immediates on top of these
+  typedef const __attribute__((address_space(3))) unsigned char* lds_cptr;
+  lds_cptr k_rd[8], v_rd[4];
+  {
+    const int k_rd_row = n * kRowB;
+    const int k_rd_x = (g ^ (n & 15)) << 4;
+    const int tr_i = (lane >> 2) & 3, tr_cc = lane & 3, tr_dh = (lane >> 4) & 1;
+    const int v_rd_row = (4 * g + tr_i) * kRowB + ((2 * tr_dh + (tr_cc >> 1)) << 4) + 8 * (tr_cc & 1);
+    const int v_rd_x = tr_i << 6;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+      k_rd[ks] = (lds_cptr)(uintptr_t)((uint32_t)(uintptr_t)&sm.k[0][0] + k_rd_row + ((32 * ks) ^ k_rd_x));
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+      v_rd[dt] = (lds_cptr)(uintptr_t)((uint32_t)(uintptr_t)&sm.v[0][0] + v_rd_row + ((dt << 6) ^ v_rd_x));
+  }
+
+  // scores of the tile in LDS stage `stage`: sacc[kt] += K Q^T over head-dim slices ks_lo..ks_lo+3
+  auto qk_block = [&](int stage, int kt, int ks_lo) {
+#pragma unroll
+    for (int ks = ks_lo; ks < ks_lo + 4; ++ks) {
+      const bf16x8 a = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(
+          k_rd[ks] + stage * kTileB + 32 * kt * kRowB);
+      sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], sacc[kt], 0, 0, 0);
+    }
+  };
+  // O^T += V^T P^T for the 16 keys of block blk of the tile in LDS stage `stage`
+  auto pv_block = [&](int stage, int blk) {
+    const bf16x8 pb = __builtin_bit_cast(bf16x8, pk[blk]);
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) {
+      const u32x2 lo = lds_read_tr3(v_rd[dt] + stage * kTileB + 16 * blk * kRowB);
+      const u32x2 hi = lds_read_tr3(v_rd[dt] + stage * kTileB + (16 * blk + 8) * kRowB);
+      const u32x4 av = {lo[0], lo[1], hi[0], hi[1]};
+      oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pb, oacc[dt], 0, 0, 0);
+    }
+  };
+  // matrix phase: O += P V (V tile in stage SV) interleaved with the scores of the next tile (K in
+  // stage SK).  Only this wave feeds the SIMD's matrix core during the phase, so its LDS operand
+  // reads are scheduled eight MFMAs ahead of their use (sched_group_barrier: 0x008 MFMA, 0x100 LDS read).
+  auto MM_full = [&](int sv, int sk) {
+    __builtin_amdgcn_s_setprio(2);
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) sacc[kt][i] = 0.0f;
+#pragma unroll
+    for (int blk = 0; blk < 4; ++blk) {
+      pv_block(sv, blk);
+      qk_block(sk, blk >> 1, 4 * (blk & 1));
+    }
+    __builtin_amdgcn_sched_group_barrier(0x100, kPrefetchReads, 0);
+#pragma unroll
+    for (int blk = 0; blk < 4; ++blk) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {   // P.V group
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, kPrefetchReads == 12 ? 2 : 1, 0);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {   // score group
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, kPrefetchReads == 12 ? 1 : 2, 0);
+      }
+    }
+    __builtin_amdgcn_s_setprio(0);
+  };
+  auto MM_last = [&](int sv) {   // last tile: no further scores
+    __builtin_amdgcn_s_setprio(2);
+#pragma unroll
+    for (int blk = 0; blk < 4; ++blk) pv_block(sv, blk);
+    __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    }
+    __builtin_amdgcn_s_setprio(0);
+  };
+  // softmax phase: sacc (scores of one tile) -> pk (bf16 P), running reference m and sum l.
+  // Fast path: exponentials are taken against the current reference m without first looking for
+  // the tile's maximum; the row sum then certifies the result: if this lane's sum of P is at most
+  // 2^16, no P exceeded 2^16, which fp32 accumulators and bf16 operands hold comfortably.  Only
+  // when some lane fails that test (always on the first tile, where m = -inf makes every P inf)
+  // does the wave find the true maximum, move m, rescale O and l, and redo the exponentials.
+  // While it runs, the wave also issues its four tile loads (K into stage sk if do_k, V into stage
+  // sv if do_v), spread between the exponential blocks so that the eight waves do not hit the
+  // load path at once.
+  auto exp_block = [&](int kt, int half, float& psum) {
+    float p[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      p[j] = __builtin_amdgcn_exp2f(fmaf(sacc[kt][8 * half + j], scale2, -m));
+      psum += p[j];
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) pk[2 * kt + half][j] = pack_bf16x2(p[2 * j], p[2 * j + 1]);
+    // anchor the block here, between the tile loads that surround it in program order
+    asm volatile("" : "+v"(pk[2 * kt + half]));
+  };
+  auto SM = [&](int sk, int sv, bool do_k, bool do_v) {
+    float psum = 0.0f;
+    // sched_barrier: keep each load between two blocks of arithmetic (the scheduler would
+    // otherwise hoist all four to the top, where they queue behind one another)
+    if (do_k) issue_k_half(kpre, sk, 0);
+    exp_block(0, 0, psum);
+    __builtin_amdgcn_sched_barrier(0);
+    if (do_k) issue_k_half(kpre, sk, 1);
+    exp_block(0, 1, psum);
+    __builtin_amdgcn_sched_barrier(0);
+    if (do_v) issue_v_half(vpre, sv, 0);
+    exp_block(1, 0, psum);
+    __builtin_amdgcn_sched_barrier(0);
+    if (do_v) issue_v_half(vpre, sv, 1);
+    exp_block(1, 1, psum);
+    __builtin_amdgcn_sched_barrier(0);
+    kpre += tileB;
+    vpre += tileB;
+    if (__builtin_amdgcn_ballot_w64(!(psum <= 65536.0f)) != 0ull) {
+      LAB_COUNT_SLOW();
+      float tmax = -INFINITY;
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, sacc[kt][i]);
+      const float m_new = fmaxf(m, xlane32_max(tmax) * scale2);
+      const float alpha = __builtin_amdgcn_exp2f(m - m_new);   // m = -inf (first tile) gives 0
+      m = m_new;
+      lsum *= alpha;
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) oacc[dt][i] *= alpha;
+      psum = 0.0f;
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int half = 0; half < 2; ++half) exp_block(kt, half, psum);
+    }
+    lsum += psum;
+    // pin the results here: without a use in this phase the optimiser sinks the exponentials past
+    // the barrier, next to their first use in the matrix phase
+#pragma unroll
+    for (int blk = 0; blk < 4; ++blk) asm volatile("" : "+v"(pk[blk]));
+    asm volatile("" : "+v"(lsum));
+  };
+
+  // prologue: the first tiles have landed -> scores of tile 0 (group A) / tile 1 (group B)
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+  __builtin_amdgcn_s_barrier();
+  if (grpA || nt > 1) {
+    const int st0 = grpA ? 0 : 1;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) sacc[kt][i] = 0.0f;
+      qk_block(st0, kt, 0);
+      qk_block(st0, kt, 4);
+    }
+  }
+
+  // Phases p = 0..nt, one work-group barrier each.  Group A owns the even tiles, group B the odd
+  // ones: in phase p the owner of tile p runs SM(p) while the other group runs MM(p-1), i.e.
+  // O += P(p-1) V(p-1) and the scores of its next tile p+1.  Both groups execute nt + 1 barriers.
+  //   reads in phase p : V(p-1) from stage (p-1)%3, K(p+1) from stage (p+1)%3
+  //   batch of phase p : K(p+3) -> stage p%3 (last read, as K(p), in phase p-1),
+  //                      V(p+1) -> stage (p+1)%3 (last read, as V(p-2), in phase p-1)
+  //   end of phase p   : the batch of phase p-1 must have landed (first read in phase p+1); the
+  //                      batch of phase p (4 loads if full) may still be in flight
+  auto end_phase = [&](int p) {
+    __builtin_amdgcn_sched_barrier(0);
+    if (p + 3 < nt) __builtin_amdgcn_s_waitcnt(0x0F74);   // vmcnt(4)
+    else __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0)
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto nxt = [](int x) { return x == 2 ? 0 : x + 1; };
+  auto issue_batch = [&](int p, int sp) {   // sp = p % 3; used by the phases without a softmax
+    if (p + 3 < nt) { issue_k_half(kpre, sp, 0); issue_k_half(kpre, sp, 1); }
+    if (p + 1 < nt) { issue_v_half(vpre, nxt(sp), 0); issue_v_half(vpre, nxt(sp), 1); }
+    kpre += tileB;
+    vpre += tileB;
+  };
+  int t = grpA ? 0 : 1;                  // this group's current tile; SM(t) runs in phase t
+  int st = t;                            // t % 3
+  if (!grpA) {                           // phase 0: group B has no scores yet
+    issue_batch(0, 0);
+    end_phase(0);
+  }
+  while (t + 2 < nt) {
+    LAB_STAMP(6 * t);
+    SM(st, nxt(st), t + 3 < nt, true);                   // phase t (t + 1 < nt holds here)
+    LAB_STAMP(6 * t + 1);
+    end_phase(t);
+    LAB_STAMP(6 * t + 2);
+    const int s2 = nxt(nxt(st));                         // (t + 2) % 3
+    MM_full(st, s2);                                     // phase t + 1
+    LAB_STAMP(6 * t + 3);
+    issue_batch(t + 1, nxt(st));
+    LAB_STAMP(6 * t + 4);
+    end_phase(t + 1);
+    LAB_STAMP(6 * t + 5);
+    t += 2;
+    st = s2;
+  }
+  if (t < nt) {                                          // this group's last tile
+    SM(st, nxt(st), false, t + 1 < nt);
+    end_phase(t);
+    MM_last(st);
+    issue_batch(t + 1, nxt(st));
+    end_phase(t + 1);
+    t += 2;
+  }
+  // the group whose last matrix phase was phase nt-1 sits out phase nt
+  if ((grpA && (nt % 2 == 0)) || (!grpA && (nt % 2 == 1))) end_phase(nt);
+
+  // ---- fold group B's partial state into group A's (same queries, disjoint keys) ----------------
+  // all tile reads are behind the last barrier, so the tile buffers are reused for the exchange:
+  // float slot i of wave w, lane l sits at x[(w * 66 + i) * 64 + l]
+  float* xch = reinterpret_cast<float*>(smem_raw);
+  if (!grpA) {
+    float* dst = xch + ((wave - 4) * 66) * 64 + lane;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) dst[(16 * dt + i) * 64] = oacc[dt][i];
+    dst[64 * 64] = m;
+    dst[65 * 64] = lsum;
+  }
+  __syncthreads();
+  if (!grpA) return;
+  {
+    const float* src = xch + (wave * 66) * 64 + lane;
+    const float mB = src[64 * 64], lB = src[65 * 64];
+    const float mm = fmaxf(m, mB);
+    const float wa = (mm == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(m - mm);
+    const float wb = (mm == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(mB - mm);
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) oacc[dt][i] = wa * oacc[dt][i] + wb * src[(16 * dt + i) * 64];
+    lsum = wa * lsum + wb * lB;
+    m = mm;
+  }
+  LAB_WG_END();
+
+  finish_and_store(s, oacc, m, lsum, b, h, q0, n, g);
+}
+
+
 }  // namespace
 
 bool attn_mfma_supported(const AttnStep& s) {
@@ -697,8 +1022,18 @@ usp_status launch_attn_mfma(const AttnStep& s, hipStream_t st) {
   static const hipError_t attr_pp = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_pp_kernel),
                                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(SmemPP));
   USP_CHECK_HIP(attr_pp);
+  static const hipError_t attr_sp = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_pp_split_kernel),
+                                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(SmemPP));
+  USP_CHECK_HIP(attr_sp);
   const bool fast = s.Sc > 0 && s.Sc % kTile == 0 && !s.key_mask && !s.k_scale;
-  if (fast) hipLaunchKernelGGL(attn_mfma_pp_kernel, grid, block, sizeof(SmemPP), st, s);
+  // Few query blocks (a small Q shard of a ring step): 256-query work-groups would leave CUs idle;
+  // 128-query work-groups whose two wave groups split the keys fill twice as many.
+  const int wgs256 = (int)((s.Sq + kQPerWG - 1) / kQPerWG) * s.B * s.H;
+  const bool split = s.variant == 2 || (s.variant == 0 && wgs256 <= kSplitBelowWGs);
+  if (fast && split) {
+    dim3 grid2(wg_grid_size((s.Sq + kQPerWGSplit - 1) / kQPerWGSplit, s.B * s.H));
+    hipLaunchKernelGGL(attn_mfma_pp_split_kernel, grid2, block, sizeof(SmemPP), st, s);
+  } else if (fast) hipLaunchKernelGGL(attn_mfma_pp_kernel, grid, block, sizeof(SmemPP), st, s);
   else hipLaunchKernelGGL(attn_mfma_kernel, grid, block, sizeof(Smem), st, s);
   USP_CHECK_HIP(hipGetLastError());
   return USP_OK;

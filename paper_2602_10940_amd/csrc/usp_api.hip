@@ -101,6 +101,8 @@ usp_status make_plan(const usp_attn_desc* d, Plan* p) {
     USP_CHECK_ARG(d->chunk_len[r] >= 0, "chunk_len[%d]=%d is negative", r, d->chunk_len[r]);
     if (d->chunk_len[r] > p->max_len) p->max_len = d->chunk_len[r];
   }
+  USP_CHECK_ARG(!((d->flags & USP_ATTN_KERNEL_WIDE) && (d->flags & USP_ATTN_KERNEL_SPLIT)),
+                "USP_ATTN_KERNEL_WIDE and USP_ATTN_KERNEL_SPLIT exclude each other");
   p->fp8 = d->kv_dtype == USP_FP8_E4M3FN;
   p->dbuf = (d->flags & USP_ATTN_DOUBLE_BUFFER) != 0 && p->W > 1;
   p->unfused = (d->flags & USP_ATTN_UNFUSED_MERGE) != 0 && p->W > 1;
@@ -295,6 +297,7 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
       a.ks[2] = d; a.ks[1] = (int64_t)len * d; a.ks[0] = (int64_t)desc->H * len * d;
     }
     a.scale = scale;
+    a.variant = (desc->flags & USP_ATTN_KERNEL_SPLIT) ? 2 : ((desc->flags & USP_ATTN_KERNEL_WIDE) ? 1 : 0);
     a.lse = lse;
     a.out = out;
     a.acc = p.W > 1 && !p.unfused ? (float*)(ws + p.off_acc) : nullptr;

@@ -80,6 +80,7 @@ struct AttnStep {
   //                    mode 2 = middle chunk: merge with (acc, lse), write back fp32
   //                    mode 3 = last chunk: merge with (acc, lse), write out in qo_dtype and lse
   int mode;
+  int variant;               // matrix-core fast path: 0 = pick by grid size, 1 = 256-query work-groups, 2 = key-split
   float* acc;                // fp32 [B,H,Sq,d] dense carried O (modes 1-3)
   void* out;                 // qo_dtype by os strides (modes 0, 3)
   float* lse;                // fp32 [B,H,Sq] dense

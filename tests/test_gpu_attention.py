@@ -81,6 +81,28 @@ def test_mfma_small_shapes(Sq, lens):
     _assert_parity(o, l, ro, rl)
 
 
+@pytest.mark.parametrize("variant", ["wide", "split"])
+@pytest.mark.parametrize("Sq,lens", [
+    (128, (64,)), (130, (128,)), (257, (192,)),          # 1, 2, 3 key tiles; ragged query tails
+    (384, (448, 64, 512)), (96, (1152,)),                # odd / even tile counts, several chunks
+])
+def test_mfma_both_work_decompositions(Sq, lens, variant):
+    """Unmasked chunks of whole 64-key tiles run on the ping-pong kernels; force each variant."""
+    P = _P()
+    inp = W.make_attention_inputs(_small_wl("flux1024_u", 3, Sq, lens))
+    flag = P.USP_ATTN_KERNEL_WIDE if variant == "wide" else P.USP_ATTN_KERNEL_SPLIT
+    o, l = _run(inp, flags=flag)
+    ro, rl = _oracle(inp)
+    _assert_parity(o, l, ro, rl)
+
+
+def test_kernel_variant_flags_exclude_each_other():
+    P = _P()
+    inp = W.make_attention_inputs(_small_wl("flux1024_u", 1, 64, (64,)))
+    with pytest.raises(P.UspError):
+        _run(inp, flags=P.USP_ATTN_KERNEL_WIDE | P.USP_ATTN_KERNEL_SPLIT)
+
+
 def test_mfma_matches_generic_kernel_on_fp32_copy():
     """Same bf16-exact values through the fp32 generic kernel: both must sit on the oracle."""
     inp = W.make_attention_inputs(_small_wl("flux1024_u", 2, 200, (150, 90)))
