@@ -726,15 +726,26 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_pp_split_kernel(AttnSte
   auto issue_v_half = [&](const unsigned char* tile, int stage, int half) {
     lds_dma16(tile, half ? vg1 : vg0, lds_v + stage * kTileB + half * 4 * kRowB);
   };
+  // the same rows of the partner wave (w ^ 4): 32 rows away, same swizzle (32 is a multiple of 16)
+  const int64_t pair_g = (grpA ? 32 : -32) * (int64_t)rowB;
+  const int pair_l = (grpA ? 32 : -32) * kRowB;
+  auto issue_k_pair = [&](const unsigned char* tile, int stage, int half) {
+    lds_dma16(tile + pair_g, half ? kg1 : kg0, lds_k + pair_l + stage * kTileB + half * 4 * kRowB);
+  };
+  auto issue_v_pair = [&](const unsigned char* tile, int stage, int half) {
+    lds_dma16(tile + pair_g, half ? vg1 : vg0, lds_v + pair_l + stage * kTileB + half * 4 * kRowB);
+  };
 
-  // Every wave issues one batch of tile loads per phase p: its rows of K(p+3) and V(p+1), both
-  // first read in phase p+2.  Tiles needed before the first batches land are fetched here.
+  // The group in its softmax phase p issues the whole batch of that phase, K(p+3) and V(p+1), both
+  // first read in phase p+2: each wave its own rows and those of its partner in the other group,
+  // whose matrix phase is not to be held up by load issue.  Tiles needed before the first batches
+  // land are fetched here.
   issue_k_half(kb, 0, 0); issue_k_half(kb, 0, 1);
   issue_v_half(vb, 0, 0); issue_v_half(vb, 0, 1);
   if (nt > 1) { issue_k_half(kb + tileB, 1, 0); issue_k_half(kb + tileB, 1, 1); }
   if (nt > 2) { issue_k_half(kb + 2 * tileB, 2, 0); issue_k_half(kb + 2 * tileB, 2, 1); }
-  const unsigned char* kpre = kb + 3 * tileB;   // K(p+3) / V(p+1) for the batch of phase p = 0
-  const unsigned char* vpre = vb + tileB;
+  const unsigned char* kpre = kb + (grpA ? 3 : 4) * tileB;   // K(p+3) / V(p+1) of this group's first
+  const unsigned char* vpre = vb + (grpA ? 1 : 2) * tileB;   // softmax phase, p = 0 (A) or 1 (B)
 
   // Q^T operand: lane (n, g) holds Q[q0+n][16*ks + 8*g .. +7] for ks = 0..7
   bf16x8 qreg[8];
@@ -862,20 +873,20 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_pp_split_kernel(AttnSte
     float psum = 0.0f;
     // sched_barrier: keep each load between two blocks of arithmetic (the scheduler would
     // otherwise hoist all four to the top, where they queue behind one another)
-    if (do_k) issue_k_half(kpre, sk, 0);
+    if (do_v) { issue_v_half(vpre, sv, 0); issue_v_pair(vpre, sv, 0); }
     exp_block(0, 0, psum);
     __builtin_amdgcn_sched_barrier(0);
-    if (do_k) issue_k_half(kpre, sk, 1);
+    if (do_v) { issue_v_half(vpre, sv, 1); issue_v_pair(vpre, sv, 1); }
     exp_block(0, 1, psum);
     __builtin_amdgcn_sched_barrier(0);
-    if (do_v) issue_v_half(vpre, sv, 0);
+    if (do_k) { issue_k_half(kpre, sk, 0); issue_k_pair(kpre, sk, 0); }
     exp_block(1, 0, psum);
     __builtin_amdgcn_sched_barrier(0);
-    if (do_v) issue_v_half(vpre, sv, 1);
+    if (do_k) { issue_k_half(kpre, sk, 1); issue_k_pair(kpre, sk, 1); }
     exp_block(1, 1, psum);
     __builtin_amdgcn_sched_barrier(0);
-    kpre += tileB;
-    vpre += tileB;
+    kpre += 2 * tileB;
+    vpre += 2 * tileB;
     if (__builtin_amdgcn_ballot_w64(!(psum <= 65536.0f)) != 0ull) {
       LAB_COUNT_SLOW();
       float tmax = -INFINITY;
@@ -925,54 +936,43 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_pp_split_kernel(AttnSte
   //   reads in phase p : V(p-1) from stage (p-1)%3, K(p+1) from stage (p+1)%3
   //   batch of phase p : K(p+3) -> stage p%3 (last read, as K(p), in phase p-1),
   //                      V(p+1) -> stage (p+1)%3 (last read, as V(p-2), in phase p-1)
-  //   end of phase p   : the batch of phase p-1 must have landed (first read in phase p+1); the
-  //                      batch of phase p (4 loads if full) may still be in flight
-  auto end_phase = [&](int p) {
+  //   end of phase p   : the batch of phase p-1 must have landed (first read in phase p+1); its
+  //                      issuers are the group now ending a matrix phase, which waits for all of
+  //                      its loads; the other group has only this phase's batch in flight
+  auto end_phase = [&](bool wait_loads) {
     __builtin_amdgcn_sched_barrier(0);
-    if (p + 3 < nt) __builtin_amdgcn_s_waitcnt(0x0F74);   // vmcnt(4)
-    else __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0)
+    if (wait_loads) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
   };
   auto nxt = [](int x) { return x == 2 ? 0 : x + 1; };
-  auto issue_batch = [&](int p, int sp) {   // sp = p % 3; used by the phases without a softmax
-    if (p + 3 < nt) { issue_k_half(kpre, sp, 0); issue_k_half(kpre, sp, 1); }
-    if (p + 1 < nt) { issue_v_half(vpre, nxt(sp), 0); issue_v_half(vpre, nxt(sp), 1); }
-    kpre += tileB;
-    vpre += tileB;
-  };
   int t = grpA ? 0 : 1;                  // this group's current tile; SM(t) runs in phase t
   int st = t;                            // t % 3
-  if (!grpA) {                           // phase 0: group B has no scores yet
-    issue_batch(0, 0);
-    end_phase(0);
-  }
+  if (!grpA) end_phase(false);           // phase 0: group B has no scores yet
   while (t + 2 < nt) {
     LAB_STAMP(6 * t);
     SM(st, nxt(st), t + 3 < nt, true);                   // phase t (t + 1 < nt holds here)
     LAB_STAMP(6 * t + 1);
-    end_phase(t);
+    end_phase(false);
     LAB_STAMP(6 * t + 2);
     const int s2 = nxt(nxt(st));                         // (t + 2) % 3
     MM_full(st, s2);                                     // phase t + 1
     LAB_STAMP(6 * t + 3);
-    issue_batch(t + 1, nxt(st));
     LAB_STAMP(6 * t + 4);
-    end_phase(t + 1);
+    end_phase(true);
     LAB_STAMP(6 * t + 5);
     t += 2;
     st = s2;
   }
   if (t < nt) {                                          // this group's last tile
     SM(st, nxt(st), false, t + 1 < nt);
-    end_phase(t);
+    end_phase(false);
     MM_last(st);
-    issue_batch(t + 1, nxt(st));
-    end_phase(t + 1);
+    end_phase(true);
     t += 2;
   }
   // the group whose last matrix phase was phase nt-1 sits out phase nt
-  if ((grpA && (nt % 2 == 0)) || (!grpA && (nt % 2 == 1))) end_phase(nt);
+  if ((grpA && (nt % 2 == 0)) || (!grpA && (nt % 2 == 1))) end_phase(false);
 
   // ---- fold group B's partial state into group A's (same queries, disjoint keys) ----------------
   // all tile reads are behind the last barrier, so the tile buffers are reused for the exchange:
