@@ -8,9 +8,10 @@ its unpack (usp_fp8_dequant), and attention of the [1, 24, 4608, 128] bf16 shard
 resident in HBM.  `value` is attention TFLOP/s over the whole step time (the FP8
 pack/unpack time is inside the step); per-kernel figures follow in the same JSON line.
 
-Prints ONE JSON line.  Extra legs outside the timed region: the ring-degree-4 shard
-(`flux1024_r4`, merge + side-stream double buffering, hidden fraction), and the
-fp64 oracle timed on the host cores as `cpu_baseline`.
+Prints ONE JSON line.  Extra legs outside the timed region: the ring shards
+(`flux1024_r4`, `flux2048_u2r8`: merge + double buffering over a side stream and with the
+transfers inside the attention launches, hidden fraction), and the fp64 oracle timed on
+the host cores as `cpu_baseline`.
 """
 from __future__ import annotations
 
@@ -152,7 +153,7 @@ def main() -> int:
                            "note": "[36864,3072] in one call; a plain copy kernel reaches ~6.0 TB/s on this GPU"},
         "roofline": {"bound": "mfma", "achieved": round(attn_tflops, 1), "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
-                     "kernel": "attn_mfma_kernel", "flops_per_launch": flops},
+                     "kernel": "attn_mfma_pp_kernel", "flops_per_launch": flops},
     }
 
     if args.calibrate_copy:
@@ -167,7 +168,8 @@ def main() -> int:
 
     # ---------------- ring degree 4: merge + double buffering (not part of `value`) -----------
     if not args.no_ring:
-        result["ring"] = ring_leg(P, W, torch, dev, up_bf16)
+        result["ring"] = ring_leg(P, W, torch, dev, up_bf16, "flux1024_r4")
+        result["ring_flux2048_u2r8"] = ring_leg(P, W, torch, dev, up_bf16, "flux2048_u2r8", reps=300)
 
     # ---------------- oracle on the host cores ------------------------------------------------
     if not args.no_cpu_baseline:
@@ -177,10 +179,11 @@ def main() -> int:
     return 0
 
 
-def ring_leg(P, W, torch, dev, up_bf16, reps=50):
-    """FLUX-1024 ring-degree-4 shard: all chunks resident (T_c), side-stream copies alone (T_m),
-    Algorithm 2 pipelined (T_p), copy-then-compute on one stream (T_s)."""
-    wl = W.WORKLOADS["flux1024_r4"]
+def ring_leg(P, W, torch, dev, up_bf16, name="flux1024_r4", reps=600):
+    """A ring shard: all chunks resident (T_c), the chunk copies alone on the side stream (T_m),
+    Algorithm 2 pipelined with the side stream (T_p), pipelined with the transfers riding in the
+    attention launches (T_f), and copy-then-compute on one stream (T_s)."""
+    wl = W.WORKLOADS[name]
     inp = W.make_attention_inputs(wl)
     q = up_bf16(inp.q)
     ks = [up_bf16(x) for x in inp.k]
@@ -189,13 +192,12 @@ def ring_leg(P, W, torch, dev, up_bf16, reps=50):
     lse = torch.empty((wl.B, wl.H, wl.Sq), dtype=torch.float32, device=dev)
     scale = float(inp.softmax_scale)
     side = torch.cuda.Stream()
-    cur = torch.cuda.current_stream()
     desc = P.make_attn_desc(q, ks, out, scale, P.USP_ATTN_DOUBLE_BUFFER)
     ws = torch.empty((P.usp_ring_attn_workspace_bytes(desc),), dtype=torch.uint8, device=dev)
     stage = [torch.empty_like(ks[0]) for _ in range(4)]
 
     def timed(fn):
-        for _ in range(5):
+        for _ in range(reps // 2):          # also lets the clocks settle
             fn()
         torch.cuda.synchronize()
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -213,6 +215,10 @@ def ring_leg(P, W, torch, dev, up_bf16, reps=50):
         P.usp_ring_attn_fwd(q, ks, vs, softmax_scale=scale, flags=P.USP_ATTN_DOUBLE_BUFFER, out=out, lse=lse,
                             workspace=ws, copy_stream=side)
 
+    def fused():
+        P.usp_ring_attn_fwd(q, ks, vs, softmax_scale=scale, flags=P.USP_ATTN_FUSED_PREFETCH, out=out, lse=lse,
+                            workspace=ws)
+
     def copies_only():
         for r in range(1, wl.W):
             stage[0].copy_(ks[r], non_blocking=True)
@@ -227,15 +233,16 @@ def ring_leg(P, W, torch, dev, up_bf16, reps=50):
             kk.append(stage[2 * (r & 1)]); vv.append(stage[2 * (r & 1) + 1])
         P.usp_ring_attn_fwd(q, kk, vv, softmax_scale=scale, out=out, lse=lse, workspace=ws)
 
-    t_c, t_m, t_p, t_s = timed(resident), timed(copies_only), timed(pipelined), timed(serial)
-    hidden = max(0.0, min(1.0, 1.0 - (t_p - t_c) / t_m)) if t_m > 0 else None
+    t_c, t_m, t_p, t_f, t_s = (timed(f) for f in (resident, copies_only, pipelined, fused, serial))
+    hid = lambda t: round(max(0.0, min(1.0, 1.0 - (t - t_c) / t_m)), 3) if t_m > 0 else None
     flops = wl.attn_flops()
-    return {"workload": "flux1024_r4: Sq=1152, 4 chunks of 1152, H=24 d=128 bf16",
-            "t_compute_ms": round(t_c, 4), "t_copies_ms": round(t_m, 4), "t_pipelined_ms": round(t_p, 4),
-            "t_serial_ms": round(t_s, 4), "hidden_fraction": None if hidden is None else round(hidden, 3),
-            "serial_over_pipelined": round(t_s / t_p, 3),
-            "tflops_resident": round(flops / (t_c * 1e-3) * 1e-12, 1),
-            "tflops_pipelined": round(flops / (t_p * 1e-3) * 1e-12, 1),
+    tf = lambda t: round(flops / (t * 1e-3) * 1e-12, 1)
+    return {"workload": "%s: Sq=%d, %d chunks of %d, H=%d d=%d bf16" % (name, wl.Sq, wl.W, wl.chunk_len[0], wl.H, wl.d),
+            "t_compute_ms": round(t_c, 4), "t_copies_ms": round(t_m, 4),
+            "t_side_stream_ms": round(t_p, 4), "t_fused_prefetch_ms": round(t_f, 4), "t_serial_ms": round(t_s, 4),
+            "hidden_fraction_side_stream": hid(t_p), "hidden_fraction_fused_prefetch": hid(t_f),
+            "serial_over_side_stream": round(t_s / t_p, 3), "serial_over_fused_prefetch": round(t_s / t_f, 3),
+            "tflops_resident": tf(t_c), "tflops_side_stream": tf(t_p), "tflops_fused_prefetch": tf(t_f),
             "note": "on-device copies stand in for ring recv; an xGMI link is ~50x slower"}
 
 

@@ -48,6 +48,11 @@ typedef enum {
 #define USP_ATTN_DOUBLE_BUFFER 1u /* stage chunks 1..W-1 through two internal buffers on copy_stream */
 #define USP_ATTN_UNFUSED_MERGE 2u /* per-chunk (O_i, lse_i) then usp_lse_merge, as Algorithm 2 is written;
                                      default folds the merge into the attention kernel's epilogue */
+#define USP_ATTN_FUSED_PREFETCH 16u /* double buffering without a second stream: the transfer of chunk
+                                      r+1 into the idle internal buffer is done by extra work-groups of
+                                      step r's attention launch on compute_stream (they occupy the CUs
+                                      the attention grid leaves free); copy_stream is ignored.  Excludes
+                                      USP_ATTN_DOUBLE_BUFFER.  Same buffers, same results. */
 /* Work decomposition of the bf16 d=128 matrix-core kernel on unmasked chunks whose length is a
  * multiple of 64.  Default (neither bit): chosen from the number of work-groups the Q shard gives.
  * Both variants meet the same accuracy bar; the bits exist for tuning and for tests. */

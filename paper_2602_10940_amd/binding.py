@@ -19,6 +19,7 @@ USP_OK, USP_ERR_INVALID_ARG, USP_ERR_UNSUPPORTED, USP_ERR_WORKSPACE, USP_ERR_HIP
 USP_F32, USP_BF16, USP_FP8_E4M3FN = 0, 1, 2
 USP_ATTN_DOUBLE_BUFFER, USP_ATTN_UNFUSED_MERGE = 1, 2
 USP_ATTN_KERNEL_WIDE, USP_ATTN_KERNEL_SPLIT = 4, 8
+USP_ATTN_FUSED_PREFETCH = 16
 
 EXPORTS = ("usp_ring_attn_workspace_bytes", "usp_ring_attn_fwd", "usp_lse_merge", "usp_fp8_quant",
            "usp_fp8_dequant", "usp_last_error", "usp_version")

@@ -6,6 +6,7 @@
 //   O_r = softmax(q K^T * scale) V,   lse_r = log sum_j exp(q.k_j * scale)
 // and optionally folds the carried (O, lse) in with the merge equations of section 3.4.
 #include "usp_common.h"
+#include "prefetch_copy.h"
 
 namespace usp {
 namespace {
@@ -40,6 +41,11 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(AttnStep s) {
   __shared__ float q_sh[4][kMaxD];
   __shared__ float p_sh[4][64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (s.copy_wgs > 0 && blockIdx.x >= gridDim.x - s.copy_wgs) {   // prefetch work-groups end the x axis
+    if (blockIdx.y == 0 && blockIdx.z == 0)
+      prefetch_copy(s, blockIdx.x - (gridDim.x - s.copy_wgs), threadIdx.x, 256);
+    return;
+  }
   const int i_raw = blockIdx.x * 4 + wave;  // query row
   const bool valid = i_raw < s.Sq;          // surplus waves recompute the last row, store nothing
   const int i = valid ? i_raw : s.Sq - 1;
@@ -128,12 +134,14 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(AttnStep s) {
 
 }  // namespace
 
-usp_status launch_attn_generic(const AttnStep& s, hipStream_t st) {
+usp_status launch_attn_generic(const AttnStep& step, hipStream_t st) {
+  AttnStep s = step;
   if (s.d > kMaxD) {
     set_error("generic attention kernel supports d <= %d (got %d)", kMaxD, s.d);
     return USP_ERR_UNSUPPORTED;
   }
-  dim3 grid((unsigned)((s.Sq + 3) / 4), (unsigned)s.H, (unsigned)s.B), block(256);
+  s.copy_wgs = s.n_copy > 0 ? 32 : 0;
+  dim3 grid((unsigned)((s.Sq + 3) / 4 + s.copy_wgs), (unsigned)s.H, (unsigned)s.B), block(256);
   if (s.qo_dtype == USP_F32 && s.kv_dtype == USP_F32)
     hipLaunchKernelGGL((attn_generic_kernel<float, float>), grid, block, 0, st, s);
   else if (s.qo_dtype == USP_BF16 && s.kv_dtype == USP_BF16)

@@ -16,6 +16,7 @@
 //   * O and l are rescaled lazily: only when a row max has outgrown the exponent reference.
 //   * exp is taken in base 2 with scale * log2(e) folded into one FMA.
 #include "usp_common.h"
+#include "prefetch_copy.h"
 
 #ifndef LAB_STAMP
 #define LAB_STAMP(slot)
@@ -69,9 +70,9 @@ struct Smem {
 // last item return false.
 constexpr int kXcds = 8;
 constexpr int kSplitBelowWGs = 128;   // use the key-split kernel when 256-query work-groups number at most this
-__device__ __forceinline__ bool wg_to_tile(int nqb, int bh_total, int& bh, int& qb) {
-  const int id = blockIdx.x;
-  const int per_xcd = (int)gridDim.x / kXcds;
+__device__ __forceinline__ bool wg_to_tile(int copy_wgs, int nqb, int bh_total, int& bh, int& qb) {
+  const int id = blockIdx.x;                          // the copy work-groups are the last ids of the grid
+  const int per_xcd = ((int)gridDim.x - copy_wgs) / kXcds;
   const int item = (id % kXcds) * per_xcd + id / kXcds;
   bh = item / nqb;
   qb = item - bh * nqb;
@@ -152,7 +153,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_kernel(AttnStep s) {
   const int lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, g = lane >> 5;
   int bh_, qb_;
-  if (!wg_to_tile((s.Sq + kQPerWG - 1) / kQPerWG, s.B * s.H, bh_, qb_)) return;   // whole work-group
+  if (s.copy_wgs > 0 && blockIdx.x >= gridDim.x - s.copy_wgs) {   // prefetch work-group: copy and leave
+    prefetch_copy(s, blockIdx.x - (gridDim.x - s.copy_wgs), threadIdx.x, kThreads);
+    return;
+  }
+  if (!wg_to_tile(s.copy_wgs, (s.Sq + kQPerWG - 1) / kQPerWG, s.B * s.H, bh_, qb_)) return;   // whole work-group
   const int h = bh_ % s.H, b = bh_ / s.H;
   const int q0 = qb_ * kQPerWG + wave * kQPerWave;
 
@@ -401,7 +406,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_pp_kernel(AttnStep s) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it in an SGPR
   const int n = lane & 31, g = lane >> 5;
   int bh_, qb_;
-  if (!wg_to_tile((s.Sq + kQPerWG - 1) / kQPerWG, s.B * s.H, bh_, qb_)) return;   // whole work-group
+  if (s.copy_wgs > 0 && blockIdx.x >= gridDim.x - s.copy_wgs) {   // prefetch work-group: copy and leave
+    prefetch_copy(s, blockIdx.x - (gridDim.x - s.copy_wgs), threadIdx.x, kThreads);
+    return;
+  }
+  if (!wg_to_tile(s.copy_wgs, (s.Sq + kQPerWG - 1) / kQPerWG, s.B * s.H, bh_, qb_)) return;   // whole work-group
   const int h = bh_ % s.H, b = bh_ / s.H;
   const int q0 = qb_ * kQPerWG + wave * kQPerWave;
   const bool grpA = wave < 4;
@@ -696,7 +705,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_mfma_pp_split_kernel(AttnSte
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it in an SGPR
   const int n = lane & 31, g = lane >> 5;
   int bh_, qb_;
-  if (!wg_to_tile((s.Sq + kQPerWGSplit - 1) / kQPerWGSplit, s.B * s.H, bh_, qb_)) return;   // whole work-group
+  if (s.copy_wgs > 0 && blockIdx.x >= gridDim.x - s.copy_wgs) {   // prefetch work-group: copy and leave
+    prefetch_copy(s, blockIdx.x - (gridDim.x - s.copy_wgs), threadIdx.x, kThreads);
+    return;
+  }
+  if (!wg_to_tile(s.copy_wgs, (s.Sq + kQPerWGSplit - 1) / kQPerWGSplit, s.B * s.H, bh_, qb_)) return;   // whole work-group
   const int h = bh_ % s.H, b = bh_ / s.H;
   const int q0 = qb_ * kQPerWGSplit + (wave & 3) * kQPerWave;   // waves w and w+4 share their 32 queries
   const bool grpA = wave < 4;
@@ -1014,8 +1027,9 @@ bool attn_mfma_supported(const AttnStep& s) {
   return s.qo_dtype == USP_BF16 && s.kv_dtype == USP_BF16 && s.d == kD && s.Sq > 0;
 }
 
-usp_status launch_attn_mfma(const AttnStep& s, hipStream_t st) {
-  dim3 grid(wg_grid_size((s.Sq + kQPerWG - 1) / kQPerWG, s.B * s.H)), block(kThreads);
+usp_status launch_attn_mfma(const AttnStep& step, hipStream_t st) {
+  AttnStep s = step;
+  dim3 block(kThreads);
   static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(Smem));
   USP_CHECK_HIP(attr);
@@ -1028,13 +1042,17 @@ usp_status launch_attn_mfma(const AttnStep& s, hipStream_t st) {
   const bool fast = s.Sc > 0 && s.Sc % kTile == 0 && !s.key_mask && !s.k_scale;
   // Few query blocks (a small Q shard of a ring step): 256-query work-groups would leave CUs idle;
   // 128-query work-groups whose two wave groups split the keys fill twice as many.
-  const int wgs256 = (int)((s.Sq + kQPerWG - 1) / kQPerWG) * s.B * s.H;
-  const bool split = s.variant == 2 || (s.variant == 0 && wgs256 <= kSplitBelowWGs);
+  const unsigned wgs256 = wg_grid_size((s.Sq + kQPerWG - 1) / kQPerWG, s.B * s.H);
+  const bool split = s.variant == 2 || (s.variant == 0 && (int)wgs256 <= kSplitBelowWGs);
   if (fast && split) {
-    dim3 grid2(wg_grid_size((s.Sq + kQPerWGSplit - 1) / kQPerWGSplit, s.B * s.H));
-    hipLaunchKernelGGL(attn_mfma_pp_split_kernel, grid2, block, sizeof(SmemPP), st, s);
-  } else if (fast) hipLaunchKernelGGL(attn_mfma_pp_kernel, grid, block, sizeof(SmemPP), st, s);
-  else hipLaunchKernelGGL(attn_mfma_kernel, grid, block, sizeof(Smem), st, s);
+    const unsigned wgs = wg_grid_size((s.Sq + kQPerWGSplit - 1) / kQPerWGSplit, s.B * s.H);
+    s.copy_wgs = prefetch_wg_count(s, (int)wgs, 1);
+    hipLaunchKernelGGL(attn_mfma_pp_split_kernel, dim3(wgs + s.copy_wgs), block, sizeof(SmemPP), st, s);
+  } else {
+    s.copy_wgs = prefetch_wg_count(s, (int)wgs256, 2);
+    if (fast) hipLaunchKernelGGL(attn_mfma_pp_kernel, dim3(wgs256 + s.copy_wgs), block, sizeof(SmemPP), st, s);
+    else hipLaunchKernelGGL(attn_mfma_kernel, dim3(wgs256 + s.copy_wgs), block, sizeof(Smem), st, s);
+  }
   USP_CHECK_HIP(hipGetLastError());
   return USP_OK;
 }

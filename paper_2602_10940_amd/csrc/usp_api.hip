@@ -37,7 +37,7 @@ struct EventPool {
     if (dev != device) { ev.clear(); next = 0; device = dev; }  // events of another device are abandoned
     if (ev.size() < 64) {
       hipEvent_t x;
-      e = hipEventCreateWithFlags(&x, hipEventDisableTiming);
+      e = hipEventCreateWithFlags(&x, hipEventDisableTiming | hipEventReleaseToDevice);
       if (e != hipSuccess) return e;
       ev.push_back(x);
       *out = x;
@@ -54,6 +54,7 @@ struct Plan {
   int W = 0;
   int max_len = 0;
   bool fp8 = false, dbuf = false, unfused = false, mfma = false, dequant_stage = false;
+  bool fused_pf = false;      // dbuf with the transfers riding in the attention launches
   size_t rows_q = 0;          // B*H*Sq
   size_t off_acc = 0;         // fp32 carried O            (fused, W > 1)
   size_t off_tmp_o = 0;       // per-chunk O_i             (unfused, W > 1)
@@ -104,14 +105,17 @@ usp_status make_plan(const usp_attn_desc* d, Plan* p) {
   USP_CHECK_ARG(!((d->flags & USP_ATTN_KERNEL_WIDE) && (d->flags & USP_ATTN_KERNEL_SPLIT)),
                 "USP_ATTN_KERNEL_WIDE and USP_ATTN_KERNEL_SPLIT exclude each other");
   p->fp8 = d->kv_dtype == USP_FP8_E4M3FN;
-  p->dbuf = (d->flags & USP_ATTN_DOUBLE_BUFFER) != 0 && p->W > 1;
+  USP_CHECK_ARG(!((d->flags & USP_ATTN_DOUBLE_BUFFER) && (d->flags & USP_ATTN_FUSED_PREFETCH)),
+                "USP_ATTN_DOUBLE_BUFFER and USP_ATTN_FUSED_PREFETCH exclude each other");
+  p->dbuf = (d->flags & (USP_ATTN_DOUBLE_BUFFER | USP_ATTN_FUSED_PREFETCH)) != 0 && p->W > 1;
+  p->fused_pf = p->dbuf && (d->flags & USP_ATTN_FUSED_PREFETCH) != 0;
   p->unfused = (d->flags & USP_ATTN_UNFUSED_MERGE) != 0 && p->W > 1;
   p->mfma = d->qo_dtype == USP_BF16 && d->d == 128;
   p->dequant_stage = p->fp8 && p->mfma;
   if (p->fp8 || p->dbuf) {
     for (int r = 0; r < p->W; ++r)
       if (d->chunk_len[r] > 0 && !kv_dense(d, d->chunk_len[r])) {
-        set_error("FP8 K/V and USP_ATTN_DOUBLE_BUFFER need dense [B,H,chunk_len,d] chunks (chunk %d is strided)", r);
+        set_error("FP8 K/V and the double-buffered modes need dense [B,H,chunk_len,d] chunks (chunk %d is strided)", r);
         return USP_ERR_UNSUPPORTED;
       }
   }
@@ -232,7 +236,8 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
     USP_CHECK_ARG((reinterpret_cast<uintptr_t>(workspace) & 255u) == 0, "workspace must be 256-byte aligned");
   }
   hipStream_t cs = (hipStream_t)compute_stream, xs = (hipStream_t)copy_stream;
-  if (p.dbuf) USP_CHECK_ARG(xs != cs, "USP_ATTN_DOUBLE_BUFFER needs a copy_stream different from compute_stream");
+  if (p.dbuf && !p.fused_pf)
+    USP_CHECK_ARG(xs != cs, "USP_ATTN_DOUBLE_BUFFER needs a copy_stream different from compute_stream");
 
   char* ws = (char*)workspace;
   const int d = desc->d;
@@ -258,7 +263,22 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
     USP_CHECK_HIP(hipEventRecord(copied[r], xs));
     return USP_OK;
   };
-  if (p.dbuf) {
+  // The same transfer as a list of segments for the work-groups that ride in step r-1's launch.
+  auto prefetch_segments = [&](int r, AttnStep* a) {
+    const int len = desc->chunk_len[r];
+    char* buf = ws + p.off_buf[(r - 1) & 1];
+    a->n_copy = 0;
+    if (len <= 0) return;
+    const int64_t bytes = (int64_t)desc->B * desc->H * len * d * (int64_t)kv_es;
+    a->copy[a->n_copy++] = {k_chunks[r], buf + p.buf_k, bytes};
+    a->copy[a->n_copy++] = {v_chunks[r], buf + p.buf_v, bytes};
+    if (p.fp8) {
+      const int64_t sb = (int64_t)desc->B * desc->H * len * 4;
+      a->copy[a->n_copy++] = {k_scales[r], buf + p.buf_ks, sb};
+      a->copy[a->n_copy++] = {v_scales[r], buf + p.buf_vs, sb};
+    }
+  };
+  if (p.dbuf && !p.fused_pf) {
     hipEvent_t entry;
     USP_CHECK_HIP(g_events.get(&entry));
     USP_CHECK_HIP(hipEventRecord(entry, cs));            // inputs were produced on the compute stream
@@ -274,11 +294,14 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
     const float* vsp = p.fp8 ? v_scales[r] : nullptr;
     if (p.dbuf && r >= 1) {
       // line 6: the chunk must have arrived; line 7: start the next transfer, which may only
-      // overwrite the other buffer once the step that read it (r-1) has finished.
-      USP_CHECK_HIP(hipStreamWaitEvent(cs, copied[r], 0));
-      if (r + 1 < p.W) {
-        if (r >= 2) USP_CHECK_HIP(hipStreamWaitEvent(xs, computed[r - 1], 0));
-        if ((st = stage_chunk(r + 1)) != USP_OK) return st;
+      // overwrite the other buffer once the step that read it (r-1) has finished.  With the
+      // transfers inside the attention launches, stream order alone gives both.
+      if (!p.fused_pf) {
+        USP_CHECK_HIP(hipStreamWaitEvent(cs, copied[r], 0));
+        if (r + 1 < p.W) {
+          if (r >= 2) USP_CHECK_HIP(hipStreamWaitEvent(xs, computed[r - 1], 0));
+          if ((st = stage_chunk(r + 1)) != USP_OK) return st;
+        }
       }
       char* buf = ws + p.off_buf[(r - 1) & 1];
       kp = buf + p.buf_k;
@@ -296,6 +319,7 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
     if (p.fp8 || (p.dbuf && r >= 1) || kv_auto(desc)) {  // dense chunk
       a.ks[2] = d; a.ks[1] = (int64_t)len * d; a.ks[0] = (int64_t)desc->H * len * d;
     }
+    if (p.fused_pf && r + 1 < p.W) prefetch_segments(r + 1, &a);
     a.scale = scale;
     a.variant = (desc->flags & USP_ATTN_KERNEL_SPLIT) ? 2 : ((desc->flags & USP_ATTN_KERNEL_WIDE) ? 1 : 0);
     a.lse = lse;
@@ -328,7 +352,7 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
                             (const float*)(ws + p.off_tmp_lse), out, lse, cs);
       if (st != USP_OK) return st;
     }
-    if (p.dbuf && r >= 1 && r + 2 < p.W) {  // a later transfer will reuse this step's buffer
+    if (p.dbuf && !p.fused_pf && r >= 1 && r + 2 < p.W) {  // a later transfer will reuse this step's buffer
       USP_CHECK_HIP(g_events.get(&computed[r]));
       USP_CHECK_HIP(hipEventRecord(computed[r], cs));
     }

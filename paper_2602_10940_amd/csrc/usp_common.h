@@ -84,7 +84,23 @@ struct AttnStep {
   float* acc;                // fp32 [B,H,Sq,d] dense carried O (modes 1-3)
   void* out;                 // qo_dtype by os strides (modes 0, 3)
   float* lse;                // fp32 [B,H,Sq] dense
+  // Prefetch carried by this launch (Algorithm 2, the transfer of the next chunk): the last
+  // copy_wgs work-groups of the grid copy the n_copy segments and exit; they are dispatched after
+  // the attention work-groups, onto the CU slots those leave free.  The launcher fills copy_wgs (0 when n_copy == 0).
+  struct CopySeg { const void* src; void* dst; int64_t bytes; };
+  int n_copy;
+  int copy_wgs;
+  CopySeg copy[4];
 };
+// Copy work-groups appended to a launch of attn_wgs attention work-groups, slots_per_cu of which
+// fit on a CU: the CU slots the attention grid leaves free, as a multiple of 8 in [16, 64]
+// (one work-group moves about 50 GB/s).
+inline int prefetch_wg_count(const AttnStep& s, int attn_wgs, int slots_per_cu) {
+  if (s.n_copy <= 0) return 0;
+  const int spare = 256 * slots_per_cu - attn_wgs % (256 * slots_per_cu);
+  const int n = spare / 8 * 8;
+  return n < 16 ? 16 : (n > 64 ? 64 : n);
+}
 usp_status launch_attn_generic(const AttnStep& s, hipStream_t st);
 usp_status launch_attn_mfma(const AttnStep& s, hipStream_t st);
 bool attn_mfma_supported(const AttnStep& s);

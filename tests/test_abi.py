@@ -66,6 +66,14 @@ def test_workspace_sizes_and_descriptor_checks():
     assert b.usp_ring_attn_workspace_bytes(d) == rows * 128 * 4            # fp32 carried O
     d.flags = b.USP_ATTN_DOUBLE_BUFFER
     assert b.usp_ring_attn_workspace_bytes(d) == rows * 128 * 4 + 4 * rows * 128 * 2
+    d.flags = b.USP_ATTN_FUSED_PREFETCH                                    # same two staging buffers
+    assert b.usp_ring_attn_workspace_bytes(d) == rows * 128 * 4 + 4 * rows * 128 * 2
+    for both in (b.USP_ATTN_FUSED_PREFETCH | b.USP_ATTN_DOUBLE_BUFFER,
+                 b.USP_ATTN_KERNEL_WIDE | b.USP_ATTN_KERNEL_SPLIT):
+        d.flags = both
+        with pytest.raises(b.UspError):
+            b.usp_ring_attn_workspace_bytes(d)
+    d.flags = b.USP_ATTN_DOUBLE_BUFFER
     d.kv_dtype = b.USP_FP8_E4M3FN
     fp8 = b.usp_ring_attn_workspace_bytes(d)
     assert fp8 == rows * 128 * 4 + 2 * (2 * rows * 128 + 2 * rows * 4) + 2 * rows * 128 * 2

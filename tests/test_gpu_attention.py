@@ -60,6 +60,9 @@ def test_tiny_fp32_ring2():
     _assert_parity(o, l, ro, rl, fp32=True)
     o2, l2 = _run(inp, flags=2)          # merge as a separate kernel
     _assert_parity(o2, l2, ro, rl, fp32=True)
+    o3, l3 = _run(inp, flags=16)         # chunk 1 staged by work-groups of step 0's launch
+    np.testing.assert_array_equal(o3, o)
+    np.testing.assert_array_equal(l3, l)
 
 
 def _small_wl(name, H, Sq, lens, **kw):
@@ -152,21 +155,31 @@ def test_ring4_fused_unfused_and_double_buffered_agree():
     od, ld = _run(inp, flags=1, copy_stream=side)
     np.testing.assert_array_equal(od, o)        # same kernels, same order: bit-identical
     np.testing.assert_array_equal(ld, l)
+    of, lf = _run(inp, flags=16)                # transfers inside the attention launches
+    np.testing.assert_array_equal(of, o)
+    np.testing.assert_array_equal(lf, l)
+    of2, lf2 = _run(inp, flags=16 | 2)          # ... with the merge as a separate kernel
+    np.testing.assert_array_equal(of2, ou)
+    np.testing.assert_array_equal(lf2, lu)
 
 
-def test_double_buffer_poisoned_staging():
+@pytest.mark.parametrize("flags", [1, 16])
+@pytest.mark.parametrize("lens", [(136,) * 8, (128, 0, 192, 64, 0, 7, 256, 64)])
+def test_double_buffer_poisoned_staging(flags, lens):
     """Fill the workspace with NaN bit patterns first: a chunk consumed before its copy landed
-    (a missing event) would put NaN into O."""
+    (a missing event, a transfer into the wrong buffer) would put NaN into O.  Both transfer
+    modes; equal chunks, and unequal ones with empty chunks, a ragged tail and whole-tile chunks
+    (every attention kernel variant carries a transfer at some step)."""
     P = _P()
-    wl = W.Workload("r8_small", 5, 1, 2, 128, 200, (136,) * 8, "bf16")
+    wl = W.Workload("r8_small", 5, 1, 2, 128, 200, tuple(lens), "bf16")
     inp = W.make_attention_inputs(wl)
     q = dev_bf16(inp.q); ks = [dev_bf16(k) for k in inp.k]; vs = [dev_bf16(v) for v in inp.v]
     out = torch.empty_like(q)
-    desc = P.make_attn_desc(q, ks, out, float(inp.softmax_scale), 1)
+    desc = P.make_attn_desc(q, ks, out, float(inp.softmax_scale), flags)
     ws = torch.full((P.usp_ring_attn_workspace_bytes(desc),), 0xFF, dtype=torch.uint8, device=DEV)
-    side = torch.cuda.Stream()
+    side = torch.cuda.Stream() if flags == 1 else None
     for _ in range(3):
-        o, l = P.usp_ring_attn_fwd(q, ks, vs, softmax_scale=float(inp.softmax_scale), flags=1,
+        o, l = P.usp_ring_attn_fwd(q, ks, vs, softmax_scale=float(inp.softmax_scale), flags=flags,
                                    out=out, workspace=ws, copy_stream=side)
     torch.cuda.synchronize()
     ro, rl = _oracle(inp)
@@ -190,7 +203,7 @@ def test_fp8_kv_ring_against_oracle_on_dequantised_values():
         kx.append(orc.dequant_exact_f64(a.cpu().numpy().reshape(B, H, L, d), sa.cpu().numpy().reshape(B, H, L)))
         vx.append(orc.dequant_exact_f64(b.cpu().numpy().reshape(B, H, L, d), sb.cpu().numpy().reshape(B, H, L)))
     ro, rl = orc.ring_attention(inp.q, kx, vx, float(inp.softmax_scale))
-    for flags, side in ((0, None), (1, torch.cuda.Stream())):
+    for flags, side in ((0, None), (1, torch.cuda.Stream()), (16, None)):
         o, l = P.usp_ring_attn_fwd(q, kq, vq, k_scales=ksc, v_scales=vsc,
                                    softmax_scale=float(inp.softmax_scale), flags=flags, copy_stream=side)
         torch.cuda.synchronize()
