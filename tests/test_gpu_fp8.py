@@ -87,6 +87,52 @@ def test_converter_every_rounding_boundary():
     assert np.all(es == 1.0)
 
 
+def test_converter_exhaustive_every_float32_up_to_448():
+    """Every float32 bit pattern with |x| <= 448, both signs (2.28e9 values), through the row
+    kernel with scale 1.0 (each row starts with 448).  The expected code comes from the oracle:
+    its encoder is a step function of the magnitude, so the 126 smallest float32 values at which
+    it steps (found by bisection on the oracle, and verified on both sides of each step) define
+    it everywhere; the device only looks the values up in that table."""
+    P = _usp()
+    enc = lambda b: int(orc.e4m3fn_encode(np.array([b], np.uint32).view(np.float32))[0])
+    top = 0x43E00000                                   # 448.0f
+    assert enc(top) == 0x7E and enc(0) == 0
+    steps = []
+    for c in range(1, 0x7F):
+        lo, hi = 0, top                                # smallest bits with code >= c
+        while lo < hi:
+            mid = (lo + hi) // 2
+            if enc(mid) >= c:
+                hi = mid
+            else:
+                lo = mid + 1
+        assert enc(lo) == c and enc(lo - 1) == c - 1
+        steps.append(lo)
+    # the oracle really is monotone between its steps (sampled)
+    rng = np.random.Generator(np.random.PCG64(5))
+    sample = np.sort(rng.integers(0, top + 1, 200000).astype(np.uint32))
+    codes = orc.e4m3fn_encode(sample.view(np.float32)).astype(np.int64)
+    assert np.all(np.diff(codes) >= 0)
+    np.testing.assert_array_equal(codes, np.searchsorted(np.array(steps, np.uint32), sample, side="right"))
+
+    steps_d = torch.tensor(steps, dtype=torch.int32, device=DEV)
+    per_row, rows = 2040, 32768
+    lead = torch.zeros((rows, 8), dtype=torch.float32, device=DEV)
+    lead[:, 0] = 448.0
+    for start in range(0, top + 1, per_row * rows):
+        n = min(per_row * rows, top + 1 - start)
+        bits = torch.arange(start, start + per_row * rows, dtype=torch.int32, device=DEV)
+        bits[n:] = 0                                   # past 448: pad with +0
+        want = torch.bucketize(bits, steps_d, right=True).to(torch.uint8).reshape(rows, per_row)
+        mag = bits.view(torch.float32).reshape(rows, per_row)
+        for sign, neg in ((1.0, 0), (-1.0, 0x80)):
+            x = torch.cat([lead, mag * sign], dim=1).contiguous()
+            q, sc = P.usp_fp8_quant(x)
+            assert bool((sc == 1.0).all())
+            bad = (q[:, 8:] != (want | neg)).nonzero()
+            assert bad.numel() == 0, (start, sign, bad[:4].tolist())
+
+
 def test_division_exact_next_to_every_rounding_boundary():
     """Arbitrary scales: for 256 seeded absmax values, every row holds x = fl(mid * s) shifted by
     -2..+2 ulps for each of the 126 midpoints between adjacent E4M3 magnitudes, so x / s lands on
