@@ -62,6 +62,8 @@ struct Plan {
   size_t off_buf[2] = {0, 0}; // staged chunk: K | V | k_scale | v_scale
   size_t buf_k = 0, buf_v = 0, buf_ks = 0, buf_vs = 0;  // offsets inside a staging buffer
   size_t off_deq_k = 0, off_deq_v = 0;  // bf16 K/V after dequantisation (FP8 + MFMA kernel)
+  size_t off_ext = 0, off_nlive = 0;    // per-tile key records and live tile counts (MFMA kernel, masks / scales / ragged chunks)
+  bool ext = false;
   size_t total = 0;
 };
 
@@ -146,6 +148,13 @@ usp_status make_plan(const usp_attn_desc* d, Plan* p) {
   if (p->dequant_stage) {
     p->off_deq_k = off; off += align_up(chunk_elems * 2);
     p->off_deq_v = off; off += align_up(chunk_elems * 2);
+  }
+  if (p->mfma) {
+    // Records are needed by chunks with FP8 scales, a key mask (not known here: assume one) or a
+    // length that is not a multiple of 64; they are small (1 KB per 64 keys of a head).
+    p->ext = true;
+    p->off_ext = off; off += align_up(attn_mfma_ext_bytes(d->B, d->H, p->max_len));
+    p->off_nlive = off; off += align_up((size_t)d->B * 4);
   }
   p->total = off;
   p->valid = true;
@@ -336,14 +345,20 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
     } else a.mode = r == 0 ? 1 : (r == p.W - 1 ? 3 : 2);
 
     if (p.dequant_stage && len > 0) {
-      // Algorithm 1 line 4, split in two so that no rounding is added: the codes are widened to
-      // bf16 exactly here (scale 1), and the MFMA kernel multiplies the fp32 scores and P by the
-      // per-token scales.
+      // Algorithm 1 line 4.  K: the codes are widened to bf16 exactly here (scale 1) and the MFMA
+      // kernel multiplies the fp32 scores by the per-token scales, so the exponents see no rounding
+      // beyond the quantisation itself.  V: dequantised to the working precision, bf16(code * scale).
       const int64_t rows = (int64_t)desc->B * desc->H * len;
       if ((st = launch_fp8_dequant(rows, d, USP_BF16, (const uint8_t*)kp, nullptr, ws + p.off_deq_k, cs)) != USP_OK) return st;
-      if ((st = launch_fp8_dequant(rows, d, USP_BF16, (const uint8_t*)vp, nullptr, ws + p.off_deq_v, cs)) != USP_OK) return st;
+      if ((st = launch_fp8_dequant(rows, d, USP_BF16, (const uint8_t*)vp, vsp, ws + p.off_deq_v, cs)) != USP_OK) return st;
       a.k = ws + p.off_deq_k; a.v = ws + p.off_deq_v;
+      a.v_scale = nullptr;
       a.kv_dtype = USP_BF16;
+    }
+    if (attn_mfma_supported(a) && attn_mfma_needs_ext(a)) {
+      a.ext = (float*)(ws + p.off_ext);
+      a.n_live = (int*)(ws + p.off_nlive);
+      if ((st = launch_attn_ext_prepare(a, cs)) != USP_OK) return st;
     }
     st = attn_mfma_supported(a) ? launch_attn_mfma(a, cs) : launch_attn_generic(a, cs);
     if (st != USP_OK) return st;

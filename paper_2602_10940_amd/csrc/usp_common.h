@@ -80,10 +80,15 @@ struct AttnStep {
   //                    mode 2 = middle chunk: merge with (acc, lse), write back fp32
   //                    mode 3 = last chunk: merge with (acc, lse), write out in qo_dtype and lse
   int mode;
-  int variant;               // matrix-core fast path: 0 = pick by grid size, 1 = 256-query work-groups, 2 = key-split
+  int variant;               // matrix-core kernels: 0 = pick by grid size, 1 = 256-query work-groups, 2 = key-split
   float* acc;                // fp32 [B,H,Sq,d] dense carried O (modes 1-3)
   void* out;                 // qo_dtype by os strides (modes 0, 3)
   float* lse;                // fp32 [B,H,Sq] dense
+  // Matrix-core kernels, chunks with a key mask, FP8 scales or a length that is not a multiple of 64:
+  // per-(batch, head, 64-key tile) records (attn_mfma_ext_bytes) and per-batch live tile counts [B],
+  // filled by launch_attn_ext_prepare on the same stream before the attention launch
+  float* ext;
+  int* n_live;
   // Prefetch carried by this launch (Algorithm 2, the transfer of the next chunk): the last
   // copy_wgs work-groups of the grid copy the n_copy segments and exit; they are dispatched after
   // the attention work-groups, onto the CU slots those leave free.  The launcher fills copy_wgs (0 when n_copy == 0).
@@ -104,5 +109,8 @@ inline int prefetch_wg_count(const AttnStep& s, int attn_wgs, int slots_per_cu) 
 usp_status launch_attn_generic(const AttnStep& s, hipStream_t st);
 usp_status launch_attn_mfma(const AttnStep& s, hipStream_t st);
 bool attn_mfma_supported(const AttnStep& s);
+bool attn_mfma_needs_ext(const AttnStep& s);
+size_t attn_mfma_ext_bytes(int B, int H, int Sc);
+usp_status launch_attn_ext_prepare(const AttnStep& s, hipStream_t st);
 
 }  // namespace usp

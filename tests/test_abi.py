@@ -63,11 +63,14 @@ def test_workspace_sizes_and_descriptor_checks():
     for i, s in enumerate((24 * 1152 * 128, 1152 * 128, 128)):
         d.q_stride[i] = d.o_stride[i] = s
     rows = 24 * 1152
-    assert b.usp_ring_attn_workspace_bytes(d) == rows * 128 * 4            # fp32 carried O
+    # bf16 d=128: per-(head, 64-key tile) records of 1 KB for masks / scales / ragged chunks, plus
+    # one live-tile count per batch entry (256-byte granularity)
+    recs = 24 * (1152 // 64) * 1024 + 256
+    assert b.usp_ring_attn_workspace_bytes(d) == rows * 128 * 4 + recs     # fp32 carried O
     d.flags = b.USP_ATTN_DOUBLE_BUFFER
-    assert b.usp_ring_attn_workspace_bytes(d) == rows * 128 * 4 + 4 * rows * 128 * 2
+    assert b.usp_ring_attn_workspace_bytes(d) == rows * 128 * 4 + 4 * rows * 128 * 2 + recs
     d.flags = b.USP_ATTN_FUSED_PREFETCH                                    # same two staging buffers
-    assert b.usp_ring_attn_workspace_bytes(d) == rows * 128 * 4 + 4 * rows * 128 * 2
+    assert b.usp_ring_attn_workspace_bytes(d) == rows * 128 * 4 + 4 * rows * 128 * 2 + recs
     for both in (b.USP_ATTN_FUSED_PREFETCH | b.USP_ATTN_DOUBLE_BUFFER,
                  b.USP_ATTN_KERNEL_WIDE | b.USP_ATTN_KERNEL_SPLIT):
         d.flags = both
@@ -76,8 +79,12 @@ def test_workspace_sizes_and_descriptor_checks():
     d.flags = b.USP_ATTN_DOUBLE_BUFFER
     d.kv_dtype = b.USP_FP8_E4M3FN
     fp8 = b.usp_ring_attn_workspace_bytes(d)
-    assert fp8 == rows * 128 * 4 + 2 * (2 * rows * 128 + 2 * rows * 4) + 2 * rows * 128 * 2
+    assert fp8 == rows * 128 * 4 + 2 * (2 * rows * 128 + 2 * rows * 4) + 2 * rows * 128 * 2 + recs
     d.n_chunks = 1; d.flags = 0; d.kv_dtype = b.USP_BF16
+    assert b.usp_ring_attn_workspace_bytes(d) == recs
+    d.d = 64                                                               # generic kernel: nothing
+    for i, s in enumerate((24 * 1152 * 64, 1152 * 64, 64)):
+        d.q_stride[i] = d.o_stride[i] = s
     assert b.usp_ring_attn_workspace_bytes(d) == 0
     d.d = 100
     with pytest.raises(b.UspError):

@@ -65,6 +65,9 @@ def test_tiny_fp32_ring2():
     np.testing.assert_array_equal(l3, l)
 
 
+_KERNEL_FLAG = {"auto": 0, "wide": 4, "split": 8}   # USP_ATTN_KERNEL_*
+
+
 def _small_wl(name, H, Sq, lens, **kw):
     base = W.WORKLOADS[name]
     return W.Workload(base.name + "_small", base.seed, 1, H, 128, Sq, tuple(lens), "bf16",
@@ -77,9 +80,10 @@ def _small_wl(name, H, Sq, lens, **kw):
     (33, (1,)), (1, (70,)), (513, (129, 64, 7)),         # degenerate sizes, several chunks
     (128, (0, 96)), (64, (64, 0, 64)),                   # empty chunks
 ])
-def test_mfma_small_shapes(Sq, lens):
+@pytest.mark.parametrize("kernel", ["auto", "wide", "split"])
+def test_mfma_small_shapes(Sq, lens, kernel):
     inp = W.make_attention_inputs(_small_wl("flux1024_u", 2, Sq, lens))
-    o, l = _run(inp)
+    o, l = _run(inp, flags=_KERNEL_FLAG[kernel])
     ro, rl = _oracle(inp)
     _assert_parity(o, l, ro, rl)
 
@@ -116,16 +120,26 @@ def test_mfma_matches_generic_kernel_on_fp32_copy():
     _assert_parity(o32, l32, ro, rl, fp32=True)
 
 
-def test_key_mask_and_fully_masked_rows():
+@pytest.mark.parametrize("kernel", ["wide", "split"])
+def test_key_mask_and_fully_masked_rows(kernel):
+    fl = _KERNEL_FLAG[kernel]
     wl = _small_wl("qwen_r2", 2, 192, (128, 128), masked_keys=(90, 256))   # chunk 1 fully masked
     inp = W.make_attention_inputs(wl)
-    o, l = _run(inp)
+    o, l = _run(inp, flags=fl)
     ro, rl = _oracle(inp)
     _assert_parity(o, l, ro, rl)
     wl2 = _small_wl("qwen_r2", 1, 64, (64, 64), masked_keys=(0, 128))      # nothing left
     inp2 = W.make_attention_inputs(wl2)
-    o2, l2 = _run(inp2)
+    o2, l2 = _run(inp2, flags=fl)
     assert np.all(o2 == 0) and np.all(np.isneginf(l2))
+    # dead keys at the front, in the middle of a tile, and whole dead tiles between live ones
+    wl3 = _small_wl("qwen_r2", 2, 100, (300, 200), masked_keys=(0, 70))
+    inp3 = W.make_attention_inputs(wl3)
+    inp3.key_mask[0][:, 130:260] = 0
+    inp3.key_mask[1][:, 5:9] = 0
+    o3, l3 = _run(inp3, flags=fl)
+    ro3, rl3 = _oracle(inp3)
+    _assert_parity(o3, l3, ro3, rl3)
 
 
 def test_strided_layouts():
@@ -203,7 +217,7 @@ def test_fp8_kv_ring_against_oracle_on_dequantised_values():
         kx.append(orc.dequant_exact_f64(a.cpu().numpy().reshape(B, H, L, d), sa.cpu().numpy().reshape(B, H, L)))
         vx.append(orc.dequant_exact_f64(b.cpu().numpy().reshape(B, H, L, d), sb.cpu().numpy().reshape(B, H, L)))
     ro, rl = orc.ring_attention(inp.q, kx, vx, float(inp.softmax_scale))
-    for flags, side in ((0, None), (1, torch.cuda.Stream()), (16, None)):
+    for flags, side in ((0, None), (1, torch.cuda.Stream()), (16, None), (4, None), (8, None)):
         o, l = P.usp_ring_attn_fwd(q, kq, vq, k_scales=ksc, v_scales=vsc,
                                    softmax_scale=float(inp.softmax_scale), flags=flags, copy_stream=side)
         torch.cuda.synchronize()
