@@ -28,6 +28,9 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2516.6   # 256 CU x 4096 flop/clk x 2.4 GHz (dense, no sparsity)
 PEAK_HBM_GBS = 8000.0
+# HBM bytes of one flux1024_u attention launch (104.1 MB read + 28.8 MB written), from the rocprofv3
+# FETCH_SIZE / WRITE_SIZE runs summarised in profiles/attn_pp_kernel_flux1024_u.md
+ATTN_TRAFFIC_BYTES = 132.9e6
 
 
 def _events(n):
@@ -84,12 +87,15 @@ def main() -> int:
     ss = [torch.empty((R,), dtype=torch.float32, device=dev) for _ in range(NBUF)]
     ys = [torch.empty((R, C), dtype=torch.bfloat16, device=dev) for _ in range(NBUF)]
 
+    desc = P.make_attn_desc(q, [k], out, scale, 0)
+    ws = torch.empty((max(P.usp_ring_attn_workspace_bytes(desc), 256),), dtype=torch.uint8, device=dev)
+
     def step(i, ev=None):
         j = i % NBUF
         P.usp_fp8_quant(xs[j], qs[j], ss[j])
         P.usp_fp8_dequant(qs[j], ss[j], y=ys[j])
         if ev: ev[0].record()
-        P.usp_ring_attn_fwd(q, [k], [v], softmax_scale=scale, out=out, lse=lse)
+        P.usp_ring_attn_fwd(q, [k], [v], softmax_scale=scale, out=out, lse=lse, workspace=ws)
         if ev: ev[1].record()
 
     for i in range(args.warmup):
@@ -152,8 +158,8 @@ def main() -> int:
                            "dequant_gbs": round(8 * fp8_bytes / (t_deq8 * 1e-3) * 1e-9, 1),
                            "note": "[36864,3072] in one call; a plain copy kernel reaches ~6.0 TB/s on this GPU"},
         "roofline": {"bound": "mfma", "achieved": round(attn_tflops, 1), "peak": PEAK_BF16_TFLOPS,
-                     "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
-                     "kernel": "attn_mfma_pp_kernel", "flops_per_launch": flops},
+                     "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4), "traffic": ATTN_TRAFFIC_BYTES,
+                     "kernel": "attn_pp_kernel<wide, plain>", "flops_per_launch": flops},
     }
 
     if args.calibrate_copy:
@@ -170,6 +176,8 @@ def main() -> int:
     if not args.no_ring:
         result["ring"] = ring_leg(P, W, torch, dev, up_bf16, "flux1024_r4")
         result["ring_flux2048_u2r8"] = ring_leg(P, W, torch, dev, up_bf16, "flux2048_u2r8", reps=300)
+
+        result["qwen_r2"] = qwen_leg(P, W, torch, dev, up_bf16)
 
     # ---------------- oracle on the host cores ------------------------------------------------
     if not args.no_cpu_baseline:
@@ -244,6 +252,47 @@ def ring_leg(P, W, torch, dev, up_bf16, name="flux1024_r4", reps=600):
             "serial_over_side_stream": round(t_s / t_p, 3), "serial_over_fused_prefetch": round(t_s / t_f, 3),
             "tflops_resident": tf(t_c), "tflops_side_stream": tf(t_p), "tflops_fused_prefetch": tf(t_f),
             "note": "on-device copies stand in for ring recv; an xGMI link is ~50x slower"}
+
+
+def qwen_leg(P, W, torch, dev, up_bf16, reps=200):
+    """Qwen-Image-like shard: FP8 K/V chunks (quantised here by usp_fp8_quant) with per-token scales
+    and the key mask of the padded text tokens; all chunks resident."""
+    wl = W.WORKLOADS["qwen_r2"]
+    inp = W.make_attention_inputs(wl, heads=wl.H)
+    q = up_bf16(inp.q)
+    kq, ksc, vq, vsc = [], [], [], []
+    for k, v in zip(inp.k, inp.v):
+        B, H, L, d = k.shape
+        a, sa = P.usp_fp8_quant(up_bf16(k).reshape(B * H * L, d))
+        b, sb = P.usp_fp8_quant(up_bf16(v).reshape(B * H * L, d))
+        kq.append(a.reshape(B, H, L, d)); ksc.append(sa.reshape(B, H, L))
+        vq.append(b.reshape(B, H, L, d)); vsc.append(sb.reshape(B, H, L))
+    km = [torch.from_numpy(m).to(dev) for m in inp.key_mask]
+    out = torch.empty_like(q)
+    lse = torch.empty((wl.B, wl.H, wl.Sq), dtype=torch.float32, device=dev)
+    scale = float(inp.softmax_scale)
+    desc = P.make_attn_desc(q, kq, out, scale, 0)
+    ws = torch.empty((P.usp_ring_attn_workspace_bytes(desc),), dtype=torch.uint8, device=dev)
+
+    def call():
+        P.usp_ring_attn_fwd(q, kq, vq, k_scales=ksc, v_scales=vsc, key_mask=km, softmax_scale=scale,
+                            out=out, lse=lse, workspace=ws)
+    for _ in range(reps // 2):
+        call()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(reps):
+        call()
+    b.record()
+    torch.cuda.synchronize()
+    ms = a.elapsed_time(b) / reps
+    live = sum(int(m[0].sum()) for m in inp.key_mask)
+    return {"workload": "qwen_r2: Sq=4096, 2 chunks of 4096 FP8 E4M3 K/V + per-token scales, H=24 d=128, %d of %d keys live"
+                        % (live, wl.S),
+            "ms": round(ms, 4), "tflops_nominal": round(wl.attn_flops() / (ms * 1e-3) * 1e-12, 1),
+            "tflops_live_keys": round(wl.attn_flops() * live / wl.S / (ms * 1e-3) * 1e-12, 1),
+            "includes": "record preparation, FP8 widening of K and dequantisation of V, attention, merge"}
 
 
 def cpu_baseline(W, wl, heads=24):

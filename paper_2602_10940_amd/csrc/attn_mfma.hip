@@ -519,6 +519,33 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
     // anchor the block here, between the tile loads that surround it in program order
     asm volatile("" : "+v"(pk[2 * kt + half]));
   };
+  // largest exponent argument (before the reference is subtracted) of this lane's query over the tile
+  auto tile_max = [&](int xs) -> float {
+    float tmax = -INFINITY;
+    if (!kExt) {
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, sacc[kt][i]);
+      return xlane32_max(tmax) * scale2;
+    }
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        const f32x4 c = x_vec(xs, 0, kt, a), bias = x_vec(xs, 1, kt, a);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) tmax = fmaxf(tmax, fmaf(sacc[kt][4 * a + e], c[e], bias[e]));
+      }
+    return xlane32_max(tmax);
+  };
+  // Tiles still to be handled maximum-first (wave-uniform).  After a failed certification with a
+  // reference already in place, the next kMaxFirstTiles softmax phases of the wave find the tile's
+  // maximum before the exponentials and move the reference if it is outgrown by more than 2^8; every
+  // such move re-arms the counter.  Scores with heavy tails then cost one maximum pass per tile
+  // instead of a second round of exponentials on most tiles; ordinary scores never arm it.
+  constexpr int kMaxFirstTiles = 8;
+  int max_first = 0;
   // SM of the tile whose record sits in stage xs; loads K tile kpre_idx into stage sk (if do_k, with
   // the record of tile xpre_idx into stage xst if do_x) and V tile vpre_idx into stage sv (if do_v)
   auto SM = [&](int xs, int sk, int sv, bool do_k, bool do_v, bool do_x, int xpre_idx, int xst) {
@@ -529,6 +556,22 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
           (lds_cptr)(uintptr_t)(lds_ext + xs * kExtTileB + 512));
       x_load(0, xs, 0, 0);
       dead_keys = __builtin_amdgcn_readfirstlane(__float_as_uint(f)) != 0u;
+    }
+    if (max_first > 0) {
+      --max_first;
+      const float tmax = tile_max(xs);
+      const bool jump = tmax > m + 8.0f;
+      if (__builtin_amdgcn_ballot_w64(jump) != 0ull) {
+        const float alpha = jump ? __builtin_amdgcn_exp2f(m - tmax) : 1.0f;   // m = -inf gives 0
+        m = jump ? tmax : m;
+        lsum *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) oacc[dt][i] *= alpha;
+        max_first = kMaxFirstTiles;
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
     // sched_barrier: keep each load between two blocks of arithmetic (the scheduler would
     // otherwise hoist all of them to the top, where they queue behind one another)
@@ -565,24 +608,10 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
     vpre += kPreStep * tileB; vpre_idx += kPreStep;
     if (__builtin_amdgcn_ballot_w64(!(psum <= 65536.0f)) != 0ull) {
       LAB_COUNT_SLOW();
-      float tmax = -INFINITY;
-      if (!kExt) {
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, sacc[kt][i]);
-        tmax = xlane32_max(tmax) * scale2;
-      } else {
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-          for (int a = 0; a < 4; ++a) {
-            const f32x4 c = x_vec(xs, 0, kt, a), bias = x_vec(xs, 1, kt, a);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) tmax = fmaxf(tmax, fmaf(sacc[kt][4 * a + e], c[e], bias[e]));
-          }
-        tmax = xlane32_max(tmax);
-      }
+      // a reference that was already set and still failed: scores with heavy tails; look for the
+      // maximum first on the next tiles instead of paying for the exponentials twice
+      if (__builtin_amdgcn_ballot_w64(m != -INFINITY) != 0ull) max_first = kMaxFirstTiles;
+      const float tmax = tile_max(xs);
       const float m_new = fmaxf(m, tmax);
       // m = -inf (first live tile) gives alpha 0; no live key so far: nothing to rescale, P = 0
       const float alpha = m_new == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(m - m_new);
