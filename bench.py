@@ -133,6 +133,19 @@ def main() -> int:
     t_deq8 = per_launch(lambda i: P.usp_fp8_dequant(qb, sb, y=yb), reps=100)
     del xb, qb, sb, yb
 
+    # standalone merge (the second line under Algorithm 2) on the flux1024_r4 state: 27648 rows x 128,
+    # rotating over 8 buffer sets (8 x 21.5 MB x ... beyond what one launch touches, inside the cache)
+    mrows = 24 * 1152
+    mo1 = [torch.randn((mrows, 128), device=dev).to(torch.bfloat16) for _ in range(8)]
+    mo2 = [torch.randn((mrows, 128), device=dev).to(torch.bfloat16) for _ in range(8)]
+    ml1 = [torch.randn((mrows,), device=dev) for _ in range(8)]
+    ml2 = [torch.randn((mrows,), device=dev) for _ in range(8)]
+    mo = [torch.empty_like(x) for x in mo1]
+    ml = [torch.empty_like(x) for x in ml1]
+    t_merge = per_launch(lambda i: P.usp_lse_merge(mo1[i % 8], ml1[i % 8], mo2[i % 8], ml2[i % 8], mo[i % 8], ml[i % 8]))
+    merge_bytes = mrows * 128 * 3 * 2 + mrows * 12
+    del mo1, mo2, ml1, ml2, mo, ml
+
     flops = wl.attn_flops()
     value = flops / (ms_per_step * 1e-3) * 1e-12
     attn_tflops = flops / (t_attn * 1e-3) * 1e-12
@@ -157,6 +170,8 @@ def main() -> int:
                            "quant_gbs": round(8 * fp8_bytes / (t_quant8 * 1e-3) * 1e-9, 1),
                            "dequant_gbs": round(8 * fp8_bytes / (t_deq8 * 1e-3) * 1e-9, 1),
                            "note": "[36864,3072] in one call; a plain copy kernel reaches ~6.0 TB/s on this GPU"},
+        "lse_merge": {"us": round(t_merge * 1e3, 2), "gbs": round(merge_bytes / (t_merge * 1e-3) * 1e-9, 1),
+                      "bytes": merge_bytes, "note": "flux1024_r4 state [27648,128] bf16, cache-warm (21 MB per launch)"},
         "roofline": {"bound": "mfma", "achieved": round(attn_tflops, 1), "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4), "traffic": ATTN_TRAFFIC_BYTES,
                      "kernel": "attn_pp_kernel<wide, plain>", "flops_per_launch": flops},
