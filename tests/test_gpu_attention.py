@@ -142,6 +142,44 @@ def test_key_mask_and_fully_masked_rows(kernel):
     _assert_parity(o3, l3, ro3, rl3)
 
 
+@pytest.mark.parametrize("kernel", ["wide", "split"])
+def test_batch_of_three_with_a_different_mask_per_entry(kernel):
+    """B = 3: every batch entry has its own key mask (different live tile counts, one entry with
+    trailing dead tiles only, one fully dead second chunk), FP8 K/V with per-(b,h,token) scales on
+    one pass and plain bf16 on the other; also a ring of plain chunks in every transfer mode."""
+    P = _P()
+    wl = W.Workload("b3", 11, 3, 2, 128, 150, (200, 136), "bf16", masked_keys=(100, 336))
+    inp = W.make_attention_inputs(wl)
+    inp.key_mask[0][0, :] = 1; inp.key_mask[1][0, :] = 1          # entry 0: nothing masked
+    inp.key_mask[0][1, :] = 1; inp.key_mask[0][1, 3:70] = 0      # entry 1: a hole in chunk 0, chunk 1 dead
+    inp.key_mask[0][2, 64:] = 0; inp.key_mask[1][2, :] = 0        # entry 2: only the first tile lives
+    inp.key_mask[1][2, 5] = 1                                     # ... and one key of chunk 1
+    fl = _KERNEL_FLAG[kernel]
+    o, l = _run(inp, flags=fl)
+    ro, rl = _oracle(inp)
+    _assert_parity(o, l, ro, rl)
+    for extra in (16, 2):                                         # fused prefetch, unfused merge
+        o2, l2 = _run(inp, flags=fl | extra)
+        _assert_parity(o2, l2, ro, rl)
+    # FP8 K/V of the same values
+    q = dev_bf16(inp.q)
+    kq, ksc, vq, vsc, kx, vx = [], [], [], [], [], []
+    for k, v in zip(inp.k, inp.v):
+        B, H, L, d = k.shape
+        a, sa = P.usp_fp8_quant(dev_bf16(k).reshape(B * H * L, d))
+        b, sb = P.usp_fp8_quant(dev_bf16(v).reshape(B * H * L, d))
+        kq.append(a.reshape(B, H, L, d)); ksc.append(sa.reshape(B, H, L))
+        vq.append(b.reshape(B, H, L, d)); vsc.append(sb.reshape(B, H, L))
+        kx.append(orc.dequant_exact_f64(a.cpu().numpy().reshape(B, H, L, d), sa.cpu().numpy().reshape(B, H, L)))
+        vx.append(orc.dequant_exact_f64(b.cpu().numpy().reshape(B, H, L, d), sb.cpu().numpy().reshape(B, H, L)))
+    km = [torch.from_numpy(m).to(DEV) for m in inp.key_mask]
+    fo, fl_ = P.usp_ring_attn_fwd(q, kq, vq, k_scales=ksc, v_scales=vsc, key_mask=km,
+                                  softmax_scale=float(inp.softmax_scale), flags=fl | 16)
+    torch.cuda.synchronize()
+    ro8, rl8 = orc.ring_attention(inp.q, kx, vx, float(inp.softmax_scale), inp.key_mask)
+    _assert_parity(host_f64(fo), host_f64(fl_), ro8, rl8)
+
+
 def test_strided_layouts():
     """[B,S,H,d] storage viewed as [B,H,S,d]: token stride H*d, head stride d."""
     P = _P()
