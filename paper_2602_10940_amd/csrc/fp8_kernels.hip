@@ -162,6 +162,56 @@ __global__ __launch_bounds__(256) void fp8_quant_longrow_kernel(const T* __restr
   }
 }
 
+// ---- few, very long rows (per-tensor scale = one row: Algorithm 1 as printed): a row is cut into
+// chunks so that the whole chip works on it.  Three steps on the stream: scales[row] <- 0; every
+// chunk folds its |x| maximum into scales[row] (non-negative floats order like their bit patterns,
+// so an unsigned atomic max does it); every chunk is cast with the row's scale, computed from that
+// maximum by the same arithmetic as in the other kernels; scales[row] <- scale.
+__global__ void fp8_fill_kernel(float* dst, int64_t n, float value) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = value;
+}
+template <typename T>
+__global__ __launch_bounds__(256) void fp8_absmax_chunks_kernel(const T* __restrict__ x, float* __restrict__ scales,
+                                                                int64_t units, int64_t chunk_units) {
+  __shared__ float red[4];
+  const int64_t row = blockIdx.y;
+  const int64_t u0 = (int64_t)blockIdx.x * chunk_units, u1 = min(u0 + chunk_units, units);
+  const T* xr = x + row * units * 8;
+  float a = 0.0f;
+  for (int64_t u = u0 + threadIdx.x; u < u1; u += 256) {
+    float v[8];
+    load8(xr + u * 8, v);
+    a = absmax8(v, a);
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) a = fmaxf(a, __shfl_xor(a, off, 64));
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = a;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    a = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    atomicMax(reinterpret_cast<unsigned int*>(scales + row), __float_as_uint(a));
+  }
+}
+template <typename T>
+__global__ __launch_bounds__(256) void fp8_quant_chunks_kernel(const T* __restrict__ x, uint8_t* __restrict__ q,
+                                                               const float* __restrict__ absmax,
+                                                               int64_t units, int64_t chunk_units) {
+  const int64_t row = blockIdx.y;
+  const int64_t u0 = (int64_t)blockIdx.x * chunk_units, u1 = min(u0 + chunk_units, units);
+  const int64_t base = row * units * 8;
+  const RowDiv d = make_rowdiv(scale_from_absmax(absmax[row]));
+  for (int64_t u = u0 + threadIdx.x; u < u1; u += 256) {
+    float v[8];
+    load8(x + base + u * 8, v);
+    *reinterpret_cast<uint2*>(q + base + u * 8) = d.fast ? encode8<true>(v, d) : encode8<false>(v, d);
+  }
+}
+__global__ void fp8_scales_from_absmax_kernel(float* scales, int64_t rows) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < rows) scales[i] = scale_from_absmax(scales[i]);
+}
+
 // all-zero-column case: scales still have to be defined
 __global__ void fp8_fill_scales_kernel(float* scales, int64_t rows) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -231,8 +281,20 @@ usp_status quant_dispatch(int64_t rows, int64_t cols, const T* x, uint8_t* q, fl
     hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 64, 6>), dim3(blocks(1)), dim3(256), 0, st, x, q, scales, rows, (int)units);
   } else if (units <= 512) {
     hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 64, 8>), dim3(blocks(1)), dim3(256), 0, st, x, q, scales, rows, (int)units);
-  } else {
+  } else if (rows >= 1024 || rows * units < 4096 * 8) {
     hipLaunchKernelGGL((fp8_quant_longrow_kernel<T>), dim3((unsigned)rows), dim3(256), 0, st, x, q, scales, units);
+  } else {
+    // too few rows to fill the chip with one block per row: about 2048 chunks of whole 256-unit strides
+    const int64_t per_row = (2048 + rows - 1) / rows;
+    int64_t chunk_units = (units + per_row - 1) / per_row;
+    chunk_units = (chunk_units + 255) / 256 * 256;
+    if (chunk_units < 1024) chunk_units = 1024;
+    const dim3 grid((unsigned)((units + chunk_units - 1) / chunk_units), (unsigned)rows);
+    const unsigned rb = (unsigned)((rows + 255) / 256);
+    hipLaunchKernelGGL(fp8_fill_kernel, dim3(rb), dim3(256), 0, st, scales, rows, 0.0f);
+    hipLaunchKernelGGL((fp8_absmax_chunks_kernel<T>), grid, dim3(256), 0, st, x, scales, units, chunk_units);
+    hipLaunchKernelGGL((fp8_quant_chunks_kernel<T>), grid, dim3(256), 0, st, x, q, scales, units, chunk_units);
+    hipLaunchKernelGGL(fp8_scales_from_absmax_kernel, dim3(rb), dim3(256), 0, st, scales, rows);
   }
   USP_CHECK_HIP(hipGetLastError());
   return USP_OK;

@@ -215,6 +215,43 @@ def test_ring4_fused_unfused_and_double_buffered_agree():
     np.testing.assert_array_equal(lf2, lu)
 
 
+@pytest.mark.parametrize("flags", [0, 16, 2])
+def test_ring_call_replays_from_a_hip_graph(flags):
+    """The library allocates nothing and clears nothing with memset nodes, so a ring call can be
+    captured into a HIP graph.  Every replay (with eager calls and synchronisations of the program
+    in between, outputs scrubbed first) must reproduce the eager result bit for bit."""
+    P = _P()
+    wl = W.Workload("r4_graph", 12, 1, 3, 128, 200, (192, 64, 100, 128), "bf16")
+    inp = W.make_attention_inputs(wl)
+    q = dev_bf16(inp.q); ks = [dev_bf16(k) for k in inp.k]; vs = [dev_bf16(v) for v in inp.v]
+    out = torch.empty_like(q)
+    lse = torch.empty((1, 3, 200), dtype=torch.float32, device=DEV)
+    desc = P.make_attn_desc(q, ks, out, float(inp.softmax_scale), flags)
+    ws = torch.empty((P.usp_ring_attn_workspace_bytes(desc),), dtype=torch.uint8, device=DEV)
+    call = lambda: P.usp_ring_attn_fwd(q, ks, vs, softmax_scale=float(inp.softmax_scale), flags=flags,
+                                       out=out, lse=lse, workspace=ws)
+    call()
+    torch.cuda.synchronize()
+    ref_o, ref_l = out.clone(), lse.clone()
+    ro, rl = _oracle(inp)
+    _assert_parity(host_f64(ref_o), host_f64(ref_l), ro, rl)
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            call()
+    torch.cuda.synchronize()
+    for _ in range(3):
+        out.zero_(); lse.zero_(); ws.fill_(0xFF)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref_o) and torch.equal(lse, ref_l)
+        call()                                   # eager work of the program between replays
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref_o) and torch.equal(lse, ref_l)
+
+
 @pytest.mark.parametrize("flags", [1, 16])
 @pytest.mark.parametrize("lens", [(136,) * 8, (128, 0, 192, 64, 0, 7, 256, 64)])
 def test_double_buffer_poisoned_staging(flags, lens):

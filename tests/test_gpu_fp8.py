@@ -37,6 +37,8 @@ def _check_quant(x32, dtype):
     (3, 4104, "bf16"), (2, 20000, "bf16"),      # long-row kernel
     (1, 65536, "bf16"),                          # per-tensor scale = one row
     (1001, 128, "bf16"),                         # ring K/V view, ragged row count
+    (1, 1 << 22, "bf16"), (3, 500008, "f32"),    # few very long rows: chunked over the whole chip
+    (600, 8200, "bf16"), (1030, 4104, "bf16"),   # both sides of the rows threshold of that path
 ])
 def test_quant_bit_exact(rows, cols, dtype):
     x = W.make_matrix(100 + rows + cols, rows, cols, dtype, "wide" if rows % 2 else "normal")
