@@ -664,13 +664,24 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
     // A wave waits for its own tile loads at the end of its softmax phases: the batch issued one
     // softmax phase earlier must have landed, the batch just issued (if full: 4 loads, 5 with a
     // record) may be in flight.
-    auto phase_barrier = [&](int wait_mode) {   // 0: no wait, 1: all but the last full batch, 2: vmcnt(0)
+    // Only the barrier in front of A's matrix phase / B's softmax phase is needed (kOneBarrier): with
+    // three stages no load of the half-period after it overwrites what that half-period or the one
+    // before the next barrier still reads, and every tile is waited for by its loaders before the
+    // barrier in front of its first reader.  The second barrier only kept the groups in step, which
+    // equal phase lengths do by themselves.  (The key records are read in the softmax phases of both
+    // halves; with three stages they need both barriers.)
+#ifdef USP_TWO_BARRIERS
+    constexpr bool kOneBarrier = false;
+#else
+    constexpr bool kOneBarrier = !kExt;
+#endif
+    auto phase_barrier = [&](int wait_mode, bool needed = true) {   // 0: no wait, 1: all but the last full batch, 2: vmcnt(0)
       __builtin_amdgcn_sched_barrier(0);
       if (wait_mode == 1) {
         if (kExt && grpA) __builtin_amdgcn_s_waitcnt(0x0F75);   // vmcnt(5)
         else __builtin_amdgcn_s_waitcnt(0x0F74);                // vmcnt(4)
       } else if (wait_mode == 2) __builtin_amdgcn_s_waitcnt(0x0F70);
-      __builtin_amdgcn_s_barrier();
+      if (needed || !kOneBarrier) __builtin_amdgcn_s_barrier();
       __builtin_amdgcn_sched_barrier(0);
     };
     int st = 0;                            // LDS stage of tile j, j % 3
@@ -686,21 +697,21 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
         LAB_STAMP(6 * j + 3);
         MM_full(st, s1);
         LAB_STAMP(6 * j + 5);
-        phase_barrier(0);
+        phase_barrier(0, false);
         st = s1;
       }
       SM(st, 0, 0, false, false, false, 0, 0);
       phase_barrier(2);
       MM_last(st);
+      phase_barrier(0, false);
       phase_barrier(0);
-      phase_barrier(0);
-      phase_barrier(0);
+      phase_barrier(0, false);
     } else {
       // tile j: phase 2j = MM(j-1) with V(j-1) in stage st-1, K(j) in stage st;
       //         phase 2j+1 = SM(j), prefetching K(j+3) -> stage st, V(j+2) -> stage st+2
       phase_barrier(0);                                 // phase 0: nothing to do yet
       SM(0, 0, 2, 3 < nt, 2 < nt, false, 0, 0);         // phase 1 (tile 0)
-      phase_barrier(3 < nt ? 1 : 2);
+      phase_barrier(3 < nt ? 1 : 2, false);
       for (int j = 1; j < nt; ++j) {
         const int sp = st;                              // stage of tile j-1
         st = nxt(st);
@@ -711,11 +722,11 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
         LAB_STAMP(6 * j + 3);
         SM(st, st, sp, j + 3 < nt, j + 2 < nt, false, 0, 0);   // st+2 == sp (mod 3)
         LAB_STAMP(6 * j + 5);
-        phase_barrier(j + 3 < nt ? 1 : 2);
+        phase_barrier(j + 3 < nt ? 1 : 2, false);
       }
       MM_last(st);
       phase_barrier(0);
-      phase_barrier(0);
+      phase_barrier(0, false);
     }
   } else {
     // scores of tile 0 (group A) / tile 1 (group B)
