@@ -55,10 +55,13 @@ typedef enum {
                                       USP_ATTN_DOUBLE_BUFFER.  Same buffers, same results. */
 /* Work decomposition of the bf16 d=128 matrix-core kernel on unmasked chunks whose length is a
  * multiple of 64.  Default (neither bit): chosen from the number of work-groups the Q shard gives.
- * Both variants meet the same accuracy bar; the bits exist for tuning and for tests. */
+ * All variants meet the same accuracy bar; the bits exist for tuning and for tests. */
 #define USP_ATTN_KERNEL_WIDE 4u   /* 256 queries per work-group, every wave visits every key */
 #define USP_ATTN_KERNEL_SPLIT 8u  /* 128 queries per work-group, the two wave groups take alternate
                                      64-key tiles and combine their partial results at the end */
+#define USP_ATTN_KERNEL_MIXED 32u /* one launch of both: 256-query work-groups, and the blocks of the
+                                     last, partly filled round as pairs of key-split work-groups
+                                     (forced: the second half of all blocks) */
 
 /*
  * Shape of one ring-attention call (paper section 2.2: Q, K, V are [B, H, S, D]).

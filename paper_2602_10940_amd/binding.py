@@ -20,6 +20,7 @@ USP_F32, USP_BF16, USP_FP8_E4M3FN = 0, 1, 2
 USP_ATTN_DOUBLE_BUFFER, USP_ATTN_UNFUSED_MERGE = 1, 2
 USP_ATTN_KERNEL_WIDE, USP_ATTN_KERNEL_SPLIT = 4, 8
 USP_ATTN_FUSED_PREFETCH = 16
+USP_ATTN_KERNEL_MIXED = 32
 
 EXPORTS = ("usp_ring_attn_workspace_bytes", "usp_ring_attn_fwd", "usp_lse_merge", "usp_fp8_quant",
            "usp_fp8_dequant", "usp_last_error", "usp_version")

@@ -243,22 +243,16 @@ __global__ __launch_bounds__(64) void attn_ext_prepare_kernel(AttnStep s, float*
   }
 }
 
+// One work-group's share: the queries q_base .. q_base + 255 (wide) or + 127 (split) of (batch, head) bh_.
 template <bool kSplit, bool kExt>
-__device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* smem_raw) {
+__device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* smem_raw, int bh_, int q_base) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it in an SGPR
   const int n = lane & 31, g = lane >> 5;
-  constexpr int kQBlock = kSplit ? kQPerWGSplit : kQPerWG;
-  if (s.copy_wgs > 0 && blockIdx.x >= gridDim.x - s.copy_wgs) {   // prefetch work-group: copy and leave
-    prefetch_copy(s, blockIdx.x - (gridDim.x - s.copy_wgs), threadIdx.x, kThreads);
-    return;
-  }
-  int bh_, qb_;
-  if (!wg_to_tile(s.copy_wgs, (s.Sq + kQBlock - 1) / kQBlock, s.B * s.H, bh_, qb_)) return;   // whole work-group
   const int h = bh_ % s.H, b = bh_ / s.H;
   // split: waves w and w+4 share their 32 queries
-  const int q0 = qb_ * kQBlock + (kSplit ? (wave & 3) : wave) * kQPerWave;
+  const int q0 = q_base + (kSplit ? (wave & 3) : wave) * kQPerWave;
   const bool grpA = wave < 4;
   LAB_WG_START();
 
@@ -811,7 +805,49 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
 template <bool kSplit, bool kExt>
 __global__ __launch_bounds__(kThreads, 2) void attn_pp_kernel(AttnStep s) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  attn_pp_body<kSplit, kExt>(s, smem_raw);
+  if (s.copy_wgs > 0 && blockIdx.x >= gridDim.x - s.copy_wgs) {   // prefetch work-group: copy and leave
+    prefetch_copy(s, blockIdx.x - (gridDim.x - s.copy_wgs), threadIdx.x, kThreads);
+    return;
+  }
+  constexpr int kQBlock = kSplit ? kQPerWGSplit : kQPerWG;
+  int bh_, qb_;
+  if (!wg_to_tile(s.copy_wgs, (s.Sq + kQBlock - 1) / kQBlock, s.B * s.H, bh_, qb_)) return;   // whole work-group
+  attn_pp_body<kSplit, kExt>(s, smem_raw, bh_, qb_ * kQBlock);
+}
+
+// Mixed launch: when the 256-query blocks do not fill the last round of work-groups on the 256 CUs
+// (one work-group per CU at a time), the blocks of that round are run as two key-split work-groups
+// of 128 queries each, which take about 0.55 of a wide work-group's time.  Per XCD (ids go round
+// robin) the contiguous, head-major range of blocks is dispatched wide blocks first, then the
+// halves of its last s.mix_halves blocks.
+template <bool kExt>
+__global__ __launch_bounds__(kThreads, 2) void attn_pp_mixed_kernel(AttnStep s) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  if (s.copy_wgs > 0 && blockIdx.x >= gridDim.x - s.copy_wgs) {
+    prefetch_copy(s, blockIdx.x - (gridDim.x - s.copy_wgs), threadIdx.x, kThreads);
+    return;
+  }
+  const int nqb = (s.Sq + kQPerWG - 1) / kQPerWG;
+  const int items = nqb * s.B * s.H;
+  const int per = (items + kXcds - 1) / kXcds;
+  const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+  const int first = xcd * per;
+  const int count = min(per, items - first);          // blocks of this XCD (may be <= 0 on the last ones)
+  const int halves = min(s.mix_halves, count);
+  const int wide = count - halves;
+  if (slot < wide) {
+    const int item = first + slot;
+    const int bh_ = item / nqb;
+    attn_pp_body<false, kExt>(s, smem_raw, bh_, (item - bh_ * nqb) * kQPerWG);
+  } else {
+    const int hs = slot - wide;
+    if (hs >= 2 * halves) return;
+    const int item = first + wide + (hs >> 1);
+    const int bh_ = item / nqb;
+    const int q_base = (item - bh_ * nqb) * kQPerWG + (hs & 1) * kQPerWGSplit;
+    if (q_base >= s.Sq) return;                        // second half of a ragged last block
+    attn_pp_body<true, kExt>(s, smem_raw, bh_, q_base);
+  }
 }
 
 }  // namespace
@@ -864,6 +900,32 @@ usp_status launch_attn_mfma(const AttnStep& step, hipStream_t st) {
   if (s.v_scale != nullptr) {
     set_error("the bf16 matrix-core kernels take V already multiplied by its scales");
     return USP_ERR_INVALID_ARG;
+  }
+  // Mixed launch when the last round of 256-query work-groups would be at most half full
+  const int items = (int)((s.Sq + kQPerWG - 1) / kQPerWG) * s.B * s.H;
+  const int rem = items % 256;
+  int mix_blocks = 0;
+  if (s.variant == 4) mix_blocks = (items + 1) / 2;                       // forced: the second half of the blocks
+  else if (s.variant == 0 && !split && rem > 0 && rem <= 128) mix_blocks = rem;
+  if (mix_blocks > 0) {
+    s.mix_halves = (mix_blocks + kXcds - 1) / kXcds;
+    const int per = (items + kXcds - 1) / kXcds;
+    const unsigned wgs_mixed = (unsigned)(kXcds * (per + s.mix_halves));
+    s.copy_wgs = prefetch_wg_count(s, (int)wgs_mixed, 1);
+    constexpr int lds_e = (int)sizeof(SmemPPExt), lds_p = (int)sizeof(SmemPP);
+    if (ext) {
+      static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_pp_mixed_kernel<true>),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds_e);
+      USP_CHECK_HIP(attr);
+      hipLaunchKernelGGL((attn_pp_mixed_kernel<true>), dim3(wgs_mixed + s.copy_wgs), dim3(kThreads), lds_e, st, s);
+    } else {
+      static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_pp_mixed_kernel<false>),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds_p);
+      USP_CHECK_HIP(attr);
+      hipLaunchKernelGGL((attn_pp_mixed_kernel<false>), dim3(wgs_mixed + s.copy_wgs), dim3(kThreads), lds_p, st, s);
+    }
+    USP_CHECK_HIP(hipGetLastError());
+    return USP_OK;
   }
   const unsigned wgs = split ? wg_grid_size((s.Sq + kQPerWGSplit - 1) / kQPerWGSplit, s.B * s.H) : wgs256;
   s.copy_wgs = prefetch_wg_count(s, (int)wgs, 1);

@@ -104,8 +104,10 @@ usp_status make_plan(const usp_attn_desc* d, Plan* p) {
     USP_CHECK_ARG(d->chunk_len[r] >= 0, "chunk_len[%d]=%d is negative", r, d->chunk_len[r]);
     if (d->chunk_len[r] > p->max_len) p->max_len = d->chunk_len[r];
   }
-  USP_CHECK_ARG(!((d->flags & USP_ATTN_KERNEL_WIDE) && (d->flags & USP_ATTN_KERNEL_SPLIT)),
-                "USP_ATTN_KERNEL_WIDE and USP_ATTN_KERNEL_SPLIT exclude each other");
+  {
+    const uint32_t kf = d->flags & (USP_ATTN_KERNEL_WIDE | USP_ATTN_KERNEL_SPLIT | USP_ATTN_KERNEL_MIXED);
+    USP_CHECK_ARG((kf & (kf - 1)) == 0, "the USP_ATTN_KERNEL_* flags exclude one another");
+  }
   p->fp8 = d->kv_dtype == USP_FP8_E4M3FN;
   USP_CHECK_ARG(!((d->flags & USP_ATTN_DOUBLE_BUFFER) && (d->flags & USP_ATTN_FUSED_PREFETCH)),
                 "USP_ATTN_DOUBLE_BUFFER and USP_ATTN_FUSED_PREFETCH exclude each other");
@@ -330,7 +332,8 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
     }
     if (p.fused_pf && r + 1 < p.W) prefetch_segments(r + 1, &a);
     a.scale = scale;
-    a.variant = (desc->flags & USP_ATTN_KERNEL_SPLIT) ? 2 : ((desc->flags & USP_ATTN_KERNEL_WIDE) ? 1 : 0);
+    a.variant = (desc->flags & USP_ATTN_KERNEL_SPLIT) ? 2 : (desc->flags & USP_ATTN_KERNEL_WIDE) ? 1 :
+                (desc->flags & USP_ATTN_KERNEL_MIXED) ? 4 : 0;
     a.lse = lse;
     a.out = out;
     a.acc = p.W > 1 && !p.unfused ? (float*)(ws + p.off_acc) : nullptr;

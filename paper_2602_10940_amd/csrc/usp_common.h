@@ -80,7 +80,8 @@ struct AttnStep {
   //                    mode 2 = middle chunk: merge with (acc, lse), write back fp32
   //                    mode 3 = last chunk: merge with (acc, lse), write out in qo_dtype and lse
   int mode;
-  int variant;               // matrix-core kernels: 0 = pick by grid size, 1 = 256-query work-groups, 2 = key-split
+  int variant;               // matrix-core kernels: 0 = pick by grid size, 1 = 256-query work-groups, 2 = key-split, 4 = mixed
+  int mix_halves;            // mixed launch: blocks per XCD run as two key-split halves (set by the launcher)
   float* acc;                // fp32 [B,H,Sq,d] dense carried O (modes 1-3)
   void* out;                 // qo_dtype by os strides (modes 0, 3)
   float* lse;                // fp32 [B,H,Sq] dense

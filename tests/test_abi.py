@@ -72,7 +72,7 @@ def test_workspace_sizes_and_descriptor_checks():
     d.flags = b.USP_ATTN_FUSED_PREFETCH                                    # same two staging buffers
     assert b.usp_ring_attn_workspace_bytes(d) == rows * 128 * 4 + 4 * rows * 128 * 2 + recs
     for both in (b.USP_ATTN_FUSED_PREFETCH | b.USP_ATTN_DOUBLE_BUFFER,
-                 b.USP_ATTN_KERNEL_WIDE | b.USP_ATTN_KERNEL_SPLIT):
+                 b.USP_ATTN_KERNEL_WIDE | b.USP_ATTN_KERNEL_SPLIT, b.USP_ATTN_KERNEL_SPLIT | b.USP_ATTN_KERNEL_MIXED):
         d.flags = both
         with pytest.raises(b.UspError):
             b.usp_ring_attn_workspace_bytes(d)

@@ -65,7 +65,7 @@ def test_tiny_fp32_ring2():
     np.testing.assert_array_equal(l3, l)
 
 
-_KERNEL_FLAG = {"auto": 0, "wide": 4, "split": 8}   # USP_ATTN_KERNEL_*
+_KERNEL_FLAG = {"auto": 0, "wide": 4, "split": 8, "mixed": 32}   # USP_ATTN_KERNEL_*
 
 
 def _small_wl(name, H, Sq, lens, **kw):
@@ -80,7 +80,7 @@ def _small_wl(name, H, Sq, lens, **kw):
     (33, (1,)), (1, (70,)), (513, (129, 64, 7)),         # degenerate sizes, several chunks
     (128, (0, 96)), (64, (64, 0, 64)),                   # empty chunks
 ])
-@pytest.mark.parametrize("kernel", ["auto", "wide", "split"])
+@pytest.mark.parametrize("kernel", ["auto", "wide", "split", "mixed"])
 def test_mfma_small_shapes(Sq, lens, kernel):
     inp = W.make_attention_inputs(_small_wl("flux1024_u", 2, Sq, lens))
     o, l = _run(inp, flags=_KERNEL_FLAG[kernel])
@@ -88,7 +88,7 @@ def test_mfma_small_shapes(Sq, lens, kernel):
     _assert_parity(o, l, ro, rl)
 
 
-@pytest.mark.parametrize("variant", ["wide", "split"])
+@pytest.mark.parametrize("variant", ["wide", "split", "mixed"])
 @pytest.mark.parametrize("Sq,lens", [
     (128, (64,)), (130, (128,)), (257, (192,)),          # 1, 2, 3 key tiles; ragged query tails
     (384, (448, 64, 512)), (96, (1152,)),                # odd / even tile counts, several chunks
@@ -97,7 +97,7 @@ def test_mfma_both_work_decompositions(Sq, lens, variant):
     """Unmasked chunks of whole 64-key tiles run on the ping-pong kernels; force each variant."""
     P = _P()
     inp = W.make_attention_inputs(_small_wl("flux1024_u", 3, Sq, lens))
-    flag = P.USP_ATTN_KERNEL_WIDE if variant == "wide" else P.USP_ATTN_KERNEL_SPLIT
+    flag = _KERNEL_FLAG[variant]
     o, l = _run(inp, flags=flag)
     ro, rl = _oracle(inp)
     _assert_parity(o, l, ro, rl)
@@ -120,7 +120,7 @@ def test_mfma_matches_generic_kernel_on_fp32_copy():
     _assert_parity(o32, l32, ro, rl, fp32=True)
 
 
-@pytest.mark.parametrize("kernel", ["wide", "split"])
+@pytest.mark.parametrize("kernel", ["wide", "split", "mixed"])
 def test_key_mask_and_fully_masked_rows(kernel):
     fl = _KERNEL_FLAG[kernel]
     wl = _small_wl("qwen_r2", 2, 192, (128, 128), masked_keys=(90, 256))   # chunk 1 fully masked
@@ -142,7 +142,7 @@ def test_key_mask_and_fully_masked_rows(kernel):
     _assert_parity(o3, l3, ro3, rl3)
 
 
-@pytest.mark.parametrize("kernel", ["wide", "split"])
+@pytest.mark.parametrize("kernel", ["wide", "split", "mixed"])
 def test_batch_of_three_with_a_different_mask_per_entry(kernel):
     """B = 3: every batch entry has its own key mask (different live tile counts, one entry with
     trailing dead tiles only, one fully dead second chunk), FP8 K/V with per-(b,h,token) scales on
