@@ -81,18 +81,10 @@ __device__ __forceinline__ float xlane32_sum(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-// LDS transposing read: the 16 lanes of a group each name 8 bytes; seen as a 4 x 16 matrix of
-// bf16 (row i = the data of lanes 4i..4i+3), lane j of the group receives column j.
-__device__ __forceinline__ u32x2 lds_read_tr(const unsigned char* p) {
-  typedef short s16x4 __attribute__((ext_vector_type(4)));
-  s16x4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-      (s16x4 __attribute__((address_space(3)))*)(p));
-  return __builtin_bit_cast(u32x2, r);
-}
-
-// Chunk result from the running state (O~ = oacc, reference m in log2 units, this lane's part of l),
-// merged with the carried (O, lse) of earlier chunks by the section 3.4 equations, and stored.
-__device__ __forceinline__ void finish_and_store(const AttnStep& s, f32x16 (&oacc)[4], float m, float lsum,
+// Chunk result, merge and store straight from the accumulator layout (32 bytes per query row and
+// instruction): what the key-split work-groups use, whose epilogue is too short for the detour
+// through LDS to pay.
+__device__ __forceinline__ void finish_and_store_direct(const AttnStep& s, f32x16 (&oacc)[4], float m, float lsum,
                                                  int b, int h, int q0, int n, int g) {
   // ---- chunk result, merge with carried state, store ------------------------------------
   const float l = xlane32_sum(lsum);
@@ -134,6 +126,72 @@ __device__ __forceinline__ void finish_and_store(const AttnStep& s, f32x16 (&oac
         *reinterpret_cast<uint2*>(outp + dcol) = make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
     }
   if (g == 0) s.lse[row] = lse_new;
+}
+
+// Chunk result from the running state (O~ = oacc, reference m in log2 units, this lane's part of l),
+// merged with the carried (O, lse) of earlier chunks by the section 3.4 equations, and stored.
+// In the accumulator layout a lane holds four consecutive head dims of one query, so direct stores
+// would touch 32 rows with 32 bytes each per instruction.  The wave therefore turns its 32 x 128
+// tile through its own LDS region (row pitch 528 bytes, so that rows do not all start in the same bank) and then moves
+// whole rows: 32 lanes x 16 bytes (fp32 carry, read and write) or x 8 bytes (bf16 output) per row,
+// two rows per instruction.  Only this wave touches the region; LDS operations of one wave complete
+// in order, so no barrier is needed.
+constexpr int kEpiPitch = kD * 4 + 16;                    // bytes per staged row
+constexpr int kEpiWaveB = kQPerWave * kEpiPitch + 512;    // + per-row (scale of O~, weight of the carry, lse, unused)
+__device__ __forceinline__ void finish_and_store(const AttnStep& s, f32x16 (&oacc)[4], float m, float lsum,
+                                                 int b, int h, int q0, int n, int g, unsigned char* epi) {
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
+  const int lane = n + 32 * g;
+  const float l = xlane32_sum(lsum);
+  const int qi = q0 + n;
+  const int64_t row0 = ((int64_t)b * s.H + h) * s.Sq;     // first row of this (batch, head) in lse / acc
+  float lse_r = -INFINITY, c_cur = 0.0f;
+  if (l > 0.0f) { lse_r = (m + log2f(l)) * 0.69314718055994530942f; c_cur = 1.0f / l; }
+  float w_prev = 0.0f, lse_new = lse_r;
+  if (s.mode >= 2) {
+    const float lse_p = s.lse[row0 + min(qi, s.Sq - 1)];
+    const float mm = fmaxf(lse_p, lse_r);
+    if (mm == -INFINITY) { w_prev = 0.0f; c_cur = 0.0f; lse_new = -INFINITY; }
+    else {
+      lse_new = mm + logf(expf(lse_p - mm) + expf(lse_r - mm));
+      w_prev = expf(lse_p - lse_new);
+      c_cur *= expf(lse_r - lse_new);
+    }
+  }
+  if (g == 0 && qi < s.Sq) s.lse[row0 + qi] = lse_new;
+  // stage: row n, head dims 32*dt + 8*i4 + 4*g .. +3
+  float* info = reinterpret_cast<float*>(epi + kQPerWave * kEpiPitch);
+  if (g == 0) { info[2 * n] = c_cur; info[2 * n + 1] = w_prev; }
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int i4 = 0; i4 < 4; ++i4) {
+      const f32x4 v = {oacc[dt][4 * i4], oacc[dt][4 * i4 + 1], oacc[dt][4 * i4 + 2], oacc[dt][4 * i4 + 3]};
+      *reinterpret_cast<f32x4*>(epi + n * kEpiPitch + (32 * dt + 8 * i4 + 4 * g) * 4) = v;
+    }
+  // rows: lane (r2, c) handles head dims 4c .. 4c+3 of rows 2*it + r2
+  const int r2 = lane >> 5, c = lane & 31;
+  const int rows_valid = min(kQPerWave, s.Sq - q0);       // <= 0: nothing to store
+#pragma unroll 4
+  for (int it = 0; it < kQPerWave / 2; ++it) {
+    const int r = 2 * it + r2;
+    if (r >= rows_valid) continue;
+    const f32x4 v = *reinterpret_cast<const f32x4*>(epi + r * kEpiPitch + c * 16);
+    const float cc = info[2 * r], wp = info[2 * r + 1];
+    float o[4] = {v[0] * cc, v[1] * cc, v[2] * cc, v[3] * cc};
+    const int64_t row = row0 + q0 + r;
+    if (s.mode >= 2) {
+      const float4 p = *reinterpret_cast<const float4*>(s.acc + row * kD + 4 * c);
+      o[0] = fmaf(wp, p.x, o[0]); o[1] = fmaf(wp, p.y, o[1]);
+      o[2] = fmaf(wp, p.z, o[2]); o[3] = fmaf(wp, p.w, o[3]);
+    }
+    if (s.mode == 1 || s.mode == 2)
+      *reinterpret_cast<float4*>(s.acc + row * kD + 4 * c) = make_float4(o[0], o[1], o[2], o[3]);
+    else {
+      bf16_t* outp = (bf16_t*)s.out + b * s.os[0] + h * s.os[1] + (int64_t)(q0 + r) * s.os[2];
+      *reinterpret_cast<uint2*>(outp + 4 * c) = make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
+    }
+  }
 }
 
 // =============================================================================================
@@ -193,12 +251,17 @@ struct SmemPP {
   unsigned char k[kStages][kTileB];
   unsigned char v[kStages][kTileB];
 };
+// The wide work-groups' epilogue stages each wave's O tile through LDS (eight regions from offset 0,
+// over the tile stages, which are dead by then).
+constexpr int kLdsBytes = 8 * kEpiWaveB;
 struct SmemPPExt {
   unsigned char k[kStages][kTileB];
   unsigned char v[kStages][kTileB];
   unsigned char ext[kStages][kExtTileB];
 };
 
+// LDS transposing read: the 16 lanes of a group each name 8 bytes; seen as a 4 x 16 matrix of
+// bf16 (row i = the data of lanes 4i..4i+3), lane j of the group receives column j.
 __device__ __forceinline__ u32x2 lds_read_tr3(const __attribute__((address_space(3))) unsigned char* p) {
   typedef short s16x4 __attribute__((ext_vector_type(4)));
   s16x4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p));
@@ -799,7 +862,9 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
   }
   LAB_WG_END();
 
-  finish_and_store(s, oacc, m, lsum, b, h, q0, n, g);
+  // every tile read of the work-group is behind a barrier here (the one after the last matrix phase)
+  if (kSplit) finish_and_store_direct(s, oacc, m, lsum, b, h, q0, n, g);
+  else finish_and_store(s, oacc, m, lsum, b, h, q0, n, g, smem_raw + wave * kEpiWaveB);
 }
 
 template <bool kSplit, bool kExt>
@@ -876,7 +941,8 @@ usp_status launch_attn_ext_prepare(const AttnStep& s, hipStream_t st) {
 namespace {
 template <bool kSplit, bool kExt>
 usp_status launch_pp(const AttnStep& s, unsigned wgs, hipStream_t st) {
-  constexpr int lds = kExt ? (int)sizeof(SmemPPExt) : (int)sizeof(SmemPP);
+  static_assert(kLdsBytes >= (int)sizeof(SmemPPExt) && kLdsBytes <= 160 * 1024, "LDS plan");
+  constexpr int lds = kLdsBytes;
   static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_pp_kernel<kSplit, kExt>),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   USP_CHECK_HIP(attr);
@@ -912,7 +978,7 @@ usp_status launch_attn_mfma(const AttnStep& step, hipStream_t st) {
     const int per = (items + kXcds - 1) / kXcds;
     const unsigned wgs_mixed = (unsigned)(kXcds * (per + s.mix_halves));
     s.copy_wgs = prefetch_wg_count(s, (int)wgs_mixed, 1);
-    constexpr int lds_e = (int)sizeof(SmemPPExt), lds_p = (int)sizeof(SmemPP);
+    constexpr int lds_e = kLdsBytes, lds_p = kLdsBytes;
     if (ext) {
       static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_pp_mixed_kernel<true>),
                                                          hipFuncAttributeMaxDynamicSharedMemorySize, lds_e);
