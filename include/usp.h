@@ -71,7 +71,8 @@ typedef enum {
  * [B,H,chunk_len[r],d] array" (the only way to describe dense chunks of unequal length).
  */
 typedef struct usp_attn_desc {
-  int32_t B, H, d;          /* d: 64 or 128 for bf16 (MFMA path), any multiple of 4 up to 256 for f32 */
+  int32_t B, H, d;          /* d: a multiple of 8 up to 256.  bf16 with d = 128 runs on the matrix-core
+                               kernels; every other combination on a slower general kernel */
   int32_t Sq;               /* tokens of the local Q shard */
   int32_t n_chunks;         /* ring degree W >= 1 */
   const int32_t* chunk_len; /* HOST array [n_chunks] */
@@ -86,8 +87,8 @@ typedef struct usp_attn_desc {
 
 /*
  * Bytes of device workspace usp_ring_attn_fwd needs for this descriptor
- * (0 is possible: one bf16/f32 chunk, no staging).  Returns (size_t)-1 if the
- * descriptor is invalid.
+ * (0 is possible, e.g. one f32 chunk; bf16 with d = 128 always asks for a little, about
+ * 1/16 of a K chunk).  Returns (size_t)-1 if the descriptor is invalid.
  */
 size_t usp_ring_attn_workspace_bytes(const usp_attn_desc* desc);
 
@@ -105,7 +106,9 @@ size_t usp_ring_attn_workspace_bytes(const usp_attn_desc* desc);
  *   k_scales / v_scales   NULL unless kv_dtype is FP8: HOST arrays of device pointers,
  *              chunk r -> float [B,H,chunk_len[r]] dense, one scale per (b,h,token)
  *              (value = code * scale, as produced by usp_fp8_quant on the
- *              [B*H*chunk_len, d] view when the chunk is dense)
+ *              [B*H*chunk_len, d] view when the chunk is dense).  With bf16 Q and d = 128
+ *              K enters exactly (codes, scale applied to the fp32 scores) and V as
+ *              bf16(code * scale); otherwise both products are taken in fp32.
  *   key_mask   NULL, or HOST array of n_chunks device pointers (entries may be NULL):
  *              uint8 [B,chunk_len[r]], nonzero = key takes part.  A query whose keys
  *              are all masked gets O = 0, lse = -inf.
