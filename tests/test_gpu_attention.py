@@ -342,6 +342,38 @@ def test_flux1024_ring4_full_size_sampled_rows():
     _assert_parity(o[:, :, rows], l[:, :, rows], ro, rl)
 
 
+def test_flux1024_ring4_full_size_every_transfer_mode_bit_identical():
+    """Config 3 at full size: the plain call, the side-stream schedule, the transfers inside the
+    attention launches and the separate-merge variant of the latter all run the same kernels on the
+    same values in the same order."""
+    wl = W.WORKLOADS["flux1024_r4"]
+    inp = W.make_attention_inputs(wl)
+    o0, l0 = _run(inp)
+    o1, l1 = _run(inp, flags=1, copy_stream=torch.cuda.Stream())
+    o16, l16 = _run(inp, flags=16)
+    np.testing.assert_array_equal(o1, o0); np.testing.assert_array_equal(l1, l0)
+    np.testing.assert_array_equal(o16, o0); np.testing.assert_array_equal(l16, l0)
+
+
+def test_long_sequence_16k_keys_single_chunk_and_ragged_ring():
+    """A 2048 x 2048-image-sized sequence (16 896 tokens + a ragged remainder) on 3 heads: one chunk
+    of 16 896 keys (264 tiles per work-group) on the plain kernels, and the same keys plus 40 more
+    as three unequal chunks, the last of them ragged (extended kernels, merge, fused prefetch)."""
+    wl = W.Workload("long16k", 31, 1, 3, 128, 1000, (16896,), "bf16", k_mul=0.5)
+    inp = W.make_attention_inputs(wl)
+    rows = W.sample_rows(5, wl.Sq, 40)
+    ro, rl = _oracle(inp, rows)
+    for kernel in ("auto", "wide"):
+        o, l = _run(inp, flags=_KERNEL_FLAG[kernel])
+        _assert_parity(o[:, :, rows], l[:, :, rows], ro, rl)
+    wl2 = W.Workload("long16k_r3", 32, 1, 3, 128, 1000, (8192, 6400, 2344), "bf16", k_mul=0.5)
+    inp2 = W.make_attention_inputs(wl2)
+    ro2, rl2 = _oracle(inp2, rows)
+    for flags in (0, 16):
+        o2, l2 = _run(inp2, flags=flags)
+        _assert_parity(o2[:, :, rows], l2[:, :, rows], ro2, rl2)
+
+
 def test_flux2048_u2r8_full_size_sampled_rows():
     """Config 4 shapes: H=12, Q shard 2112 (8.25 query blocks), eight chunks of 2112 (33 tiles),
     per-head scales U(0.5,2), double-buffered; oracle on 40 seeded rows of every head."""
