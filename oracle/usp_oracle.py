@@ -21,6 +21,11 @@ What each function follows (paper = FastUSP, arXiv 2602.10940):
                        i.e. the OCP "fn" variant: no infinities, one NaN code)
   fp8_quant()/fp8_dequant()   Algorithm 1 lines 1-2 and 4, with one scale per
                        row of the 2-D view (per token)
+  fp8_quant_mapped()/fp8_dequant_mapped()   the same two steps with the rows
+                       gathered from / scattered to the layouts on either side
+                       of the All-to-All of section 2.2.1 ([B,H,S/N,D] <->
+                       [B,H/N,S,D]): a row permutation around fp8_quant /
+                       fp8_dequant, nothing else
 
 Readings taken where the paper is silent are listed in the repository's design
 notes; the ones that matter here:
@@ -37,7 +42,10 @@ logsumexp, chunk-order invariance over every permutation, merge-tree
 associativity, raw-form == difference-form merge, the OCP E4M3 value table facts
 (448, 2^-9, 2^-6, NaN codes, monotonicity), torch.float8_e4m3fn casts inside
 +-448, encode(decode(b)) == b, tie and saturation cases, per-row invariants of
-the quantiser and its provable round-trip bound.
+the quantiser and its provable round-trip bound; for the mapped variants the
+identity with numpy transposes of the plain result, and a four-rank emulation
+of the exchange of section 2.2.1 (8 heads, 1024 tokens: [B,8,256,D] ->
+[B,2,1024,D] and back).
 The paper's "<0.1% precision loss" has no stated metric: parity unpinned for
 that figure (only aggregate readings of it are asserted).
 """
@@ -251,3 +259,42 @@ def bf16_bits_to_f64(b: np.ndarray) -> np.ndarray:
 def dequant_exact_f64(codes: np.ndarray, scales: np.ndarray) -> np.ndarray:
     """decode(code) * scale in fp64 (exact): what an FP8 K/V chunk means as numbers."""
     return e4m3fn_decode(codes) * np.asarray(scales, dtype=np.float64)[..., None]
+
+
+# ---------------------------------------------------------------------------
+# Algorithm 1 around the All-to-All of section 2.2.1: rows visited as a 4-D index
+# ---------------------------------------------------------------------------
+def row_map_offsets(n: Sequence[int], strides: Sequence[int]) -> np.ndarray:
+    """Offset sum_k i_k * strides[k] of every index (i0, i1, i2, i3), i3 fastest."""
+    idx = np.indices(tuple(int(x) for x in n), dtype=np.int64).reshape(4, -1)
+    return (idx * np.asarray(strides, dtype=np.int64)[:, None]).sum(axis=0)
+
+
+def fp8_quant_mapped(x_flat: np.ndarray, n: Sequence[int], src_stride: Sequence[int],
+                     dst_row_stride: Sequence[int], cols: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Row (i0..i3) is x_flat[sum i_k src_stride[k] : +cols]; its codes and scale go to row
+    sum i_k dst_row_stride[k] of the dense [rows, cols] / [rows] outputs."""
+    src = row_map_offsets(n, src_stride)
+    dst = row_map_offsets(n, dst_row_stride)
+    rows = np.asarray(x_flat, dtype=np.float32).reshape(-1)[src[:, None] + np.arange(cols)[None, :]]
+    q, s = fp8_quant(rows)
+    total = int(np.prod(n))
+    assert sorted(dst.tolist()) == list(range(total)), "destination rows must be a permutation"
+    q_out = np.empty((total, cols), dtype=np.uint8)
+    s_out = np.empty((total,), dtype=np.float32)
+    q_out[dst] = q
+    s_out[dst] = s
+    return q_out, s_out
+
+
+def fp8_dequant_mapped(codes: np.ndarray, scales: np.ndarray, n: Sequence[int],
+                       src_row_stride: Sequence[int], dst_stride: Sequence[int], cols: int,
+                       out_elems: int, to_bf16: bool) -> np.ndarray:
+    """Row (i0..i3) is read at row sum i_k src_row_stride[k] of codes / scales and written to
+    y_flat[sum i_k dst_stride[k] : +cols]; elements no row maps to stay 0."""
+    src = row_map_offsets(n, src_row_stride)
+    dst = row_map_offsets(n, dst_stride)
+    y = fp8_dequant_bf16(codes[src], scales[src]) if to_bf16 else fp8_dequant(codes[src], scales[src])
+    out = np.zeros((out_elems,), dtype=np.float32)
+    out[dst[:, None] + np.arange(cols)[None, :]] = y
+    return out

@@ -239,3 +239,67 @@ def test_dequant_values():
     np.testing.assert_array_equal(y, [[0.5, -0.5, 224.0, 2.0 ** -10]])
     ex = orc.dequant_exact_f64(codes, np.array([0.1], np.float32))
     np.testing.assert_array_equal(ex, orc.e4m3fn_decode(codes) * np.float64(np.float32(0.1)))
+
+
+# ---------------------------------------------------------------------------
+# mapped variants: a row permutation around the plain quantiser (section 2.2.1 layouts)
+# ---------------------------------------------------------------------------
+def _a2a_maps(N, B, H, S_loc, D):
+    """Row maps of the four pack / unpack steps around the two All-to-Alls of section 2.2.1.
+    Send / receive buffers are [N][B][H/N][S_loc] rows (one contiguous block per peer)."""
+    Hn, S = H // N, N * S_loc
+    n = (N, B, Hn, S_loc)
+    dense = (B * Hn * S_loc, Hn * S_loc, S_loc, 1)
+    return {
+        "n": n, "dense": dense,
+        "seq_sharded": (Hn * S_loc * D, H * S_loc * D, S_loc * D, D),   # element strides into [B,H,S_loc,D]
+        "head_sharded": (S_loc * D, Hn * S * D, S * D, D),              # element strides into [B,Hn,S,D]
+    }
+
+
+def test_mapped_quant_is_a_transpose_of_the_plain_result():
+    rng = np.random.Generator(np.random.PCG64(41))
+    N, B, H, S_loc, D = 4, 2, 8, 6, 16
+    m = _a2a_maps(N, B, H, S_loc, D)
+    x = rng.standard_normal((B, H, S_loc, D)).astype(np.float32)
+    q, s = orc.fp8_quant_mapped(x, m["n"], m["seq_sharded"], m["dense"], D)
+    pq, ps = orc.fp8_quant(x.reshape(-1, D))
+    # plain rows are (b, peer, h, t); the send buffer wants (peer, b, h, t)
+    np.testing.assert_array_equal(q.reshape(N, B, H // N, S_loc, D),
+                                  pq.reshape(B, N, H // N, S_loc, D).transpose(1, 0, 2, 3, 4))
+    np.testing.assert_array_equal(s.reshape(N, B, H // N, S_loc), ps.reshape(B, N, H // N, S_loc).transpose(1, 0, 2, 3))
+    y = orc.fp8_dequant_mapped(q, s, m["n"], m["dense"], m["seq_sharded"], D, x.size, to_bf16=False)
+    np.testing.assert_array_equal(y.reshape(x.shape), orc.fp8_dequant(pq, ps).reshape(x.shape))
+
+
+def test_four_rank_exchange_of_section_2_2_1():
+    """The worked example of section 2.2.1: 4 GPUs, 8 heads, 1024 tokens: every rank starts with
+    [B, 8, 256, D] and ends with [B, 2, 1024, D]; the second exchange restores [B, 8, 256, D]."""
+    rng = np.random.Generator(np.random.PCG64(42))
+    N, B, H, S_loc, D = 4, 1, 8, 256, 8
+    Hn, S = H // N, N * S_loc
+    m = _a2a_maps(N, B, H, S_loc, D)
+    xs = [rng.standard_normal((B, H, S_loc, D)).astype(np.float32) for _ in range(N)]
+    full = np.concatenate(xs, axis=2)                                       # [B, H, S, D]
+    fq, fs = orc.fp8_quant(full.reshape(-1, D))
+    full_dq = orc.fp8_dequant(fq, fs).reshape(full.shape)                   # what every element must become
+    send = [orc.fp8_quant_mapped(x, m["n"], m["seq_sharded"], m["dense"], D) for x in xs]
+    blk = B * Hn * S_loc
+    ys = []
+    for r in range(N):                                                      # all_to_all: block r of every sender
+        rq = np.concatenate([send[src][0][r * blk:(r + 1) * blk] for src in range(N)])
+        rs = np.concatenate([send[src][1][r * blk:(r + 1) * blk] for src in range(N)])
+        y = orc.fp8_dequant_mapped(rq, rs, m["n"], m["dense"], m["head_sharded"], D, B * Hn * S * D, to_bf16=False)
+        y = y.reshape(B, Hn, S, D)
+        assert y.shape == (1, 2, 1024, 8)
+        np.testing.assert_array_equal(y, full_dq[:, r * Hn:(r + 1) * Hn])
+        ys.append(y)
+    # the output exchange: pack [B,Hn,S,D] per peer = token range, unpack into [B,H,S_loc,D]
+    send2 = [orc.fp8_quant_mapped(y, m["n"], m["head_sharded"], m["dense"], D) for y in ys]
+    for r in range(N):
+        rq = np.concatenate([send2[src][0][r * blk:(r + 1) * blk] for src in range(N)])
+        rs = np.concatenate([send2[src][1][r * blk:(r + 1) * blk] for src in range(N)])
+        z = orc.fp8_dequant_mapped(rq, rs, m["n"], m["dense"], m["seq_sharded"], D, B * H * S_loc * D, to_bf16=False)
+        z = z.reshape(B, H, S_loc, D)
+        # quantising an already dequantised row reproduces it (idempotence), so z is the first round trip
+        np.testing.assert_array_equal(z, full_dq[:, :, r * S_loc:(r + 1) * S_loc])
