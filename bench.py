@@ -142,6 +142,21 @@ def main() -> int:
     yb = torch.empty((8 * R, C), dtype=torch.bfloat16, device=dev)
     t_quant8 = per_launch(lambda i: P.usp_fp8_quant(xb, qb, sb), reps=100, rounds=3)
     t_deq8 = per_launch(lambda i: P.usp_fp8_dequant(qb, sb, y=yb), reps=100, rounds=3)
+    # pack / unpack in the layouts around the All-to-All (section 2.2.1), 8 peers: the same 28.3 MB as
+    # [1, 24, 4608, 128] on the sequence-sharded side -> send blocks [8][1][3][4608] rows of 128 ->
+    # (exchange) -> [1, 3, 36864, 128] on the head-sharded side
+    Nr, Hh, Sl, Dd = 8, 24, R, 128
+    Hn = Hh // Nr
+    n4 = (Nr, 1, Hn, Sl)
+    dense = (Hn * Sl, Hn * Sl, Sl, 1)
+    seq_sh = (Hn * Sl * Dd, Hh * Sl * Dd, Sl * Dd, Dd)
+    head_sh = (Sl * Dd, Hn * Nr * Sl * Dd, Nr * Sl * Dd, Dd)
+    qm = [torch.empty((Hh * Sl, Dd), dtype=torch.uint8, device=dev) for _ in range(NBUF)]
+    sm = [torch.empty((Hh * Sl,), dtype=torch.float32, device=dev) for _ in range(NBUF)]
+    t_quant_map = per_launch(lambda i: P.usp_fp8_quant_mapped(xs[i % NBUF], n4, seq_sh, dense, Dd, qm[i % NBUF], sm[i % NBUF]), rounds=3)
+    t_deq_map = per_launch(lambda i: P.usp_fp8_dequant_mapped(qm[i % NBUF], sm[i % NBUF], n4, dense, head_sh, ys[i % NBUF]), rounds=3)
+    map_bytes = R * C * 3 + Hh * Sl * 4
+    del qm, sm
     # Algorithm 1 as printed: one scale for the whole tensor = the payload viewed as a single row
     x1 = xs[0].reshape(1, R * C)
     q1 = torch.empty((1, R * C), dtype=torch.uint8, device=dev)
@@ -189,6 +204,10 @@ def main() -> int:
                            "quant_gbs": round(8 * fp8_bytes / (t_quant8 * 1e-3) * 1e-9, 1),
                            "dequant_gbs": round(8 * fp8_bytes / (t_deq8 * 1e-3) * 1e-9, 1),
                            "note": "[36864,3072] in one call; a plain copy kernel reaches ~6.0 TB/s on this GPU"},
+        "fp8_a2a_layouts": {"pack_us": round(t_quant_map * 1e3, 2), "unpack_us": round(t_deq_map * 1e3, 2),
+                            "pack_gbs": round(map_bytes / (t_quant_map * 1e-3) * 1e-9, 1),
+                            "unpack_gbs": round(map_bytes / (t_deq_map * 1e-3) * 1e-9, 1),
+                            "note": "rows of 128 (one scale per head and token), written / read one block per peer, 8 peers"},
         "fp8_quant_per_tensor": {"us": round(t_quant_pt * 1e3, 2),
                                  "gbs": round((R * C * 3 + 4) / (t_quant_pt * 1e-3) * 1e-9, 1),
                                  "note": "the payload as one row (one scale): absmax pass + cast pass, input read twice, cache-warm"},

@@ -163,6 +163,31 @@ usp_status usp_fp8_quant(int64_t rows, int64_t cols, int32_t in_dt, const void* 
 usp_status usp_fp8_dequant(int64_t rows, int64_t cols, int32_t out_dt, const uint8_t* q,
                            const float* scales, void* y, void* stream);
 
+/*
+ * The same pack / unpack with the rows taken from, or delivered to, the layouts on either side of
+ * the All-to-All of section 2.2.1 ([B, H, S/N, D] on the sequence-sharded side, [B, H/N, S, D] on
+ * the head-sharded side), so that the send buffer is written, and the receive buffer read, one
+ * contiguous block per peer with no separate transposition pass.  Rows are visited as a 4-D index
+ * (i0, i1, i2, i3), i3 fastest, n[k] values each (for the exchange: peer, batch, head, token).
+ *   usp_fp8_quant_mapped:   row (i0..i3) starts at element  sum_k i_k * src_stride[k]  of x and its
+ *                           codes / scale go to row  sum_k i_k * dst_stride[k]  of q [rows, cols] /
+ *                           scales [rows]  (rows = n[0]*n[1]*n[2]*n[3]; the destination rows must be
+ *                           a permutation of 0 .. rows-1)
+ *   usp_fp8_dequant_mapped: row (i0..i3) is read at row  sum_k i_k * src_stride[k]  of q / scales and
+ *                           written from element  sum_k i_k * dst_stride[k]  of y on
+ * Arithmetic exactly as in usp_fp8_quant / usp_fp8_dequant.  cols: a multiple of 8, at most 4096;
+ * element strides must keep every row 16-byte aligned.  Strides are not checked for overlap.
+ */
+typedef struct usp_row_map {
+  int64_t n[4];
+  int64_t src_stride[4];
+  int64_t dst_stride[4];
+} usp_row_map;
+usp_status usp_fp8_quant_mapped(const usp_row_map* map, int64_t cols, int32_t in_dt, const void* x,
+                                uint8_t* q, float* scales, void* stream);
+usp_status usp_fp8_dequant_mapped(const usp_row_map* map, int64_t cols, int32_t out_dt, const uint8_t* q,
+                                  const float* scales, void* y, void* stream);
+
 /* Thread-local, statically stored description of the last failure ("" if none). */
 const char* usp_last_error(void);
 

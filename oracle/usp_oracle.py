@@ -294,7 +294,9 @@ def fp8_dequant_mapped(codes: np.ndarray, scales: np.ndarray, n: Sequence[int],
     y_flat[sum i_k dst_stride[k] : +cols]; elements no row maps to stay 0."""
     src = row_map_offsets(n, src_row_stride)
     dst = row_map_offsets(n, dst_stride)
-    y = fp8_dequant_bf16(codes[src], scales[src]) if to_bf16 else fp8_dequant(codes[src], scales[src])
+    y = fp8_dequant(codes[src], scales[src])
+    if to_bf16:   # the bf16-rounded values, held as float32
+        y = bf16_bits_to_f64(round_to_bf16(y)).astype(np.float32)
     out = np.zeros((out_elems,), dtype=np.float32)
     out[dst[:, None] + np.arange(cols)[None, :]] = y
     return out

@@ -23,7 +23,19 @@ USP_ATTN_FUSED_PREFETCH = 16
 USP_ATTN_KERNEL_MIXED = 32
 
 EXPORTS = ("usp_ring_attn_workspace_bytes", "usp_ring_attn_fwd", "usp_lse_merge", "usp_fp8_quant",
-           "usp_fp8_dequant", "usp_last_error", "usp_version")
+           "usp_fp8_dequant", "usp_fp8_quant_mapped", "usp_fp8_dequant_mapped", "usp_last_error", "usp_version")
+
+
+class RowMap(ctypes.Structure):
+    """usp_row_map: rows visited as (i0..i3), i3 fastest; offsets sum i_k * stride[k]."""
+    _fields_ = [("n", ctypes.c_int64 * 4), ("src_stride", ctypes.c_int64 * 4), ("dst_stride", ctypes.c_int64 * 4)]
+
+
+def make_row_map(n, src_stride, dst_stride) -> "RowMap":
+    m = RowMap()
+    for k in range(4):
+        m.n[k], m.src_stride[k], m.dst_stride[k] = int(n[k]), int(src_stride[k]), int(dst_stride[k])
+    return m
 
 
 class UspError(RuntimeError):
@@ -71,6 +83,10 @@ def load_library() -> ctypes.CDLL:
     lib.usp_fp8_quant.argtypes = [i64, i64, i32, vp, vp, vp, vp]
     lib.usp_fp8_dequant.restype = i32
     lib.usp_fp8_dequant.argtypes = [i64, i64, i32, vp, vp, vp, vp]
+    lib.usp_fp8_quant_mapped.restype = i32
+    lib.usp_fp8_quant_mapped.argtypes = [ctypes.POINTER(RowMap), i64, i32, vp, vp, vp, vp]
+    lib.usp_fp8_dequant_mapped.restype = i32
+    lib.usp_fp8_dequant_mapped.argtypes = [ctypes.POINTER(RowMap), i64, i32, vp, vp, vp, vp]
     _lib = lib
     return lib
 
@@ -136,6 +152,36 @@ def usp_fp8_dequant(q: torch.Tensor, scales: torch.Tensor, out_dtype: torch.dtyp
     if y is None:
         y = torch.empty((rows, cols), dtype=out_dtype, device=q.device)
     _check(lib.usp_fp8_dequant(rows, cols, _dt(y.dtype), _ptr(q), _ptr(scales), _ptr(y), _stream_handle(stream)))
+    return y
+
+
+def usp_fp8_quant_mapped(x: torch.Tensor, n, src_stride, dst_stride, cols: int,
+                         q: Optional[torch.Tensor] = None, scales: Optional[torch.Tensor] = None,
+                         stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """x: any contiguous tensor (flat element offsets); returns q uint8 [rows, cols], scales f32 [rows]
+    with rows = prod(n).  src_stride in elements of x, dst_stride in rows of q."""
+    lib = load_library()
+    assert x.is_contiguous() and x.is_cuda
+    rows = int(n[0]) * int(n[1]) * int(n[2]) * int(n[3])
+    if q is None:
+        q = torch.empty((rows, cols), dtype=torch.uint8, device=x.device)
+    if scales is None:
+        scales = torch.empty((rows,), dtype=torch.float32, device=x.device)
+    m = make_row_map(n, src_stride, dst_stride)
+    _check(lib.usp_fp8_quant_mapped(ctypes.byref(m), cols, _dt(x.dtype), _ptr(x), _ptr(q), _ptr(scales),
+                                    _stream_handle(stream)))
+    return q, scales
+
+
+def usp_fp8_dequant_mapped(q: torch.Tensor, scales: torch.Tensor, n, src_stride, dst_stride, y: torch.Tensor,
+                           stream=None) -> torch.Tensor:
+    """q uint8 [rows, cols] and scales read by row (src_stride in rows); rows written into the contiguous
+    tensor y (bf16 or f32) at element offsets sum i_k * dst_stride[k]."""
+    lib = load_library()
+    assert q.dim() == 2 and q.is_contiguous() and q.dtype == torch.uint8 and y.is_contiguous()
+    m = make_row_map(n, src_stride, dst_stride)
+    _check(lib.usp_fp8_dequant_mapped(ctypes.byref(m), q.shape[1], _dt(y.dtype), _ptr(q), _ptr(scales), _ptr(y),
+                                      _stream_handle(stream)))
     return y
 
 

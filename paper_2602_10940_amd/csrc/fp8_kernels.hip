@@ -89,18 +89,33 @@ __device__ __forceinline__ float scale_from_absmax(float a) {
 }
 
 // ---- rows that fit one wave: LPR lanes per row, up to NV 8-element units per lane ---------
-template <typename T, int LPR, int NV>
+// Mapped variants (kMapped): the row id is split into (i0..i3) and the row is read from / written to
+// sum_k i_k * stride[k]; everything else is the same code.
+__device__ __forceinline__ void map_row(const RowMap& m, int64_t row, int64_t& src, int64_t& dst) {
+  const int64_t a = row / m.n3, i3 = row - a * m.n3;
+  const int64_t b = a / m.n2, i2 = a - b * m.n2;
+  const int64_t i0 = b / m.n1, i1 = b - i0 * m.n1;
+  src = i0 * m.src[0] + i1 * m.src[1] + i2 * m.src[2] + i3 * m.src[3];
+  dst = i0 * m.dst[0] + i1 * m.dst[1] + i2 * m.dst[2] + i3 * m.dst[3];
+}
+
+template <typename T, int LPR, int NV, bool kMapped = false>
 __global__ __launch_bounds__(256) void fp8_quant_rows_kernel(const T* __restrict__ x,
                                                              uint8_t* __restrict__ q,
                                                              float* __restrict__ scales,
-                                                             int64_t rows, int units) {
+                                                             int64_t rows, int units, RowMap map) {
   constexpr int RPW = 64 / LPR;
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int64_t row = ((int64_t)blockIdx.x * 4 + wave) * RPW + lane / LPR;
   const int l = lane % LPR;
   const bool row_ok = row < rows;
-  const int64_t base = row * (int64_t)units * 8;
+  int64_t base = row * (int64_t)units * 8;   // first element of the row in x
+  int64_t orow = row;                         // row of q / scales
+  if (kMapped) {
+    map_row(map, row_ok ? row : 0, base, orow);
+  }
+  const int64_t obase = orow * (int64_t)units * 8;
 
   float v[NV][8];
   float a = 0.0f;
@@ -115,19 +130,19 @@ __global__ __launch_bounds__(256) void fp8_quant_rows_kernel(const T* __restrict
 #pragma unroll
   for (int off = LPR / 2; off > 0; off >>= 1) a = fmaxf(a, __shfl_xor(a, off, 64));
   const float s = scale_from_absmax(a);
-  if (row_ok && l == 0) scales[row] = s;
+  if (row_ok && l == 0) scales[orow] = s;
   const RowDiv d = make_rowdiv(s);
   if (__builtin_amdgcn_ballot_w64(!d.fast) == 0ull) {
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
       const int u = l + i * LPR;
-      if (row_ok && u < units) *reinterpret_cast<uint2*>(q + base + (int64_t)u * 8) = encode8<true>(v[i], d);
+      if (row_ok && u < units) *reinterpret_cast<uint2*>(q + obase + (int64_t)u * 8) = encode8<true>(v[i], d);
     }
   } else {
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
       const int u = l + i * LPR;
-      if (row_ok && u < units) *reinterpret_cast<uint2*>(q + base + (int64_t)u * 8) = encode8<false>(v[i], d);
+      if (row_ok && u < units) *reinterpret_cast<uint2*>(q + obase + (int64_t)u * 8) = encode8<false>(v[i], d);
     }
   }
 }
@@ -240,25 +255,55 @@ __device__ __forceinline__ void store8(bf16_t* y, const float (&a)[4], const flo
                                             pack_bf16x2(b[0], b[1]), pack_bf16x2(b[2], b[3]));
 }
 
-template <typename T, int VEC, typename IDX>
+template <typename T, int VEC, typename IDX, bool kMapped = false>
 __global__ __launch_bounds__(256) void fp8_dequant_kernel(const uint8_t* __restrict__ q,
                                                           const float* __restrict__ scales,
                                                           T* __restrict__ y, IDX total_units,
-                                                          uint32_t units_per_row) {
+                                                          uint32_t units_per_row, RowMap map) {
   const IDX g = (IDX)blockIdx.x * 256 + threadIdx.x;
   if (g >= total_units) return;
   const IDX row = g / units_per_row;   // 32-bit arithmetic whenever the tensor allows it
-  const float s = scales ? scales[row] : 1.0f;   // no scales: exact widening of the codes
-  const int64_t e = (int64_t)g * VEC;
+  int64_t e = (int64_t)g * VEC, eo = e;  // first element in q, in y
+  int64_t srow = row;
+  if (kMapped) {
+    const int64_t u = (int64_t)(g - row * units_per_row) * VEC;
+    int64_t dst;
+    map_row(map, row, srow, dst);
+    e = srow * (int64_t)units_per_row * VEC + u;
+    eo = dst + u;
+  }
+  const float s = scales ? scales[srow] : 1.0f;   // no scales: exact widening of the codes
   if constexpr (VEC == 16) {
     uint4 w = *reinterpret_cast<const uint4*>(q + e);
     float a[4], b[4];
-    decode4(w.x, s, a); decode4(w.y, s, b); store8(y + e, a, b);
-    decode4(w.z, s, a); decode4(w.w, s, b); store8(y + e + 8, a, b);
+    decode4(w.x, s, a); decode4(w.y, s, b); store8(y + eo, a, b);
+    decode4(w.z, s, a); decode4(w.w, s, b); store8(y + eo + 8, a, b);
   } else {
     uint2 w = *reinterpret_cast<const uint2*>(q + e);
     float a[4], b[4];
-    decode4(w.x, s, a); decode4(w.y, s, b); store8(y + e, a, b);
+    decode4(w.x, s, a); decode4(w.y, s, b); store8(y + eo, a, b);
+  }
+}
+
+// rows of at most 4096 elements: the single-pass kernel, plain or mapped
+template <typename T, bool kMapped>
+void quant_rows_launch(int64_t rows, int64_t units, const T* x, uint8_t* q, float* scales, const RowMap& map,
+                       hipStream_t st) {
+  auto blocks = [&](int rpw) { return (unsigned)((rows + 4 * rpw - 1) / (4 * rpw)); };
+  if (units <= 16) {
+    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 16, 1, kMapped>), dim3(blocks(4)), dim3(256), 0, st, x, q, scales, rows, (int)units, map);
+  } else if (units <= 32) {
+    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 16, 2, kMapped>), dim3(blocks(4)), dim3(256), 0, st, x, q, scales, rows, (int)units, map);
+  } else if (units <= 64) {
+    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 64, 1, kMapped>), dim3(blocks(1)), dim3(256), 0, st, x, q, scales, rows, (int)units, map);
+  } else if (units <= 128) {
+    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 64, 2, kMapped>), dim3(blocks(1)), dim3(256), 0, st, x, q, scales, rows, (int)units, map);
+  } else if (units <= 256) {
+    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 64, 4, kMapped>), dim3(blocks(1)), dim3(256), 0, st, x, q, scales, rows, (int)units, map);
+  } else if (units <= 384) {
+    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 64, 6, kMapped>), dim3(blocks(1)), dim3(256), 0, st, x, q, scales, rows, (int)units, map);
+  } else {
+    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 64, 8, kMapped>), dim3(blocks(1)), dim3(256), 0, st, x, q, scales, rows, (int)units, map);
   }
 }
 
@@ -266,21 +311,8 @@ template <typename T>
 usp_status quant_dispatch(int64_t rows, int64_t cols, const T* x, uint8_t* q, float* scales,
                           hipStream_t st) {
   const int64_t units = cols / 8;
-  auto blocks = [&](int rpw) { return (unsigned)((rows + 4 * rpw - 1) / (4 * rpw)); };
-  if (units <= 16) {
-    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 16, 1>), dim3(blocks(4)), dim3(256), 0, st, x, q, scales, rows, (int)units);
-  } else if (units <= 32) {
-    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 16, 2>), dim3(blocks(4)), dim3(256), 0, st, x, q, scales, rows, (int)units);
-  } else if (units <= 64) {
-    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 64, 1>), dim3(blocks(1)), dim3(256), 0, st, x, q, scales, rows, (int)units);
-  } else if (units <= 128) {
-    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 64, 2>), dim3(blocks(1)), dim3(256), 0, st, x, q, scales, rows, (int)units);
-  } else if (units <= 256) {
-    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 64, 4>), dim3(blocks(1)), dim3(256), 0, st, x, q, scales, rows, (int)units);
-  } else if (units <= 384) {
-    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 64, 6>), dim3(blocks(1)), dim3(256), 0, st, x, q, scales, rows, (int)units);
-  } else if (units <= 512) {
-    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 64, 8>), dim3(blocks(1)), dim3(256), 0, st, x, q, scales, rows, (int)units);
+  if (units <= 512) {
+    quant_rows_launch<T, false>(rows, units, x, q, scales, RowMap(), st);
   } else if (rows >= 1024 || rows * units < 4096 * 8) {
     hipLaunchKernelGGL((fp8_quant_longrow_kernel<T>), dim3((unsigned)rows), dim3(256), 0, st, x, q, scales, units);
   } else {
@@ -306,9 +338,25 @@ usp_status dequant_launch(int64_t rows, int64_t cols, const uint8_t* q, const fl
   const int64_t upr = cols / VEC, total = rows * upr;
   const dim3 grid((unsigned)((total + 255) / 256)), block(256);
   if (total < ((int64_t)1 << 31))
-    hipLaunchKernelGGL((fp8_dequant_kernel<T, VEC, uint32_t>), grid, block, 0, st, q, scales, y, (uint32_t)total, (uint32_t)upr);
+    hipLaunchKernelGGL((fp8_dequant_kernel<T, VEC, uint32_t>), grid, block, 0, st, q, scales, y, (uint32_t)total, (uint32_t)upr, RowMap());
   else
-    hipLaunchKernelGGL((fp8_dequant_kernel<T, VEC, int64_t>), grid, block, 0, st, q, scales, y, total, (uint32_t)upr);
+    hipLaunchKernelGGL((fp8_dequant_kernel<T, VEC, int64_t>), grid, block, 0, st, q, scales, y, total, (uint32_t)upr, RowMap());
+  USP_CHECK_HIP(hipGetLastError());
+  return USP_OK;
+}
+
+template <typename T>
+usp_status dequant_mapped_launch(const RowMap& m, int64_t rows, int64_t cols, const uint8_t* q, const float* scales,
+                                 T* y, hipStream_t st) {
+  if (cols % 16 == 0) {
+    const int64_t upr = cols / 16, total = rows * upr;
+    hipLaunchKernelGGL((fp8_dequant_kernel<T, 16, int64_t, true>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                       q, scales, y, total, (uint32_t)upr, m);
+  } else {
+    const int64_t upr = cols / 8, total = rows * upr;
+    hipLaunchKernelGGL((fp8_dequant_kernel<T, 8, int64_t, true>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                       q, scales, y, total, (uint32_t)upr, m);
+  }
   USP_CHECK_HIP(hipGetLastError());
   return USP_OK;
 }
@@ -332,6 +380,22 @@ usp_status launch_fp8_quant(int64_t rows, int64_t cols, int in_dt, const void* x
   }
   if (in_dt == USP_BF16) return quant_dispatch<bf16_t>(rows, cols, (const bf16_t*)x, q, scales, st);
   return quant_dispatch<float>(rows, cols, (const float*)x, q, scales, st);
+}
+
+usp_status launch_fp8_quant_mapped(const RowMap& m, int64_t rows, int64_t cols, int in_dt, const void* x,
+                                   uint8_t* q, float* scales, hipStream_t st) {
+  if (rows == 0 || cols == 0) return USP_OK;
+  if (in_dt == USP_BF16) quant_rows_launch<bf16_t, true>(rows, cols / 8, (const bf16_t*)x, q, scales, m, st);
+  else quant_rows_launch<float, true>(rows, cols / 8, (const float*)x, q, scales, m, st);
+  USP_CHECK_HIP(hipGetLastError());
+  return USP_OK;
+}
+
+usp_status launch_fp8_dequant_mapped(const RowMap& m, int64_t rows, int64_t cols, int out_dt, const uint8_t* q,
+                                     const float* scales, void* y, hipStream_t st) {
+  if (rows == 0 || cols == 0) return USP_OK;
+  if (out_dt == USP_BF16) return dequant_mapped_launch<bf16_t>(m, rows, cols, q, scales, (bf16_t*)y, st);
+  return dequant_mapped_launch<float>(m, rows, cols, q, scales, (float*)y, st);
 }
 
 usp_status launch_fp8_dequant(int64_t rows, int64_t cols, int out_dt, const uint8_t* q,

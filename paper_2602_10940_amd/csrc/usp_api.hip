@@ -208,6 +208,59 @@ usp_status usp_fp8_dequant(int64_t rows, int64_t cols, int32_t out_dt, const uin
   return launch_fp8_dequant(rows, cols, out_dt, q, scales, y, (hipStream_t)stream);
 }
 
+namespace {
+// Validates a row map and turns it into the kernels' form; *rows receives n0*n1*n2*n3.
+usp_status check_row_map(const usp_row_map* map, int64_t cols, int64_t elt_src, int64_t elt_dst, RowMap* m, int64_t* rows) {
+  USP_CHECK_ARG(map != nullptr, "map is NULL");
+  USP_CHECK_ARG(cols >= 0 && cols % 8 == 0 && cols <= 4096, "cols=%lld must be a multiple of 8, at most 4096", (long long)cols);
+  int64_t total = 1;
+  for (int k = 0; k < 4; ++k) {
+    USP_CHECK_ARG(map->n[k] >= 0 && map->n[k] < ((int64_t)1 << 31), "n[%d]=%lld out of range", k, (long long)map->n[k]);
+    USP_CHECK_ARG(map->src_stride[k] >= 0 && map->dst_stride[k] >= 0, "strides must be >= 0");
+    // element strides must keep rows 16-byte aligned (elt_* = bytes per element, 0 for row strides)
+    USP_CHECK_ARG(elt_src == 0 || (map->src_stride[k] * elt_src) % 16 == 0, "src_stride[%d] breaks 16-byte row alignment", k);
+    USP_CHECK_ARG(elt_dst == 0 || (map->dst_stride[k] * elt_dst) % 16 == 0, "dst_stride[%d] breaks 16-byte row alignment", k);
+    total *= map->n[k];
+    USP_CHECK_ARG(total < ((int64_t)1 << 40), "too many rows");
+    m->src[k] = map->src_stride[k];
+    m->dst[k] = map->dst_stride[k];
+  }
+  m->n1 = (uint32_t)(map->n[1] > 0 ? map->n[1] : 1);
+  m->n2 = (uint32_t)(map->n[2] > 0 ? map->n[2] : 1);
+  m->n3 = (uint32_t)(map->n[3] > 0 ? map->n[3] : 1);
+  *rows = total;
+  return USP_OK;
+}
+}  // namespace
+
+usp_status usp_fp8_quant_mapped(const usp_row_map* map, int64_t cols, int32_t in_dt, const void* x,
+                                uint8_t* q, float* scales, void* stream) {
+  clear_error();
+  USP_CHECK_ARG(in_dt == USP_F32 || in_dt == USP_BF16, "in_dt must be USP_F32 or USP_BF16");
+  RowMap m;
+  int64_t rows = 0;
+  usp_status st = check_row_map(map, cols, in_dt == USP_F32 ? 4 : 2, 0, &m, &rows);
+  if (st != USP_OK) return st;
+  if (rows == 0 || cols == 0) return USP_OK;
+  USP_CHECK_ARG(x != nullptr && q != nullptr && scales != nullptr, "x, q or scales is NULL");
+  USP_CHECK_ARG(aligned16(x) && aligned16(q), "x and q must be 16-byte aligned");
+  return launch_fp8_quant_mapped(m, rows, cols, in_dt, x, q, scales, (hipStream_t)stream);
+}
+
+usp_status usp_fp8_dequant_mapped(const usp_row_map* map, int64_t cols, int32_t out_dt, const uint8_t* q,
+                                  const float* scales, void* y, void* stream) {
+  clear_error();
+  USP_CHECK_ARG(out_dt == USP_F32 || out_dt == USP_BF16, "out_dt must be USP_F32 or USP_BF16");
+  RowMap m;
+  int64_t rows = 0;
+  usp_status st = check_row_map(map, cols, 0, out_dt == USP_F32 ? 4 : 2, &m, &rows);
+  if (st != USP_OK) return st;
+  if (rows == 0 || cols == 0) return USP_OK;
+  USP_CHECK_ARG(q != nullptr && scales != nullptr && y != nullptr, "q, scales or y is NULL");
+  USP_CHECK_ARG(aligned16(q) && aligned16(y), "q and y must be 16-byte aligned");
+  return launch_fp8_dequant_mapped(m, rows, cols, out_dt, q, scales, y, (hipStream_t)stream);
+}
+
 usp_status usp_lse_merge(int64_t rows, int32_t d, int32_t dt, const void* o1, const float* lse1,
                          const void* o2, const float* lse2, void* o_out, float* lse_out, void* stream) {
   clear_error();

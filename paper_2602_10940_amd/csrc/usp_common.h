@@ -54,6 +54,15 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
 }
 
 // ---- kernel launchers implemented in the .hip files ------------------------------------
+// Row visiting order of the mapped FP8 kernels: row id -> (i0..i3), i3 fastest -> two offsets.
+struct RowMap {
+  uint32_t n1, n2, n3;       // extents of i1..i3 (i0 is what is left)
+  int64_t src[4], dst[4];
+};
+usp_status launch_fp8_quant_mapped(const RowMap& m, int64_t rows, int64_t cols, int in_dt, const void* x,
+                                   uint8_t* q, float* scales, hipStream_t st);
+usp_status launch_fp8_dequant_mapped(const RowMap& m, int64_t rows, int64_t cols, int out_dt, const uint8_t* q,
+                                     const float* scales, void* y, hipStream_t st);
 usp_status launch_fp8_quant(int64_t rows, int64_t cols, int in_dt, const void* x, uint8_t* q,
                             float* scales, hipStream_t st);
 usp_status launch_fp8_dequant(int64_t rows, int64_t cols, int out_dt, const uint8_t* q,

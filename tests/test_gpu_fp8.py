@@ -202,3 +202,70 @@ def test_full_size_flux_payload_sampled_rows():
     np.testing.assert_array_equal(q.cpu().numpy()[rows], eq[rows])
     np.testing.assert_array_equal(host_bits_bf16(y)[rows], orc.fp8_dequant_bf16(eq[rows], es[rows]))
     assert q.numel() * 2 == x.size * 2 and q.element_size() == 1   # half the bf16 volume
+
+
+# ---------------------------------------------------------------------------
+# pack / unpack in the layouts on either side of the All-to-All (section 2.2.1)
+# ---------------------------------------------------------------------------
+def _a2a_maps(N, B, H, S_loc, D):
+    Hn, S = H // N, N * S_loc
+    return {"n": (N, B, Hn, S_loc), "dense": (B * Hn * S_loc, Hn * S_loc, S_loc, 1),
+            "seq_sharded": (Hn * S_loc * D, H * S_loc * D, S_loc * D, D),    # into [B,H,S_loc,D]
+            "head_sharded": (S_loc * D, Hn * S * D, S * D, D)}               # into [B,Hn,S,D]
+
+
+@pytest.mark.parametrize("N,B,H,S_loc,D,dtype", [
+    (4, 2, 8, 37, 128, "bf16"), (2, 1, 6, 100, 64, "bf16"), (8, 1, 24, 9, 128, "f32"), (3, 2, 3, 5, 4096, "bf16"),
+])
+def test_mapped_pack_and_unpack_bit_exact(N, B, H, S_loc, D, dtype):
+    P = _usp()
+    m = _a2a_maps(N, B, H, S_loc, D)
+    Hn, S = H // N, N * S_loc
+    up = dev_bf16 if dtype == "bf16" else dev_f32
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    for side, shape in (("seq_sharded", (B, H, S_loc, D)), ("head_sharded", (B, Hn, S, D))):
+        x = W.make_matrix(300 + N + S_loc, int(np.prod(shape[:-1])), D, dtype, "wide").reshape(shape)
+        q, s = P.usp_fp8_quant_mapped(up(x), m["n"], m[side], m["dense"], D)
+        torch.cuda.synchronize()
+        eq, es = orc.fp8_quant_mapped(x, m["n"], m[side], m["dense"], D)
+        np.testing.assert_array_equal(q.cpu().numpy(), eq)
+        np.testing.assert_array_equal(s.cpu().numpy().view(np.uint32), es.view(np.uint32))
+        y = torch.zeros(shape, dtype=tdt, device=DEV)
+        P.usp_fp8_dequant_mapped(q, s, m["n"], m["dense"], m[side], y)
+        torch.cuda.synchronize()
+        ey = orc.fp8_dequant_mapped(eq, es, m["n"], m["dense"], m[side], D, x.size, to_bf16=(dtype == "bf16"))
+        got = host_bits_bf16(y).reshape(-1) if dtype == "bf16" else y.cpu().numpy().view(np.uint32).reshape(-1)
+        exp = W.f32_to_bf16_bits(ey) if dtype == "bf16" else ey.view(np.uint32)
+        np.testing.assert_array_equal(got, exp.reshape(-1))
+
+
+def test_four_rank_exchange_on_one_gpu():
+    """Section 2.2.1's example (4 ranks, 8 heads, 1024 tokens) with the ranks played in turn by one
+    GPU and the all_to_all by block slicing: [B,8,256,D] -> [B,2,1024,D], bit-equal to quantising
+    and dequantising the whole [B,8,1024,D] tensor row by row."""
+    P = _usp()
+    N, B, H, S_loc, D = 4, 1, 8, 256, 128
+    Hn, S = H // N, N * S_loc
+    m = _a2a_maps(N, B, H, S_loc, D)
+    full = W.make_matrix(77, B * H * S, D, "bf16").reshape(B, H, S, D)
+    xs = [np.ascontiguousarray(full[:, :, r * S_loc:(r + 1) * S_loc]) for r in range(N)]
+    send = [P.usp_fp8_quant_mapped(dev_bf16(x), m["n"], m["seq_sharded"], m["dense"], D) for x in xs]
+    fq, fs = orc.fp8_quant(full.reshape(-1, D))
+    want = orc.fp8_dequant_bf16(fq, fs).reshape(B, H, S, D)      # bf16 bit patterns
+    blk = B * Hn * S_loc
+    for r in range(N):
+        rq = torch.cat([send[src][0][r * blk:(r + 1) * blk] for src in range(N)])
+        rs = torch.cat([send[src][1][r * blk:(r + 1) * blk] for src in range(N)])
+        y = torch.zeros((B, Hn, S, D), dtype=torch.bfloat16, device=DEV)
+        P.usp_fp8_dequant_mapped(rq, rs, m["n"], m["dense"], m["head_sharded"], y)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(host_bits_bf16(y), want[:, r * Hn:(r + 1) * Hn])
+
+
+def test_mapped_arguments_are_checked():
+    P = _usp()
+    x = torch.zeros((4, 8, 16), dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(P.UspError):     # row stride of 4 bf16 = 8 bytes: rows not 16-byte aligned
+        P.usp_fp8_quant_mapped(x, (1, 1, 4, 8), (0, 0, 128, 4), (32, 32, 8, 1), 16)
+    with pytest.raises(P.UspError):     # cols beyond the single-pass kernel
+        P.usp_fp8_quant_mapped(x, (1, 1, 1, 1), (0, 0, 0, 0), (1, 1, 1, 1), 8192)

@@ -270,6 +270,8 @@ def test_mapped_quant_is_a_transpose_of_the_plain_result():
     np.testing.assert_array_equal(s.reshape(N, B, H // N, S_loc), ps.reshape(B, N, H // N, S_loc).transpose(1, 0, 2, 3))
     y = orc.fp8_dequant_mapped(q, s, m["n"], m["dense"], m["seq_sharded"], D, x.size, to_bf16=False)
     np.testing.assert_array_equal(y.reshape(x.shape), orc.fp8_dequant(pq, ps).reshape(x.shape))
+    yb = orc.fp8_dequant_mapped(q, s, m["n"], m["dense"], m["seq_sharded"], D, x.size, to_bf16=True)
+    np.testing.assert_array_equal(orc.round_to_bf16(yb).reshape(x.shape), orc.fp8_dequant_bf16(pq, ps).reshape(x.shape))
 
 
 def test_four_rank_exchange_of_section_2_2_1():
