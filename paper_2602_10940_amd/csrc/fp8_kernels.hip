@@ -12,6 +12,11 @@ namespace usp {
 namespace {
 
 constexpr float kFp8Max = 448.0f;
+// Launches whose output is smaller than these are written with streaming stores (see store8_nt):
+// the dequantiser's 2- or 4-byte outputs up to 64 MB (measured crossover between 57 and 85 MB), the
+// quantiser's codes, a third of its traffic, up to 256 MB (faster at every size measured, to 114 MB)
+constexpr int64_t kStreamDequantBelowBytes = 64ll << 20;
+constexpr int64_t kStreamQuantBelowBytes = 256ll << 20;
 
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
@@ -88,6 +93,18 @@ __device__ __forceinline__ float scale_from_absmax(float a) {
   return s == 0.0f ? 1.0f : s;
 }
 
+// Eight codes to memory; streaming (non-temporal) when the launch is small: see the note at store8_nt.
+template <bool kNT>
+__device__ __forceinline__ void put_codes(uint8_t* p, uint2 w) {
+  typedef uint32_t u32x2_v __attribute__((ext_vector_type(2)));
+  if (kNT) {
+    const u32x2_v v = {w.x, w.y};
+    __builtin_nontemporal_store(v, reinterpret_cast<u32x2_v*>(p));
+  } else {
+    *reinterpret_cast<uint2*>(p) = w;
+  }
+}
+
 // ---- rows that fit one wave: LPR lanes per row, up to NV 8-element units per lane ---------
 // Mapped variants (kMapped): the row id is split into (i0..i3) and the row is read from / written to
 // sum_k i_k * stride[k]; everything else is the same code.
@@ -99,7 +116,7 @@ __device__ __forceinline__ void map_row(const RowMap& m, int64_t row, int64_t& s
   dst = i0 * m.dst[0] + i1 * m.dst[1] + i2 * m.dst[2] + i3 * m.dst[3];
 }
 
-template <typename T, int LPR, int NV, bool kMapped = false>
+template <typename T, int LPR, int NV, bool kMapped = false, bool kNT = false>
 __global__ __launch_bounds__(256) void fp8_quant_rows_kernel(const T* __restrict__ x,
                                                              uint8_t* __restrict__ q,
                                                              float* __restrict__ scales,
@@ -136,13 +153,13 @@ __global__ __launch_bounds__(256) void fp8_quant_rows_kernel(const T* __restrict
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
       const int u = l + i * LPR;
-      if (row_ok && u < units) *reinterpret_cast<uint2*>(q + obase + (int64_t)u * 8) = encode8<true>(v[i], d);
+      if (row_ok && u < units) put_codes<kNT>(q + obase + (int64_t)u * 8, encode8<true>(v[i], d));
     }
   } else {
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
       const int u = l + i * LPR;
-      if (row_ok && u < units) *reinterpret_cast<uint2*>(q + obase + (int64_t)u * 8) = encode8<false>(v[i], d);
+      if (row_ok && u < units) put_codes<kNT>(q + obase + (int64_t)u * 8, encode8<false>(v[i], d));
     }
   }
 }
@@ -254,8 +271,23 @@ __device__ __forceinline__ void store8(bf16_t* y, const float (&a)[4], const flo
   *reinterpret_cast<uint4*>(y) = make_uint4(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]),
                                             pack_bf16x2(b[0], b[1]), pack_bf16x2(b[2], b[3]));
 }
+// Streaming (non-temporal) stores leave no dirty lines in the L2s for the end of the kernel to write
+// back: worth 2 us on a 28 MB launch whose successor starts right behind it, but slower than cached
+// stores once the output is several times the L2 capacity.  The launchers pick by output size.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void store8_nt(float* y, const float (&a)[4], const float (&b)[4]) {
+  typedef float f32x4_t __attribute__((ext_vector_type(4)));
+  const f32x4_t va = {a[0], a[1], a[2], a[3]}, vb = {b[0], b[1], b[2], b[3]};
+  __builtin_nontemporal_store(va, reinterpret_cast<f32x4_t*>(y));
+  __builtin_nontemporal_store(vb, reinterpret_cast<f32x4_t*>(y + 4));
+}
+__device__ __forceinline__ void store8_nt(bf16_t* y, const float (&a)[4], const float (&b)[4]) {
+  const u32x4_t v = {pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]), pack_bf16x2(b[0], b[1]), pack_bf16x2(b[2], b[3])};
+  __builtin_nontemporal_store(v, reinterpret_cast<u32x4_t*>(y));
+}
 
-template <typename T, int VEC, typename IDX, bool kMapped = false>
+template <typename T, int VEC, typename IDX, bool kMapped = false, bool kNT = false>
 __global__ __launch_bounds__(256) void fp8_dequant_kernel(const uint8_t* __restrict__ q,
                                                           const float* __restrict__ scales,
                                                           T* __restrict__ y, IDX total_units,
@@ -273,38 +305,49 @@ __global__ __launch_bounds__(256) void fp8_dequant_kernel(const uint8_t* __restr
     eo = dst + u;
   }
   const float s = scales ? scales[srow] : 1.0f;   // no scales: exact widening of the codes
+  auto put8 = [&](T* p, const float (&a)[4], const float (&b)[4]) {
+    if (kNT) store8_nt(p, a, b);
+    else store8(p, a, b);
+  };
   if constexpr (VEC == 16) {
     uint4 w = *reinterpret_cast<const uint4*>(q + e);
     float a[4], b[4];
-    decode4(w.x, s, a); decode4(w.y, s, b); store8(y + eo, a, b);
-    decode4(w.z, s, a); decode4(w.w, s, b); store8(y + eo + 8, a, b);
+    decode4(w.x, s, a); decode4(w.y, s, b); put8(y + eo, a, b);
+    decode4(w.z, s, a); decode4(w.w, s, b); put8(y + eo + 8, a, b);
   } else {
     uint2 w = *reinterpret_cast<const uint2*>(q + e);
     float a[4], b[4];
-    decode4(w.x, s, a); decode4(w.y, s, b); store8(y + eo, a, b);
+    decode4(w.x, s, a); decode4(w.y, s, b); put8(y + eo, a, b);
   }
 }
 
 // rows of at most 4096 elements: the single-pass kernel, plain or mapped
+template <typename T, bool kMapped, bool kNT>
+void quant_rows_launch_nt(int64_t rows, int64_t units, const T* x, uint8_t* q, float* scales, const RowMap& map,
+                          hipStream_t st) {
+  auto blocks = [&](int rpw) { return (unsigned)((rows + 4 * rpw - 1) / (4 * rpw)); };
+  if (units <= 16) {
+    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 16, 1, kMapped, kNT>), dim3(blocks(4)), dim3(256), 0, st, x, q, scales, rows, (int)units, map);
+  } else if (units <= 32) {
+    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 16, 2, kMapped, kNT>), dim3(blocks(4)), dim3(256), 0, st, x, q, scales, rows, (int)units, map);
+  } else if (units <= 64) {
+    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 64, 1, kMapped, kNT>), dim3(blocks(1)), dim3(256), 0, st, x, q, scales, rows, (int)units, map);
+  } else if (units <= 128) {
+    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 64, 2, kMapped, kNT>), dim3(blocks(1)), dim3(256), 0, st, x, q, scales, rows, (int)units, map);
+  } else if (units <= 256) {
+    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 64, 4, kMapped, kNT>), dim3(blocks(1)), dim3(256), 0, st, x, q, scales, rows, (int)units, map);
+  } else if (units <= 384) {
+    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 64, 6, kMapped, kNT>), dim3(blocks(1)), dim3(256), 0, st, x, q, scales, rows, (int)units, map);
+  } else {
+    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 64, 8, kMapped, kNT>), dim3(blocks(1)), dim3(256), 0, st, x, q, scales, rows, (int)units, map);
+  }
+}
+
 template <typename T, bool kMapped>
 void quant_rows_launch(int64_t rows, int64_t units, const T* x, uint8_t* q, float* scales, const RowMap& map,
                        hipStream_t st) {
-  auto blocks = [&](int rpw) { return (unsigned)((rows + 4 * rpw - 1) / (4 * rpw)); };
-  if (units <= 16) {
-    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 16, 1, kMapped>), dim3(blocks(4)), dim3(256), 0, st, x, q, scales, rows, (int)units, map);
-  } else if (units <= 32) {
-    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 16, 2, kMapped>), dim3(blocks(4)), dim3(256), 0, st, x, q, scales, rows, (int)units, map);
-  } else if (units <= 64) {
-    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 64, 1, kMapped>), dim3(blocks(1)), dim3(256), 0, st, x, q, scales, rows, (int)units, map);
-  } else if (units <= 128) {
-    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 64, 2, kMapped>), dim3(blocks(1)), dim3(256), 0, st, x, q, scales, rows, (int)units, map);
-  } else if (units <= 256) {
-    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 64, 4, kMapped>), dim3(blocks(1)), dim3(256), 0, st, x, q, scales, rows, (int)units, map);
-  } else if (units <= 384) {
-    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 64, 6, kMapped>), dim3(blocks(1)), dim3(256), 0, st, x, q, scales, rows, (int)units, map);
-  } else {
-    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 64, 8, kMapped>), dim3(blocks(1)), dim3(256), 0, st, x, q, scales, rows, (int)units, map);
-  }
+  if (rows * units * 8 < kStreamQuantBelowBytes) quant_rows_launch_nt<T, kMapped, true>(rows, units, x, q, scales, map, st);
+  else quant_rows_launch_nt<T, kMapped, false>(rows, units, x, q, scales, map, st);
 }
 
 template <typename T>
@@ -337,7 +380,10 @@ usp_status dequant_launch(int64_t rows, int64_t cols, const uint8_t* q, const fl
                           hipStream_t st) {
   const int64_t upr = cols / VEC, total = rows * upr;
   const dim3 grid((unsigned)((total + 255) / 256)), block(256);
-  if (total < ((int64_t)1 << 31))
+  const bool nt = rows * cols * (int64_t)sizeof(T) < kStreamDequantBelowBytes;
+  if (total < ((int64_t)1 << 31) && nt)
+    hipLaunchKernelGGL((fp8_dequant_kernel<T, VEC, uint32_t, false, true>), grid, block, 0, st, q, scales, y, (uint32_t)total, (uint32_t)upr, RowMap());
+  else if (total < ((int64_t)1 << 31))
     hipLaunchKernelGGL((fp8_dequant_kernel<T, VEC, uint32_t>), grid, block, 0, st, q, scales, y, (uint32_t)total, (uint32_t)upr, RowMap());
   else
     hipLaunchKernelGGL((fp8_dequant_kernel<T, VEC, int64_t>), grid, block, 0, st, q, scales, y, total, (uint32_t)upr, RowMap());
@@ -348,14 +394,17 @@ usp_status dequant_launch(int64_t rows, int64_t cols, const uint8_t* q, const fl
 template <typename T>
 usp_status dequant_mapped_launch(const RowMap& m, int64_t rows, int64_t cols, const uint8_t* q, const float* scales,
                                  T* y, hipStream_t st) {
+  const bool nt = rows * cols * (int64_t)sizeof(T) < kStreamDequantBelowBytes;
   if (cols % 16 == 0) {
     const int64_t upr = cols / 16, total = rows * upr;
-    hipLaunchKernelGGL((fp8_dequant_kernel<T, 16, int64_t, true>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                       q, scales, y, total, (uint32_t)upr, m);
+    const dim3 grid((unsigned)((total + 255) / 256));
+    if (nt) hipLaunchKernelGGL((fp8_dequant_kernel<T, 16, int64_t, true, true>), grid, dim3(256), 0, st, q, scales, y, total, (uint32_t)upr, m);
+    else hipLaunchKernelGGL((fp8_dequant_kernel<T, 16, int64_t, true, false>), grid, dim3(256), 0, st, q, scales, y, total, (uint32_t)upr, m);
   } else {
     const int64_t upr = cols / 8, total = rows * upr;
-    hipLaunchKernelGGL((fp8_dequant_kernel<T, 8, int64_t, true>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                       q, scales, y, total, (uint32_t)upr, m);
+    const dim3 grid((unsigned)((total + 255) / 256));
+    if (nt) hipLaunchKernelGGL((fp8_dequant_kernel<T, 8, int64_t, true, true>), grid, dim3(256), 0, st, q, scales, y, total, (uint32_t)upr, m);
+    else hipLaunchKernelGGL((fp8_dequant_kernel<T, 8, int64_t, true, false>), grid, dim3(256), 0, st, q, scales, y, total, (uint32_t)upr, m);
   }
   USP_CHECK_HIP(hipGetLastError());
   return USP_OK;
