@@ -189,7 +189,10 @@ __device__ __forceinline__ void finish_and_store(const AttnStep& s, f32x16 (&oac
       *reinterpret_cast<float4*>(s.acc + row * kD + 4 * c) = make_float4(o[0], o[1], o[2], o[3]);
     else {
       bf16_t* outp = (bf16_t*)s.out + b * s.os[0] + h * s.os[1] + (int64_t)(q0 + r) * s.os[2];
-      *reinterpret_cast<uint2*>(outp + 4 * c) = make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
+      // the final output is not read again here: a streaming store leaves no dirty line for the
+      // end of the kernel to write back (the fp32 carry above is re-read by the next step and stays cached)
+      { const u32x2 v = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x2*>(outp + 4 * c)); }
     }
   }
 }
