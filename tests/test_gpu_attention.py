@@ -180,16 +180,19 @@ def test_batch_of_three_with_a_different_mask_per_entry(kernel):
     _assert_parity(host_f64(fo), host_f64(fl_), ro8, rl8)
 
 
-def test_strided_layouts():
-    """[B,S,H,d] storage viewed as [B,H,S,d]: token stride H*d, head stride d."""
+@pytest.mark.parametrize("kernel,Sc", [("auto", 96), ("wide", 128), ("split", 192), ("mixed", 320)])
+def test_strided_layouts(kernel, Sc):
+    """[B,S,H,d] storage viewed as [B,H,S,d]: token stride H*d, head stride d; chunk lengths with and
+    without a ragged last tile (the kernels with and without per-tile key records)."""
     P = _P()
-    inp = W.make_attention_inputs(_small_wl("flux1024_u", 3, 130, (96,)))
+    inp = W.make_attention_inputs(_small_wl("flux1024_u", 3, 130, (Sc,)))
     def bshd(x):
         t = dev_bf16(np.ascontiguousarray(x.transpose(0, 2, 1, 3)))
         return t.permute(0, 2, 1, 3)
     q, k, v = bshd(inp.q), bshd(inp.k[0]), bshd(inp.v[0])
     out = torch.empty((1, 130, 3, 128), dtype=torch.bfloat16, device=DEV).permute(0, 2, 1, 3)
-    o, l = P.usp_ring_attn_fwd(q, [k], [v], softmax_scale=float(inp.softmax_scale), out=out)
+    o, l = P.usp_ring_attn_fwd(q, [k], [v], softmax_scale=float(inp.softmax_scale), out=out,
+                               flags=_KERNEL_FLAG[kernel])
     torch.cuda.synchronize()
     ro, rl = _oracle(inp)
     _assert_parity(host_f64(o), host_f64(l), ro, rl)
