@@ -18,4 +18,4 @@ def test_bench_and_smoke_do_not_reach_outside_the_repository():
     """The GPU machine has no reference tree: nothing the driver runs there may name it."""
     for name in ("bench.py", "__graft_entry__.py"):
         src = open(os.path.join(ROOT, name)).read()
-        assert "/root/reference" not in src and "_work" not in src
+        assert "/root/reference" not in src and "_work/" not in src
