@@ -483,45 +483,73 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
       oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pb, oacc[dt], 0, 0, 0);
     }
   };
-  // matrix phase: O += P V (V tile in stage SV) interleaved with the scores of the next tile (K in
-  // stage SK).  Only this wave feeds the SIMD's matrix core during the phase, so its LDS operand
-  // reads are scheduled eight MFMAs ahead of their use (sched_group_barrier: 0x008 MFMA, 0x100 LDS read).
+  // matrix phase: O += P V (V tile in stage sv) interleaved with the scores of the next tile (K in
+  // stage sk), in four blocks of eight MFMAs (four for P.V over 16 keys, four for the scores of 32
+  // keys over half the head dimension).  Only this wave feeds the SIMD's matrix core during the
+  // phase, so its LDS operand reads run one block (eight MFMAs, twelve reads) ahead of their use.
+  // The order is written out and pinned (sched_barrier after every MFMA and the reads issued behind
+  // it) rather than left to the instruction scheduler, whose choice changes with the code around it.
+  auto v_operand = [&](int stage, int blk, int dt) -> bf16x8 {
+    const u32x2 lo = lds_read_tr3(v_rd[dt] + stage * kTileB + 16 * blk * kRowB);
+    const u32x2 hi = lds_read_tr3(v_rd[dt] + stage * kTileB + (16 * blk + 8) * kRowB);
+    return __builtin_bit_cast(bf16x8, u32x4{lo[0], lo[1], hi[0], hi[1]});
+  };
+  auto k_operand = [&](int stage, int blk, int i) -> bf16x8 {   // block blk: keys 32 * (blk >> 1) .., head dims 64 * (blk & 1) + 16 * i ..
+    return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(
+        k_rd[4 * (blk & 1) + i] + stage * kTileB + 32 * (blk >> 1) * kRowB);
+  };
   auto MM_full = [&](int sv, int sk) {
     __builtin_amdgcn_s_setprio(2);
+    bf16x8 va[2][4], ka[2][4];
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
+    for (int i = 0; i < 4; ++i) va[0][i] = v_operand(sv, 0, i);
 #pragma unroll
-      for (int i = 0; i < 16; ++i) sacc[kt][i] = 0.0f;
-#pragma unroll
-    for (int blk = 0; blk < 4; ++blk) {
-      pv_block(sv, blk);
-      qk_block(sk, blk >> 1, 4 * (blk & 1));
-    }
-    __builtin_amdgcn_sched_group_barrier(0x100, kPrefetchReads, 0);
+    for (int i = 0; i < 4; ++i) ka[0][i] = k_operand(sk, 0, i);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int blk = 0; blk < 4; ++blk) {
+      const int c = blk & 1, kt = blk >> 1;
+      const bf16x8 pb = __builtin_bit_cast(bf16x8, pk[blk]);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {   // P.V group
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, kPrefetchReads == 12 ? 2 : 1, 0);
+      for (int dt = 0; dt < 4; ++dt) {
+        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[c][dt], pb, oacc[dt], 0, 0, 0);
+        if (blk < 3) va[c ^ 1][dt] = v_operand(sv, blk + 1, dt);
+        __builtin_amdgcn_sched_barrier(0);
       }
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {   // score group
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, kPrefetchReads == 12 ? 1 : 2, 0);
+      for (int i = 0; i < 4; ++i) {
+        const int ks = 4 * (blk & 1) + i;
+        if (ks == 0) {
+          f32x16 z;
+#pragma unroll
+          for (int e = 0; e < 16; ++e) z[e] = 0.0f;
+          sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[c][i], qreg[ks], z, 0, 0, 0);
+        } else {
+          sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[c][i], qreg[ks], sacc[kt], 0, 0, 0);
+        }
+        if (blk < 3) ka[c ^ 1][i] = k_operand(sk, blk + 1, i);
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
     __builtin_amdgcn_s_setprio(0);
   };
-  auto MM_last = [&](int sv) {   // last tile: no further scores
+  auto MM_last = [&](int sv) {   // last tile: no further scores; the reads run two blocks ahead
     __builtin_amdgcn_s_setprio(2);
+    bf16x8 va[4][4];
 #pragma unroll
-    for (int blk = 0; blk < 4; ++blk) pv_block(sv, blk);
-    __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);
+    for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      for (int i = 0; i < 4; ++i) va[blk][i] = v_operand(sv, blk, i);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int blk = 0; blk < 4; ++blk) {
+      const bf16x8 pb = __builtin_bit_cast(bf16x8, pk[blk]);
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt) {
+        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[blk][dt], pb, oacc[dt], 0, 0, 0);
+        if (blk < 2) va[blk + 2][dt] = v_operand(sv, blk + 2, dt);
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
     __builtin_amdgcn_s_setprio(0);
   };
