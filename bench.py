@@ -177,6 +177,21 @@ def main() -> int:
     merge_bytes = mrows * 128 * 3 * 2 + mrows * 12
     del mo1, mo2, ml1, ml2, mo, ml
 
+    # what the matrix cores sustain with nothing else issued: one work-group of 8 waves per CU doing
+    # back-to-back 32x32x16 bf16 MFMAs on register operands, ~1 ms per launch (the chip lowers its
+    # clock under a full matrix-core load, and by how much depends on the operand data)
+    def mfma_probe(random_data):
+        n_cu = torch.cuda.get_device_properties(dev).multi_processor_count
+        iters = 1000
+        pout = torch.empty((n_cu * 512,), dtype=torch.float32, device=dev)
+        pclk = torch.zeros((2,), dtype=torch.int64, device=dev)
+        t = per_launch(lambda i: P.usp_probe_mfma_rate(n_cu, iters, random_data, pout, pclk), reps=20, rounds=3)
+        cyc, ticks = [int(v) for v in pclk.cpu()]
+        fl = n_cu * 8 * iters * 32 * 32768.0
+        return {"tflops": round(fl / (t * 1e-3) * 1e-12, 1), "shader_mhz": round(cyc / max(ticks, 1) * 100.0),
+                "frac_of_bf16_peak": round(fl / (t * 1e-3) * 1e-12 / PEAK_BF16_TFLOPS, 4)}
+    probe_rand, probe_const = mfma_probe(True), mfma_probe(False)
+
     flops = wl.attn_flops()
     value = flops / (ms_per_step * 1e-3) * 1e-12
     attn_tflops = flops / (t_attn * 1e-3) * 1e-12
@@ -216,7 +231,11 @@ def main() -> int:
         "roofline": {"bound": "mfma", "achieved": round(attn_tflops, 1), "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4), "traffic": ATTN_TRAFFIC_BYTES,
                      "kernel": "attn_pp_kernel<wide, plain>", "flops_per_launch": flops},
+        "mfma_sustained": {"random_operands": probe_rand, "constant_operands": probe_const,
+                           "note": "MFMA-only probe on every CU (usp_probe_mfma_rate): the rate and clock the chip "
+                                   "holds under a full matrix-core load; the published peak assumes 2400 MHz"},
     }
+    result["roofline"]["frac_of_sustained_mfma"] = round(attn_tflops / probe_rand["tflops"], 4)
 
     if args.calibrate_copy:
         ca = torch.ones((64 << 20,), dtype=torch.int32, device=dev)

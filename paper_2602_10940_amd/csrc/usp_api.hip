@@ -274,6 +274,16 @@ usp_status usp_lse_merge(int64_t rows, int32_t d, int32_t dt, const void* o1, co
   return launch_lse_merge(rows, d, dt, o1, lse1, o2, lse2, o_out, lse_out, (hipStream_t)stream);
 }
 
+usp_status usp_probe_mfma_rate(int32_t wgs, int32_t iters, int32_t random_data, float* out, uint64_t* clocks,
+                               void* stream) {
+  clear_error();
+  USP_CHECK_ARG(wgs >= 1 && wgs <= 65536, "wgs=%d out of range [1, 65536]", wgs);
+  USP_CHECK_ARG(iters >= 1 && iters <= 1000000, "iters=%d out of range [1, 1000000]", iters);
+  USP_CHECK_ARG(out != nullptr && clocks != nullptr, "out or clocks is NULL");
+  return launch_probe_mfma_rate(wgs, iters, random_data, out, reinterpret_cast<unsigned long long*>(clocks),
+                                (hipStream_t)stream);
+}
+
 usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const void* const* k_chunks,
                              const void* const* v_chunks, const float* const* k_scales,
                              const float* const* v_scales, const uint8_t* const* key_mask, void* out,

@@ -116,6 +116,8 @@ inline int prefetch_wg_count(const AttnStep& s, int attn_wgs, int slots_per_cu) 
   const int n = spare / 8 * 8;
   return n < 16 ? 16 : (n > 64 ? 64 : n);
 }
+usp_status launch_probe_mfma_rate(int wgs, int iters, int random_data, float* out, unsigned long long* clocks,
+                                  hipStream_t st);
 usp_status launch_attn_generic(const AttnStep& s, hipStream_t st);
 usp_status launch_attn_mfma(const AttnStep& s, hipStream_t st);
 bool attn_mfma_supported(const AttnStep& s);

@@ -50,6 +50,10 @@ def test_validation_without_gpu():
     lib.usp_lse_merge.argtypes = [i64, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     assert lib.usp_lse_merge(8, 12, 1, None, None, None, None, None, None, None) == -1
     assert lib.usp_lse_merge(0, 128, 1, None, None, None, None, None, None, None) == 0
+    lib.usp_probe_mfma_rate.argtypes = [i32, i32, i32, vp, vp, vp]
+    assert lib.usp_probe_mfma_rate(0, 10, 1, None, None, None) == -1        # wgs out of range
+    assert lib.usp_probe_mfma_rate(4, 10, 1, None, None, None) == -1        # NULL buffers
+    assert b"NULL" in lib.usp_last_error()
 
 
 def test_workspace_sizes_and_descriptor_checks():
