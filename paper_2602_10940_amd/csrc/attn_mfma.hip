@@ -271,10 +271,6 @@ __device__ __forceinline__ u32x2 lds_read_tr3(const __attribute__((address_space
   return __builtin_bit_cast(u32x2, r);
 }
 
-#ifndef USP_PREFETCH_READS
-#define USP_PREFETCH_READS 12
-#endif
-constexpr int kPrefetchReads = USP_PREFETCH_READS;   // LDS reads in flight ahead of the first MFMA (8 or 12)
 
 // One work-group of 64 threads per (tile, batch*head): the record described above.  Blocks of tile 0
 // with h == 0 also count the tiles up to the last one that has a live key (n_live[b]); the
@@ -470,17 +466,6 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
       const bf16x8 a = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(
           k_rd[ks] + stage * kTileB + 32 * kt * kRowB);
       sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], sacc[kt], 0, 0, 0);
-    }
-  };
-  // O^T += V^T P^T for the 16 keys of block blk of the tile in LDS stage `stage`
-  auto pv_block = [&](int stage, int blk) {
-    const bf16x8 pb = __builtin_bit_cast(bf16x8, pk[blk]);
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt) {
-      const u32x2 lo = lds_read_tr3(v_rd[dt] + stage * kTileB + 16 * blk * kRowB);
-      const u32x2 hi = lds_read_tr3(v_rd[dt] + stage * kTileB + (16 * blk + 8) * kRowB);
-      const u32x4 av = {lo[0], lo[1], hi[0], hi[1]};
-      oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pb, oacc[dt], 0, 0, 0);
     }
   };
   // matrix phase: O += P V (V tile in stage sv) interleaved with the scores of the next tile (K in
