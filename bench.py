@@ -291,7 +291,10 @@ def ring_leg(P, W, torch, dev, up_bf16, name="flux1024_r4", reps=600):
         torch.cuda.synchronize()
         return a.elapsed_time(b) / reps
 
-    def resident():
+    def resident():       # one launch per chunk, as in the pipelined schedules
+        P.usp_ring_attn_fwd(q, ks, vs, softmax_scale=scale, flags=P.USP_ATTN_STEPWISE, out=out, lse=lse, workspace=ws)
+
+    def one_launch():     # what the plain call does with resident chunks: their tiles as one stream
         P.usp_ring_attn_fwd(q, ks, vs, softmax_scale=scale, out=out, lse=lse, workspace=ws)
 
     def pipelined():
@@ -314,9 +317,9 @@ def ring_leg(P, W, torch, dev, up_bf16, name="flux1024_r4", reps=600):
             stage[2 * (r & 1)].copy_(ks[r], non_blocking=True)
             stage[2 * (r & 1) + 1].copy_(vs[r], non_blocking=True)
             kk.append(stage[2 * (r & 1)]); vv.append(stage[2 * (r & 1) + 1])
-        P.usp_ring_attn_fwd(q, kk, vv, softmax_scale=scale, out=out, lse=lse, workspace=ws)
+        P.usp_ring_attn_fwd(q, kk, vv, softmax_scale=scale, flags=P.USP_ATTN_STEPWISE, out=out, lse=lse, workspace=ws)
 
-    t_c, t_m, t_p, t_f, t_s = (timed(f) for f in (resident, copies_only, pipelined, fused, serial))
+    t_c, t_m, t_p, t_f, t_s, t_1 = (timed(f) for f in (resident, copies_only, pipelined, fused, serial, one_launch))
     hid = lambda t: round(max(0.0, min(1.0, 1.0 - (t - t_c) / t_m)), 3) if t_m > 0 else None
     flops = wl.attn_flops()
     tf = lambda t: round(flops / (t * 1e-3) * 1e-12, 1)
@@ -326,6 +329,8 @@ def ring_leg(P, W, torch, dev, up_bf16, name="flux1024_r4", reps=600):
             "hidden_fraction_side_stream": hid(t_p), "hidden_fraction_fused_prefetch": hid(t_f),
             "serial_over_side_stream": round(t_s / t_p, 3), "serial_over_fused_prefetch": round(t_s / t_f, 3),
             "tflops_resident": tf(t_c), "tflops_side_stream": tf(t_p), "tflops_fused_prefetch": tf(t_f),
+            "t_resident_one_launch_ms": round(t_1, 4), "tflops_resident_one_launch": tf(t_1),
+            "frac_of_bf16_peak_one_launch": round(flops / (t_1 * 1e-3) * 1e-12 / PEAK_BF16_TFLOPS, 4),
             "note": "on-device copies stand in for ring recv; an xGMI link is ~50x slower"}
 
 

@@ -59,6 +59,12 @@ typedef enum {
 #define USP_ATTN_KERNEL_WIDE 4u   /* 256 queries per work-group, every wave visits every key */
 #define USP_ATTN_KERNEL_SPLIT 8u  /* 128 queries per work-group, the two wave groups take alternate
                                      64-key tiles and combine their partial results at the end */
+#define USP_ATTN_STEPWISE 64u     /* one attention launch per chunk even where one launch could cover the
+                                     whole ring: without the double-buffering flags, bf16 chunks with
+                                     d = 128 that need no mask and whose lengths are multiples of 64 (2 to 16
+                                     of them non-empty) are otherwise taken as one stream of key tiles by a
+                                     single launch, the running softmax state staying in registers
+                                     from the first chunk to the last.  Same result up to rounding order. */
 #define USP_ATTN_KERNEL_MIXED 32u /* one launch of both: 256-query work-groups, and the blocks of the
                                      last, partly filled round as pairs of key-split work-groups
                                      (forced: the second half of all blocks) */

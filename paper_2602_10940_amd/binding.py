@@ -21,6 +21,7 @@ USP_ATTN_DOUBLE_BUFFER, USP_ATTN_UNFUSED_MERGE = 1, 2
 USP_ATTN_KERNEL_WIDE, USP_ATTN_KERNEL_SPLIT = 4, 8
 USP_ATTN_FUSED_PREFETCH = 16
 USP_ATTN_KERNEL_MIXED = 32
+USP_ATTN_STEPWISE = 64
 
 EXPORTS = ("usp_ring_attn_workspace_bytes", "usp_ring_attn_fwd", "usp_lse_merge", "usp_fp8_quant",
            "usp_fp8_dequant", "usp_fp8_quant_mapped", "usp_fp8_dequant_mapped", "usp_probe_mfma_rate",

@@ -306,8 +306,9 @@ __global__ __launch_bounds__(64) void attn_ext_prepare_kernel(AttnStep s, float*
 }
 
 // One work-group's share: the queries q_base .. q_base + 255 (wide) or + 127 (split) of (batch, head) bh_.
-template <bool kSplit, bool kExt>
+template <bool kSplit, bool kExt, bool kMulti = false>
 __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* smem_raw, int bh_, int q_base) {
+  static_assert(!(kExt && kMulti), "several chunks per launch: plain chunks only");
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it in an SGPR
@@ -325,7 +326,11 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
   // plain: the host guarantees Sc % 64 == 0 and Sc > 0.  extended: tiles up to the last live key;
   // the last tile of the chunk may be ragged (tail_tile), none may be left (nt == 0).
   const int nt_all = (s.Sc + kTile - 1) / kTile;
-  const int nt = kExt ? min(nt_all, __builtin_amdgcn_readfirstlane(s.n_live[b])) : s.Sc / kTile;
+  int nt_multi = 0;
+  if (kMulti)
+    for (int c = 0; c < s.n_multi; ++c) nt_multi += s.chunk[c].Sc / kTile;
+  const int nt = kMulti ? nt_multi
+                        : kExt ? min(nt_all, __builtin_amdgcn_readfirstlane(s.n_live[b])) : s.Sc / kTile;
   const int tail_tile = (kExt && (s.Sc % kTile) != 0) ? nt_all - 1 : -1;
   const int tail_last_row = s.Sc - (nt_all - 1) * kTile - 1;   // last valid row of the ragged tile
 
@@ -388,18 +393,30 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
     if (kSplit) { issue_v_half(tile, tile_idx, stage, 0, true); issue_v_half(tile, tile_idx, stage, 1, true); }
   };
 
+  // Where tile idx of the K (or V) stream starts.  kMulti: the tiles of the chunks follow one another;
+  // a cursor (chunk, index of its first tile) moves forward with the indices asked for.
+  struct TileCursor { int c, first; };
+  auto tile_at = [&](TileCursor& cur, int idx, bool is_v) -> const unsigned char* {
+    if (!kMulti) return (is_v ? vb : kb) + idx * tileB;
+    while (idx >= cur.first + s.chunk[cur.c].Sc / kTile) { cur.first += s.chunk[cur.c].Sc / kTile; ++cur.c; }
+    const AttnStep::Chunk& ch = s.chunk[cur.c];
+    const bf16_t* base = (const bf16_t*)(is_v ? ch.v : ch.k) + b * ch.ks0 + h * ch.ks1;
+    return (const unsigned char*)base + (idx - cur.first) * tileB;
+  };
+  TileCursor kcur{0, 0}, vcur{0, 0};
+
   // Tiles needed before the first loads of the softmax phases land are fetched here.
   //   wide : A's SM(j) prefetches K(j+2) (with its record) and V(j+1); B's SM(j), one phase later,
   //          K(j+3) and V(j+2).
   //   split: the softmax phase p prefetches K(p+3), V(p+1) and the record of tile p+2.
   int kpre_idx, vpre_idx;   // next K / V tile this wave prefetches
   if (!kSplit) {
-    issue_k_half(kb, 0, 0, 0, false); issue_k_half(kb, 0, 0, 1, false);
-    issue_v_half(vb, 0, 0, 0, false); issue_v_half(vb, 0, 0, 1, false);
-    if (nt > 1) { issue_k_half(kb + tileB, 1, 1, 0, false); issue_k_half(kb + tileB, 1, 1, 1, false); }
+    { const unsigned char* t = tile_at(kcur, 0, false); issue_k_half(t, 0, 0, 0, false); issue_k_half(t, 0, 0, 1, false); }
+    { const unsigned char* t = tile_at(vcur, 0, true); issue_v_half(t, 0, 0, 0, false); issue_v_half(t, 0, 0, 1, false); }
+    if (nt > 1) { const unsigned char* t = tile_at(kcur, 1, false); issue_k_half(t, 1, 1, 0, false); issue_k_half(t, 1, 1, 1, false); }
     if (!grpA) {
-      if (nt > 1) { issue_v_half(vb + tileB, 1, 1, 0, false); issue_v_half(vb + tileB, 1, 1, 1, false); }
-      if (nt > 2) { issue_k_half(kb + 2 * tileB, 2, 2, 0, false); issue_k_half(kb + 2 * tileB, 2, 2, 1, false); }
+      if (nt > 1) { const unsigned char* t = tile_at(vcur, 1, true); issue_v_half(t, 1, 1, 0, false); issue_v_half(t, 1, 1, 1, false); }
+      if (nt > 2) { const unsigned char* t = tile_at(kcur, 2, false); issue_k_half(t, 2, 2, 0, false); issue_k_half(t, 2, 2, 1, false); }
     } else if (kExt) {
       issue_ext(0, 0);
       if (nt > 1) issue_ext(1, 1);
@@ -408,10 +425,10 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
     vpre_idx = grpA ? 1 : 2;
   } else {
     if (grpA) {   // the loading lambdas of the split kernel move a wave pair's rows: one group suffices
-      issue_k_tile(kb, 0, 0);
-      issue_v_tile(vb, 0, 0);
-      if (nt > 1) issue_k_tile(kb + tileB, 1, 1);
-      if (nt > 2) issue_k_tile(kb + 2 * tileB, 2, 2);
+      issue_k_tile(tile_at(kcur, 0, false), 0, 0);
+      issue_v_tile(tile_at(vcur, 0, true), 0, 0);
+      if (nt > 1) issue_k_tile(tile_at(kcur, 1, false), 1, 1);
+      if (nt > 2) issue_k_tile(tile_at(kcur, 2, false), 2, 2);
       if (kExt) {
         issue_ext(0, 0);
         if (nt > 1) issue_ext(1, 1);
@@ -420,8 +437,8 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
     kpre_idx = grpA ? 3 : 4;   // K(p+3) / V(p+1) of this group's first softmax phase, p = 0 (A) or 1 (B)
     vpre_idx = grpA ? 1 : 2;
   }
-  const unsigned char* kpre = kb + kpre_idx * tileB;
-  const unsigned char* vpre = vb + vpre_idx * tileB;
+  const unsigned char* kpre = kMulti ? nullptr : kb + kpre_idx * tileB;   // kMulti: looked up when the load is issued
+  const unsigned char* vpre = kMulti ? nullptr : vb + vpre_idx * tileB;
   constexpr int kPreStep = kSplit ? 2 : 1;   // tiles between two softmax phases of a wave
 
   // Q^T operand: lane (n, g) holds Q[q0+n][16*ks + 8*g .. +7] for ks = 0..7
@@ -646,6 +663,10 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
       }
       __builtin_amdgcn_sched_barrier(0);
     }
+    if (kMulti) {
+      if (do_k) kpre = tile_at(kcur, kpre_idx, false);
+      if (do_v) vpre = tile_at(vcur, vpre_idx, true);
+    }
     // sched_barrier: keep each load between two blocks of arithmetic (the scheduler would
     // otherwise hoist all of them to the top, where they queue behind one another)
     if (!kSplit) {
@@ -677,8 +698,9 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
       exp_block(1, 1, psum, xs, dead_keys);
       __builtin_amdgcn_sched_barrier(0);
     }
-    kpre += kPreStep * tileB; kpre_idx += kPreStep;
-    vpre += kPreStep * tileB; vpre_idx += kPreStep;
+    if (!kMulti) { kpre += kPreStep * tileB; vpre += kPreStep * tileB; }
+    kpre_idx += kPreStep;
+    vpre_idx += kPreStep;
     if (__builtin_amdgcn_ballot_w64(!(psum <= 65536.0f)) != 0ull) {
       LAB_COUNT_SLOW();
       // a reference that was already set and still failed: scores with heavy tails; look for the
@@ -883,7 +905,7 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
   else finish_and_store(s, oacc, m, lsum, b, h, q0, n, g, smem_raw + wave * kEpiWaveB);
 }
 
-template <bool kSplit, bool kExt>
+template <bool kSplit, bool kExt, bool kMulti = false>
 __global__ __launch_bounds__(kThreads, 2) void attn_pp_kernel(AttnStep s) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   if (s.copy_wgs > 0 && blockIdx.x >= gridDim.x - s.copy_wgs) {   // prefetch work-group: copy and leave
@@ -893,7 +915,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_pp_kernel(AttnStep s) {
   constexpr int kQBlock = kSplit ? kQPerWGSplit : kQPerWG;
   int bh_, qb_;
   if (!wg_to_tile(s.copy_wgs, (s.Sq + kQBlock - 1) / kQBlock, s.B * s.H, bh_, qb_)) return;   // whole work-group
-  attn_pp_body<kSplit, kExt>(s, smem_raw, bh_, qb_ * kQBlock);
+  attn_pp_body<kSplit, kExt, kMulti>(s, smem_raw, bh_, qb_ * kQBlock);
 }
 
 // Mixed launch: when the 256-query blocks do not fill the last round of work-groups on the 256 CUs
@@ -955,14 +977,14 @@ usp_status launch_attn_ext_prepare(const AttnStep& s, hipStream_t st) {
 }
 
 namespace {
-template <bool kSplit, bool kExt>
+template <bool kSplit, bool kExt, bool kMulti = false>
 usp_status launch_pp(const AttnStep& s, unsigned wgs, hipStream_t st) {
   static_assert(kLdsBytes >= (int)sizeof(SmemPPExt) && kLdsBytes <= 160 * 1024, "LDS plan");
   constexpr int lds = kLdsBytes;
-  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_pp_kernel<kSplit, kExt>),
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_pp_kernel<kSplit, kExt, kMulti>),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   USP_CHECK_HIP(attr);
-  hipLaunchKernelGGL((attn_pp_kernel<kSplit, kExt>), dim3(wgs + s.copy_wgs), dim3(kThreads), lds, st, s);
+  hipLaunchKernelGGL((attn_pp_kernel<kSplit, kExt, kMulti>), dim3(wgs + s.copy_wgs), dim3(kThreads), lds, st, s);
   USP_CHECK_HIP(hipGetLastError());
   return USP_OK;
 }
@@ -970,6 +992,23 @@ usp_status launch_pp(const AttnStep& s, unsigned wgs, hipStream_t st) {
 
 usp_status launch_attn_mfma(const AttnStep& step, hipStream_t st) {
   AttnStep s = step;
+  if (s.n_multi > 0) {
+    // several resident chunks, one launch: the same two work decompositions, by the same rule
+    if (s.n_multi > AttnStep::kMaxMulti || s.mode != 0 || s.n_copy != 0 || s.key_mask || s.k_scale || s.v_scale) {
+      set_error("a launch over several chunks takes at most %d plain chunks and finishes the result", AttnStep::kMaxMulti);
+      return USP_ERR_INVALID_ARG;
+    }
+    for (int c = 0; c < s.n_multi; ++c)
+      if (s.chunk[c].Sc <= 0 || s.chunk[c].Sc % kTile != 0 || !s.chunk[c].k || !s.chunk[c].v) {
+        set_error("a launch over several chunks needs chunk lengths that are positive multiples of %d", kTile);
+        return USP_ERR_INVALID_ARG;
+      }
+    const unsigned w256 = wg_grid_size((s.Sq + kQPerWG - 1) / kQPerWG, s.B * s.H);
+    s.copy_wgs = 0;
+    if (s.variant == 2 || (s.variant != 1 && (int)w256 <= kSplitBelowWGs))
+      return launch_pp<true, false, true>(s, wg_grid_size((s.Sq + kQPerWGSplit - 1) / kQPerWGSplit, s.B * s.H), st);
+    return launch_pp<false, false, true>(s, w256, st);
+  }
   const bool ext = attn_mfma_needs_ext(s);
   // Few query blocks (a small Q shard of a ring step): 256-query work-groups would leave CUs idle;
   // 128-query work-groups whose two wave groups split the keys fill twice as many.

@@ -360,6 +360,37 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
     if ((st = stage_chunk(1)) != USP_OK) return st;
   }
 
+  // Every chunk resident and plain, merge fused: one launch over the whole ring.
+  {
+    bool one_launch = p.mfma && !p.fp8 && !p.dbuf && !p.unfused && p.W > 1 && !(desc->flags & USP_ATTN_STEPWISE);
+    int n_live = 0;
+    for (int r = 0; one_launch && r < p.W; ++r) {
+      const int len = desc->chunk_len[r];
+      if (len == 0) continue;
+      if (len % 64 != 0 || (key_mask && key_mask[r])) one_launch = false;
+      ++n_live;
+    }
+    if (one_launch && n_live >= 2 && n_live <= AttnStep::kMaxMulti) {
+      AttnStep a;
+      memset(&a, 0, sizeof(a));
+      a.B = desc->B; a.H = desc->H; a.d = d; a.Sq = desc->Sq;
+      a.qo_dtype = desc->qo_dtype; a.kv_dtype = desc->kv_dtype;
+      a.q = q; a.out = out; a.lse = lse; a.scale = scale; a.mode = 0;
+      for (int i = 0; i < 3; ++i) { a.qs[i] = desc->q_stride[i]; a.ks[i] = desc->kv_stride[i]; a.os[i] = desc->o_stride[i]; }
+      if (kv_auto(desc)) a.ks[2] = d;
+      a.variant = (desc->flags & USP_ATTN_KERNEL_SPLIT) ? 2 : (desc->flags & USP_ATTN_KERNEL_WIDE) ? 1 : 0;
+      for (int r = 0; r < p.W; ++r) {
+        const int len = desc->chunk_len[r];
+        if (len == 0) continue;
+        AttnStep::Chunk& c = a.chunk[a.n_multi++];
+        c.k = k_chunks[r]; c.v = v_chunks[r]; c.Sc = len;
+        c.ks0 = kv_auto(desc) ? (int64_t)desc->H * len * d : desc->kv_stride[0];
+        c.ks1 = kv_auto(desc) ? (int64_t)len * d : desc->kv_stride[1];
+      }
+      return launch_attn_mfma(a, cs);
+    }
+  }
+
   for (int r = 0; r < p.W; ++r) {
     const int len = desc->chunk_len[r];
     const void* kp = k_chunks[r];

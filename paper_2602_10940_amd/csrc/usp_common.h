@@ -99,6 +99,14 @@ struct AttnStep {
   // filled by launch_attn_ext_prepare on the same stream before the attention launch
   float* ext;
   int* n_live;
+  // Matrix-core kernels, several resident chunks in one launch (n_multi > 0; plain bf16 chunks whose
+  // lengths are positive multiples of 64, no mask): their 64-key tiles form one stream in ring
+  // order and the running (O~, m, l) stays in registers from the first tile to the last, which is
+  // the merge of section 3.4 applied tile by tile.  k, v, Sc and ks above are then unused.
+  struct Chunk { const void* k; const void* v; int64_t ks0, ks1; int Sc; };
+  static constexpr int kMaxMulti = 16;
+  int n_multi;
+  Chunk chunk[kMaxMulti];
   // Prefetch carried by this launch (Algorithm 2, the transfer of the next chunk): the last
   // copy_wgs work-groups of the grid copy the n_copy segments and exit; they are dispatched after
   // the attention work-groups, onto the CU slots those leave free.  The launcher fills copy_wgs (0 when n_copy == 0).

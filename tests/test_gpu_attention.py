@@ -218,7 +218,7 @@ def test_ring4_fused_unfused_and_double_buffered_agree():
     np.testing.assert_array_equal(lf2, lu)
 
 
-@pytest.mark.parametrize("flags", [0, 16, 2])
+@pytest.mark.parametrize("flags", [0, 16, 2, 64])
 def test_ring_call_replays_from_a_hip_graph(flags):
     """The library allocates nothing and clears nothing with memset nodes, so a ring call can be
     captured into a HIP graph.  Every replay (with eager calls and synchronisations of the program
@@ -351,11 +351,68 @@ def test_flux1024_ring4_full_size_every_transfer_mode_bit_identical():
     same values in the same order."""
     wl = W.WORKLOADS["flux1024_r4"]
     inp = W.make_attention_inputs(wl)
-    o0, l0 = _run(inp)
+    o0, l0 = _run(inp, flags=64)                 # one launch per chunk, all chunks resident
     o1, l1 = _run(inp, flags=1, copy_stream=torch.cuda.Stream())
     o16, l16 = _run(inp, flags=16)
     np.testing.assert_array_equal(o1, o0); np.testing.assert_array_equal(l1, l0)
     np.testing.assert_array_equal(o16, o0); np.testing.assert_array_equal(l16, l0)
+    # the plain call covers the four resident chunks with one launch: same result up to rounding order
+    om, lm = _run(inp)
+    assert not np.array_equal(om, o0)            # (a different order of operations did run)
+    assert np.abs(om - o0).max() <= 2.0 ** -7 and np.abs(lm - l0).max() <= 1e-5
+    rows = W.sample_rows(23, wl.Sq, 48)
+    ro, rl = _oracle(inp, rows)
+    _assert_parity(om[:, :, rows], lm[:, :, rows], ro, rl)
+
+
+@pytest.mark.parametrize("kernel", ["auto", "wide", "split"])
+@pytest.mark.parametrize("Sq,lens", [
+    (200, (64, 64)),
+    (300, (128, 0, 192, 64, 0, 256)),
+    (130, (64,) * 16),
+    (257, (640, 64, 1152)),
+])
+def test_one_launch_over_resident_chunks(Sq, lens, kernel):
+    """Chunks that are all resident, unmasked and multiples of 64 keys long are covered by one launch
+    (their tiles as one stream); the result must meet the same bars as the launch-per-chunk path."""
+    wl = W.Workload("multi_small", 41, 1, 3, 128, Sq, tuple(lens), "bf16")
+    inp = W.make_attention_inputs(wl)
+    ro, rl = _oracle(inp)
+    o, l = _run(inp, flags=_KERNEL_FLAG[kernel])
+    _assert_parity(o, l, ro, rl)
+    os_, ls_ = _run(inp, flags=_KERNEL_FLAG[kernel] | 64)
+    _assert_parity(os_, ls_, ro, rl)
+    assert np.abs(o - os_).max() <= 2.0 ** -6 and np.abs(l - ls_).max() <= 1e-5
+
+
+def test_one_launch_falls_back_beyond_sixteen_chunks_and_for_masks():
+    wl = W.Workload("multi_17", 42, 1, 2, 128, 150, (64,) * 17, "bf16")
+    inp = W.make_attention_inputs(wl)
+    ro, rl = _oracle(inp)
+    o, l = _run(inp)
+    _assert_parity(o, l, ro, rl)
+    o2, l2 = _run(inp, flags=64)
+    np.testing.assert_array_equal(o, o2)         # 17 chunks: the plain call is the stepwise one
+    np.testing.assert_array_equal(l, l2)
+
+
+def test_one_launch_strided_kv_chunks():
+    """Chunks that are slices of one [B, H, S, d] array (a common kv_stride instead of dense chunks)."""
+    P = _P()
+    wl = W.Workload("multi_strided", 43, 2, 3, 128, 190, (128, 256, 64), "bf16")
+    inp = W.make_attention_inputs(wl)
+    ro, rl = _oracle(inp)
+    q = dev_bf16(inp.q)
+    kfull = dev_bf16(np.concatenate(inp.k, axis=2))
+    vfull = dev_bf16(np.concatenate(inp.v, axis=2))
+    bounds = np.cumsum((0,) + wl.chunk_len)
+    ks = [kfull[:, :, a:b] for a, b in zip(bounds[:-1], bounds[1:])]
+    vs = [vfull[:, :, a:b] for a, b in zip(bounds[:-1], bounds[1:])]
+    assert not ks[1].is_contiguous()
+    for flags in (0, 64):
+        o, l = P.usp_ring_attn_fwd(q, ks, vs, softmax_scale=float(inp.softmax_scale), flags=flags)
+        torch.cuda.synchronize()
+        _assert_parity(host_f64(o), host_f64(l), ro, rl)
 
 
 def test_long_sequence_16k_keys_single_chunk_and_ragged_ring():
