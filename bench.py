@@ -277,6 +277,8 @@ def ring_leg(P, W, torch, dev, up_bf16, name="flux1024_r4", reps=600):
     side = torch.cuda.Stream()
     desc = P.make_attn_desc(q, ks, out, scale, P.USP_ATTN_DOUBLE_BUFFER)
     ws = torch.empty((P.usp_ring_attn_workspace_bytes(desc),), dtype=torch.uint8, device=dev)
+    desc1 = P.make_attn_desc(q, ks, out, scale, P.USP_ATTN_FUSED_PREFETCH)
+    ws1 = torch.empty((P.usp_ring_attn_workspace_bytes(desc1),), dtype=torch.uint8, device=dev)
     stage = [torch.empty_like(ks[0]) for _ in range(4)]
 
     def timed(fn):
@@ -301,9 +303,13 @@ def ring_leg(P, W, torch, dev, up_bf16, name="flux1024_r4", reps=600):
         P.usp_ring_attn_fwd(q, ks, vs, softmax_scale=scale, flags=P.USP_ATTN_DOUBLE_BUFFER, out=out, lse=lse,
                             workspace=ws, copy_stream=side)
 
-    def fused():
+    def fused():          # one launch per chunk, each carrying the transfer of the next chunk
+        P.usp_ring_attn_fwd(q, ks, vs, softmax_scale=scale, flags=P.USP_ATTN_FUSED_PREFETCH | P.USP_ATTN_STEPWISE,
+                            out=out, lse=lse, workspace=ws1)
+
+    def ring_one_launch():  # Algorithm 2 inside one launch: copy work-groups publish arrival counters
         P.usp_ring_attn_fwd(q, ks, vs, softmax_scale=scale, flags=P.USP_ATTN_FUSED_PREFETCH, out=out, lse=lse,
-                            workspace=ws)
+                            workspace=ws1)
 
     def copies_only():
         for r in range(1, wl.W):
@@ -319,7 +325,8 @@ def ring_leg(P, W, torch, dev, up_bf16, name="flux1024_r4", reps=600):
             kk.append(stage[2 * (r & 1)]); vv.append(stage[2 * (r & 1) + 1])
         P.usp_ring_attn_fwd(q, kk, vv, softmax_scale=scale, flags=P.USP_ATTN_STEPWISE, out=out, lse=lse, workspace=ws)
 
-    t_c, t_m, t_p, t_f, t_s, t_1 = (timed(f) for f in (resident, copies_only, pipelined, fused, serial, one_launch))
+    t_c, t_m, t_p, t_f, t_s, t_1, t_r1 = (timed(f) for f in (resident, copies_only, pipelined, fused, serial, one_launch,
+                                                            ring_one_launch))
     hid = lambda t: round(max(0.0, min(1.0, 1.0 - (t - t_c) / t_m)), 3) if t_m > 0 else None
     flops = wl.attn_flops()
     tf = lambda t: round(flops / (t * 1e-3) * 1e-12, 1)
@@ -331,6 +338,9 @@ def ring_leg(P, W, torch, dev, up_bf16, name="flux1024_r4", reps=600):
             "tflops_resident": tf(t_c), "tflops_side_stream": tf(t_p), "tflops_fused_prefetch": tf(t_f),
             "t_resident_one_launch_ms": round(t_1, 4), "tflops_resident_one_launch": tf(t_1),
             "frac_of_bf16_peak_one_launch": round(flops / (t_1 * 1e-3) * 1e-12 / PEAK_BF16_TFLOPS, 4),
+            "t_pipelined_one_launch_ms": round(t_r1, 4), "tflops_pipelined_one_launch": tf(t_r1),
+            "hidden_fraction_one_launch": round(max(0.0, min(1.0, 1.0 - (t_r1 - t_1) / t_m)), 3) if t_m > 0 else None,
+            "serial_over_pipelined_one_launch": round(t_s / t_r1, 3),
             "note": "on-device copies stand in for ring recv; an xGMI link is ~50x slower"}
 
 

@@ -48,11 +48,21 @@ typedef enum {
 #define USP_ATTN_DOUBLE_BUFFER 1u /* stage chunks 1..W-1 through two internal buffers on copy_stream */
 #define USP_ATTN_UNFUSED_MERGE 2u /* per-chunk (O_i, lse_i) then usp_lse_merge, as Algorithm 2 is written;
                                      default folds the merge into the attention kernel's epilogue */
-#define USP_ATTN_FUSED_PREFETCH 16u /* double buffering without a second stream: the transfer of chunk
-                                      r+1 into the idle internal buffer is done by extra work-groups of
-                                      step r's attention launch on compute_stream (they occupy the CUs
-                                      the attention grid leaves free); copy_stream is ignored.  Excludes
-                                      USP_ATTN_DOUBLE_BUFFER.  Same buffers, same results. */
+#define USP_ATTN_FUSED_PREFETCH 16u /* Algorithm 2 without a second stream: the transfers are done by extra
+                                      work-groups of the attention launches on compute_stream;
+                                      copy_stream is ignored.  Excludes USP_ATTN_DOUBLE_BUFFER.  Two forms:
+                                      - one launch per chunk (always with USP_ATTN_STEPWISE, FP8 K/V, a
+                                        key mask or a chunk length that is not a multiple of 64): step
+                                        r's launch carries the transfer of chunk r+1 into the idle one
+                                        of two internal buffers, in work-groups that occupy the CUs the
+                                        attention grid leaves free.  Same buffers and results as
+                                        USP_ATTN_DOUBLE_BUFFER.
+                                      - otherwise one launch for the whole ring (see USP_ATTN_STEPWISE):
+                                        its first work-groups copy chunks 1..W-1, each into an internal
+                                        buffer of its own, and count themselves on a per-chunk arrival
+                                        counter; an attention work-group waits for a chunk's count
+                                        before it loads that chunk's first keys.  Same result as the
+                                        plain call on resident chunks. */
 /* Work decomposition of the bf16 d=128 matrix-core kernel on unmasked chunks whose length is a
  * multiple of 64.  Default (neither bit): chosen from the number of work-groups the Q shard gives.
  * All variants meet the same accuracy bar; the bits exist for tuning and for tests. */
@@ -60,11 +70,12 @@ typedef enum {
 #define USP_ATTN_KERNEL_SPLIT 8u  /* 128 queries per work-group, the two wave groups take alternate
                                      64-key tiles and combine their partial results at the end */
 #define USP_ATTN_STEPWISE 64u     /* one attention launch per chunk even where one launch could cover the
-                                     whole ring: without the double-buffering flags, bf16 chunks with
-                                     d = 128 that need no mask and whose lengths are multiples of 64 (2 to 16
-                                     of them non-empty) are otherwise taken as one stream of key tiles by a
-                                     single launch, the running softmax state staying in registers
-                                     from the first chunk to the last.  Same result up to rounding order. */
+                                     whole ring: without USP_ATTN_DOUBLE_BUFFER and USP_ATTN_UNFUSED_MERGE,
+                                     bf16 chunks with d = 128 that need no mask and whose lengths are
+                                     multiples of 64 (2 to 16 of them non-empty) are otherwise taken as one
+                                     stream of key tiles by a single launch, the running softmax state
+                                     staying in registers from the first chunk to the last (no carried
+                                     state in the workspace).  Same result up to rounding order. */
 #define USP_ATTN_KERNEL_MIXED 32u /* one launch of both: 256-query work-groups, and the blocks of the
                                      last, partly filled round as pairs of key-split work-groups
                                      (forced: the second half of all blocks) */

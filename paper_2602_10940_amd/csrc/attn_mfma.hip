@@ -60,8 +60,8 @@ constexpr int kTileB = kTile * kRowB;          // 16 KB
 // last item return false.
 constexpr int kXcds = 8;
 constexpr int kSplitBelowWGs = 128;   // use the key-split kernel when 256-query work-groups number at most this
-__device__ __forceinline__ bool wg_to_tile(int copy_wgs, int nqb, int bh_total, int& bh, int& qb) {
-  const int id = blockIdx.x;                          // the copy work-groups are the last ids of the grid
+__device__ __forceinline__ bool wg_to_tile(int copy_wgs, int nqb, int bh_total, int& bh, int& qb, int lead = 0) {
+  const int id = blockIdx.x - lead;                   // the copy work-groups are the last ids of the grid, or the first `lead` (a multiple of 8)
   const int per_xcd = ((int)gridDim.x - copy_wgs) / kXcds;
   const int item = (id % kXcds) * per_xcd + id / kXcds;
   bh = item / nqb;
@@ -305,6 +305,26 @@ __global__ __launch_bounds__(64) void attn_ext_prepare_kernel(AttnStep s, float*
   }
 }
 
+// Wait of an attention work-group for a chunk that the copy work-groups of the same launch are still
+// writing: polls the chunk's counter with device-scope loads until it reaches `need`.  The copy
+// work-groups are dispatched before every attention work-group and wait for nothing, so the count
+// is reached; the poll limit (of the order of a second) only keeps a launch from spinning forever
+// should that ever not hold, at the price of a result the caller can recognise as invalid (NaN).
+constexpr int kArrivePolls = 1 << 21;
+__device__ __forceinline__ bool wait_arrival(const int* counter, int need) {
+  for (int i = 0; i < kArrivePolls; ++i) {
+    if (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= need) {
+      asm volatile("" ::: "memory");
+      return true;
+    }
+    __builtin_amdgcn_s_sleep(4);
+  }
+  return false;
+}
+__global__ __launch_bounds__(64) void attn_arrive_reset_kernel(int* arrive) {
+  if (threadIdx.x < AttnStep::kMaxMulti) arrive[threadIdx.x] = 0;
+}
+
 // One work-group's share: the queries q_base .. q_base + 255 (wide) or + 127 (split) of (batch, head) bh_.
 template <bool kSplit, bool kExt, bool kMulti = false>
 __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* smem_raw, int bh_, int q_base) {
@@ -340,6 +360,7 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
 #pragma unroll
     for (int i = 0; i < 16; ++i) oacc[dt][i] = 0.0f;
   float m = -INFINITY, lsum = 0.0f;
+  bool late = false;   // an awaited chunk never arrived (see wait_arrival): the results are replaced by NaN
 
   if (!kExt || nt > 0) {   // (uniform over the work-group)
   // ---- direct global->LDS tile loads, 4 rows (16 lanes each) per instruction.  wide: wave w moves
@@ -398,7 +419,11 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
   struct TileCursor { int c, first; };
   auto tile_at = [&](TileCursor& cur, int idx, bool is_v) -> const unsigned char* {
     if (!kMulti) return (is_v ? vb : kb) + idx * tileB;
-    while (idx >= cur.first + s.chunk[cur.c].Sc / kTile) { cur.first += s.chunk[cur.c].Sc / kTile; ++cur.c; }
+    while (idx >= cur.first + s.chunk[cur.c].Sc / kTile) {
+      cur.first += s.chunk[cur.c].Sc / kTile;
+      ++cur.c;
+      if (s.arrive != nullptr && !wait_arrival(s.arrive + cur.c, s.copy_wgs)) late = true;
+    }
     const AttnStep::Chunk& ch = s.chunk[cur.c];
     const bf16_t* base = (const bf16_t*)(is_v ? ch.v : ch.k) + b * ch.ks0 + h * ch.ks1;
     return (const unsigned char*)base + (idx - cur.first) * tileB;
@@ -899,6 +924,7 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
     m = mm;
   }
   LAB_WG_END();
+  if (kMulti && late) lsum = __builtin_nanf("");
 
   // every tile read of the work-group is behind a barrier here (the one after the last matrix phase)
   if (kSplit) finish_and_store_direct(s, oacc, m, lsum, b, h, q0, n, g);
@@ -908,13 +934,21 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
 template <bool kSplit, bool kExt, bool kMulti = false>
 __global__ __launch_bounds__(kThreads, 2) void attn_pp_kernel(AttnStep s) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  if (s.copy_wgs > 0 && blockIdx.x >= gridDim.x - s.copy_wgs) {   // prefetch work-group: copy and leave
+  if (!kMulti && s.copy_wgs > 0 && blockIdx.x >= gridDim.x - s.copy_wgs) {   // prefetch work-group: copy and leave
     prefetch_copy(s, blockIdx.x - (gridDim.x - s.copy_wgs), threadIdx.x, kThreads);
     return;
   }
   constexpr int kQBlock = kSplit ? kQPerWGSplit : kQPerWG;
   int bh_, qb_;
-  if (!wg_to_tile(s.copy_wgs, (s.Sq + kQBlock - 1) / kQBlock, s.B * s.H, bh_, qb_)) return;   // whole work-group
+  int lead = 0;
+  if (kMulti && s.arrive != nullptr) {   // the whole ring's transfers ride in this launch, in its first work-groups
+    if ((int)blockIdx.x < s.copy_wgs) {
+      stream_chunks(s, blockIdx.x, threadIdx.x, kThreads);
+      return;
+    }
+    lead = s.copy_wgs;
+  }
+  if (!wg_to_tile(s.copy_wgs, (s.Sq + kQBlock - 1) / kQBlock, s.B * s.H, bh_, qb_, lead)) return;   // whole work-group
   attn_pp_body<kSplit, kExt, kMulti>(s, smem_raw, bh_, qb_ * kQBlock);
 }
 
@@ -976,6 +1010,12 @@ usp_status launch_attn_ext_prepare(const AttnStep& s, hipStream_t st) {
   return USP_OK;
 }
 
+usp_status launch_attn_arrive_reset(int* arrive, hipStream_t st) {
+  hipLaunchKernelGGL(attn_arrive_reset_kernel, dim3(1), dim3(64), 0, st, arrive);
+  USP_CHECK_HIP(hipGetLastError());
+  return USP_OK;
+}
+
 namespace {
 template <bool kSplit, bool kExt, bool kMulti = false>
 usp_status launch_pp(const AttnStep& s, unsigned wgs, hipStream_t st) {
@@ -994,7 +1034,7 @@ usp_status launch_attn_mfma(const AttnStep& step, hipStream_t st) {
   AttnStep s = step;
   if (s.n_multi > 0) {
     // several resident chunks, one launch: the same two work decompositions, by the same rule
-    if (s.n_multi > AttnStep::kMaxMulti || s.mode != 0 || s.n_copy != 0 || s.key_mask || s.k_scale || s.v_scale) {
+    if (s.n_multi > AttnStep::kMaxMulti || s.mode != 0 || s.n_copy != 0 || s.key_mask || s.k_scale || s.v_scale) {   // (n_copy: the per-step form of the transfers)
       set_error("a launch over several chunks takes at most %d plain chunks and finishes the result", AttnStep::kMaxMulti);
       return USP_ERR_INVALID_ARG;
     }
@@ -1004,10 +1044,22 @@ usp_status launch_attn_mfma(const AttnStep& step, hipStream_t st) {
         return USP_ERR_INVALID_ARG;
       }
     const unsigned w256 = wg_grid_size((s.Sq + kQPerWG - 1) / kQPerWG, s.B * s.H);
+    const bool split = s.variant == 2 || (s.variant != 1 && (int)w256 <= kSplitBelowWGs);
+    const unsigned wgs = split ? wg_grid_size((s.Sq + kQPerWGSplit - 1) / kQPerWGSplit, s.B * s.H) : w256;
     s.copy_wgs = 0;
-    if (s.variant == 2 || (s.variant != 1 && (int)w256 <= kSplitBelowWGs))
-      return launch_pp<true, false, true>(s, wg_grid_size((s.Sq + kQPerWGSplit - 1) / kQPerWGSplit, s.B * s.H), st);
-    return launch_pp<false, false, true>(s, w256, st);
+    if (s.arrive != nullptr) {
+      for (int c = 1; c < s.n_multi; ++c)
+        if (!s.chunk[c].k_src || !s.chunk[c].v_src || s.chunk[c].bytes <= 0 || s.chunk[c].bytes % 16 != 0 ||
+            !aligned16(s.chunk[c].k_src) || !aligned16(s.chunk[c].v_src) || !aligned16(s.chunk[c].k) || !aligned16(s.chunk[c].v)) {
+          set_error("transfers inside a launch over several chunks need 16-byte aligned sources and buffers");
+          return USP_ERR_INVALID_ARG;
+        }
+      s.n_copy = 1;                                    // (only asks prefetch_wg_count for a count)
+      s.copy_wgs = prefetch_wg_count(s, (int)wgs, 1);
+      s.n_copy = 0;
+    }
+    if (split) return launch_pp<true, false, true>(s, wgs, st);
+    return launch_pp<false, false, true>(s, wgs, st);
   }
   const bool ext = attn_mfma_needs_ext(s);
   // Few query blocks (a small Q shard of a ring step): 256-query work-groups would leave CUs idle;

@@ -63,6 +63,8 @@ struct Plan {
   size_t buf_k = 0, buf_v = 0, buf_ks = 0, buf_vs = 0;  // offsets inside a staging buffer
   size_t off_deq_k = 0, off_deq_v = 0;  // bf16 K/V after dequantisation (FP8 + MFMA kernel)
   size_t off_ext = 0, off_nlive = 0;    // per-tile key records and live tile counts (MFMA kernel, masks / scales / ragged chunks)
+  bool ring1 = false;                   // fused prefetch as one launch over the whole ring: a staging buffer per chunk
+  size_t off_ring1 = 0, off_arrive = 0; // K | V of chunk 1, K | V of chunk 2, ... (dense, 256-byte aligned each); arrival counters
   bool ext = false;
   size_t total = 0;
 };
@@ -157,6 +159,24 @@ usp_status make_plan(const usp_attn_desc* d, Plan* p) {
     p->ext = true;
     p->off_ext = off; off += align_up(attn_mfma_ext_bytes(d->B, d->H, p->max_len));
     p->off_nlive = off; off += align_up((size_t)d->B * 4);
+  }
+  // Transfers inside a single launch over the whole ring (see usp_ring_attn_fwd): every chunk after
+  // the first gets a staging buffer of its own, because a buffer that is reused inside one launch
+  // would make the copy work-groups wait for the attention work-groups.
+  p->ring1 = p->fused_pf && p->mfma && !p->fp8 && !p->unfused && !(d->flags & USP_ATTN_STEPWISE);
+  if (p->ring1) {
+    int live = 0;
+    for (int r = 0; r < p->W; ++r) {
+      if (d->chunk_len[r] == 0) continue;
+      if (d->chunk_len[r] % 64 != 0) p->ring1 = false;
+      ++live;
+    }
+    if (live < 2 || live > AttnStep::kMaxMulti) p->ring1 = false;
+  }
+  if (p->ring1) {
+    p->off_ring1 = off;
+    for (int r = 1; r < p->W; ++r) off += 2 * align_up((size_t)d->B * d->H * d->chunk_len[r] * d->d * 2);
+    p->off_arrive = off; off += align_up(AttnStep::kMaxMulti * sizeof(int));
   }
   p->total = off;
   p->valid = true;
@@ -362,7 +382,7 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
 
   // Every chunk resident and plain, merge fused: one launch over the whole ring.
   {
-    bool one_launch = p.mfma && !p.fp8 && !p.dbuf && !p.unfused && p.W > 1 && !(desc->flags & USP_ATTN_STEPWISE);
+    bool one_launch = p.mfma && !p.fp8 && (!p.dbuf || p.ring1) && !p.unfused && p.W > 1 && !(desc->flags & USP_ATTN_STEPWISE);
     int n_live = 0;
     for (int r = 0; one_launch && r < p.W; ++r) {
       const int len = desc->chunk_len[r];
@@ -379,13 +399,27 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
       for (int i = 0; i < 3; ++i) { a.qs[i] = desc->q_stride[i]; a.ks[i] = desc->kv_stride[i]; a.os[i] = desc->o_stride[i]; }
       if (kv_auto(desc)) a.ks[2] = d;
       a.variant = (desc->flags & USP_ATTN_KERNEL_SPLIT) ? 2 : (desc->flags & USP_ATTN_KERNEL_WIDE) ? 1 : 0;
+      const bool transfers = p.dbuf;                      // (ring1) Algorithm 2 inside the launch
+      if (transfers) a.ks[2] = d;                         // the double-buffered modes take dense chunks only
+      size_t stage = p.off_ring1;
       for (int r = 0; r < p.W; ++r) {
         const int len = desc->chunk_len[r];
-        if (len == 0) continue;
-        AttnStep::Chunk& c = a.chunk[a.n_multi++];
-        c.k = k_chunks[r]; c.v = v_chunks[r]; c.Sc = len;
-        c.ks0 = kv_auto(desc) ? (int64_t)desc->H * len * d : desc->kv_stride[0];
-        c.ks1 = kv_auto(desc) ? (int64_t)len * d : desc->kv_stride[1];
+        const size_t bytes = (size_t)desc->B * desc->H * len * d * 2;
+        if (len > 0) {
+          AttnStep::Chunk& c = a.chunk[a.n_multi++];
+          c.k = k_chunks[r]; c.v = v_chunks[r]; c.Sc = len;
+          c.ks0 = kv_auto(desc) || transfers ? (int64_t)desc->H * len * d : desc->kv_stride[0];
+          c.ks1 = kv_auto(desc) || transfers ? (int64_t)len * d : desc->kv_stride[1];
+          if (transfers && a.n_multi > 1) {               // every live chunk but the first arrives through its buffer
+            c.k_src = k_chunks[r]; c.v_src = v_chunks[r]; c.bytes = (int64_t)bytes;
+            c.k = ws + stage; c.v = ws + stage + align_up(bytes);
+          }
+        }
+        if (r >= 1) stage += 2 * align_up(bytes);
+      }
+      if (transfers) {
+        a.arrive = (int*)(ws + p.off_arrive);
+        if ((st = launch_attn_arrive_reset(a.arrive, cs)) != USP_OK) return st;
       }
       return launch_attn_mfma(a, cs);
     }

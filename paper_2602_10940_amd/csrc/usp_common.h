@@ -103,9 +103,17 @@ struct AttnStep {
   // lengths are positive multiples of 64, no mask): their 64-key tiles form one stream in ring
   // order and the running (O~, m, l) stays in registers from the first tile to the last, which is
   // the merge of section 3.4 applied tile by tile.  k, v, Sc and ks above are then unused.
-  struct Chunk { const void* k; const void* v; int64_t ks0, ks1; int Sc; };
+  //
+  // With `arrive` set the launch also plays the ring's transfers (Algorithm 2 inside one launch): its
+  // first copy_wgs work-groups copy chunk c = 1, 2, .. from k_src / v_src (bytes each) into k / v, a
+  // staging buffer of its own per chunk, and count themselves on arrive[c] when their share of chunk
+  // c is visible device-wide; an attention work-group waits for arrive[c] == copy_wgs before it
+  // loads the first tile of chunk c.  Dependencies only point from the attention work-groups to the
+  // copy work-groups, which are dispatched first and wait for nothing.
+  struct Chunk { const void* k; const void* v; int64_t ks0, ks1; int Sc; const void* k_src; const void* v_src; int64_t bytes; };
   static constexpr int kMaxMulti = 16;
   int n_multi;
+  int* arrive;               // [kMaxMulti] counters, zero when the launch starts; or null
   Chunk chunk[kMaxMulti];
   // Prefetch carried by this launch (Algorithm 2, the transfer of the next chunk): the last
   // copy_wgs work-groups of the grid copy the n_copy segments and exit; they are dispatched after
@@ -132,5 +140,6 @@ bool attn_mfma_supported(const AttnStep& s);
 bool attn_mfma_needs_ext(const AttnStep& s);
 size_t attn_mfma_ext_bytes(int B, int H, int Sc);
 usp_status launch_attn_ext_prepare(const AttnStep& s, hipStream_t st);
+usp_status launch_attn_arrive_reset(int* arrive, hipStream_t st);
 
 }  // namespace usp

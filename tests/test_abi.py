@@ -73,8 +73,12 @@ def test_workspace_sizes_and_descriptor_checks():
     assert b.usp_ring_attn_workspace_bytes(d) == rows * 128 * 4 + recs     # fp32 carried O
     d.flags = b.USP_ATTN_DOUBLE_BUFFER
     assert b.usp_ring_attn_workspace_bytes(d) == rows * 128 * 4 + 4 * rows * 128 * 2 + recs
-    d.flags = b.USP_ATTN_FUSED_PREFETCH                                    # same two staging buffers
+    d.flags = b.USP_ATTN_FUSED_PREFETCH | b.USP_ATTN_STEPWISE             # same two staging buffers
     assert b.usp_ring_attn_workspace_bytes(d) == rows * 128 * 4 + 4 * rows * 128 * 2 + recs
+    # transfers inside one launch over the whole ring: a buffer (K | V) for each of the 3 later chunks
+    # on top, and the arrival counters
+    d.flags = b.USP_ATTN_FUSED_PREFETCH
+    assert b.usp_ring_attn_workspace_bytes(d) == rows * 128 * 4 + 4 * rows * 128 * 2 + recs + 3 * 2 * rows * 128 * 2 + 256
     for both in (b.USP_ATTN_FUSED_PREFETCH | b.USP_ATTN_DOUBLE_BUFFER,
                  b.USP_ATTN_KERNEL_WIDE | b.USP_ATTN_KERNEL_SPLIT, b.USP_ATTN_KERNEL_SPLIT | b.USP_ATTN_KERNEL_MIXED):
         d.flags = both

@@ -218,13 +218,14 @@ def test_ring4_fused_unfused_and_double_buffered_agree():
     np.testing.assert_array_equal(lf2, lu)
 
 
-@pytest.mark.parametrize("flags", [0, 16, 2, 64])
-def test_ring_call_replays_from_a_hip_graph(flags):
+@pytest.mark.parametrize("flags,lens", [(0, (192, 64, 100, 128)), (16, (192, 64, 100, 128)), (2, (192, 64, 100, 128)),
+                                        (0, (192, 64, 128, 128)), (16, (192, 64, 128, 128))])
+def test_ring_call_replays_from_a_hip_graph(flags, lens):
     """The library allocates nothing and clears nothing with memset nodes, so a ring call can be
     captured into a HIP graph.  Every replay (with eager calls and synchronisations of the program
     in between, outputs scrubbed first) must reproduce the eager result bit for bit."""
     P = _P()
-    wl = W.Workload("r4_graph", 12, 1, 3, 128, 200, (192, 64, 100, 128), "bf16")
+    wl = W.Workload("r4_graph", 12, 1, 3, 128, 200, tuple(lens), "bf16")
     inp = W.make_attention_inputs(wl)
     q = dev_bf16(inp.q); ks = [dev_bf16(k) for k in inp.k]; vs = [dev_bf16(v) for v in inp.v]
     out = torch.empty_like(q)
@@ -256,12 +257,16 @@ def test_ring_call_replays_from_a_hip_graph(flags):
 
 
 @pytest.mark.parametrize("flags", [1, 16])
-@pytest.mark.parametrize("lens", [(136,) * 8, (128, 0, 192, 64, 0, 7, 256, 64)])
+@pytest.mark.parametrize("lens", [(136,) * 8, (128, 0, 192, 64, 0, 7, 256, 64), (128, 0, 192, 64, 0, 64, 256, 64),
+                                  (0, 64, 1152, 64), (64,) * 16])
 def test_double_buffer_poisoned_staging(flags, lens):
     """Fill the workspace with NaN bit patterns first: a chunk consumed before its copy landed
     (a missing event, a transfer into the wrong buffer) would put NaN into O.  Both transfer
     modes; equal chunks, and unequal ones with empty chunks, a ragged tail and whole-tile chunks
-    (every attention kernel variant carries a transfer at some step)."""
+    (every attention kernel variant carries a transfer at some step).  With lengths that are all
+    multiples of 64, flags 16 runs the whole ring as one launch whose first work-groups copy the
+    chunks and publish arrival counters; a tile loaded before its chunk's count was reached would
+    be the NaN of the poisoned buffer."""
     P = _P()
     wl = W.Workload("r8_small", 5, 1, 2, 128, 200, tuple(lens), "bf16")
     inp = W.make_attention_inputs(wl)
@@ -355,9 +360,12 @@ def test_flux1024_ring4_full_size_every_transfer_mode_bit_identical():
     o1, l1 = _run(inp, flags=1, copy_stream=torch.cuda.Stream())
     o16, l16 = _run(inp, flags=16)
     np.testing.assert_array_equal(o1, o0); np.testing.assert_array_equal(l1, l0)
-    np.testing.assert_array_equal(o16, o0); np.testing.assert_array_equal(l16, l0)
+    o80, l80 = _run(inp, flags=16 | 64)
+    np.testing.assert_array_equal(o80, o0); np.testing.assert_array_equal(l80, l0)
     # the plain call covers the four resident chunks with one launch: same result up to rounding order
     om, lm = _run(inp)
+    # ... and so does the fused-prefetch call, whose first work-groups play the ring's transfers
+    np.testing.assert_array_equal(o16, om); np.testing.assert_array_equal(l16, lm)
     assert not np.array_equal(om, o0)            # (a different order of operations did run)
     assert np.abs(om - o0).max() <= 2.0 ** -7 and np.abs(lm - l0).max() <= 1e-5
     rows = W.sample_rows(23, wl.Sq, 48)
