@@ -361,6 +361,8 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
     for (int i = 0; i < 16; ++i) oacc[dt][i] = 0.0f;
   float m = -INFINITY, lsum = 0.0f;
   bool late = false;   // an awaited chunk never arrived (see wait_arrival): the results are replaced by NaN
+  int arrived_upto = 0, probe_c = 0, probe_val = 0;   // chunks known to have arrived; the count read ahead for chunk probe_c
+  constexpr int kProbeAheadTiles = 4;
 
   if (!kExt || nt > 0) {   // (uniform over the work-group)
   // ---- direct global->LDS tile loads, 4 rows (16 lanes each) per instruction.  wide: wave w moves
@@ -422,7 +424,19 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
     while (idx >= cur.first + s.chunk[cur.c].Sc / kTile) {
       cur.first += s.chunk[cur.c].Sc / kTile;
       ++cur.c;
-      if (s.arrive != nullptr && !wait_arrival(s.arrive + cur.c, s.copy_wgs)) late = true;
+      if (s.arrive != nullptr && cur.c > arrived_upto) {
+        // the count read a few tiles ago usually settles it; otherwise poll
+        const bool seen = probe_c == cur.c && __builtin_amdgcn_readfirstlane(probe_val) >= s.copy_wgs;
+        if (!seen && !wait_arrival(s.arrive + cur.c, s.copy_wgs)) late = true;
+        arrived_upto = cur.c;
+      }
+    }
+    // a few tiles before the K stream leaves a chunk, read the next chunk's count without waiting
+    // for the answer: a blocking poll at the boundary costs a round trip to memory on the critical path
+    if (s.arrive != nullptr && !is_v && cur.c + 1 < s.n_multi && cur.c + 1 > arrived_upto && probe_c <= cur.c &&
+        idx + kProbeAheadTiles >= cur.first + s.chunk[cur.c].Sc / kTile) {
+      probe_c = cur.c + 1;
+      probe_val = __hip_atomic_load(s.arrive + probe_c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     const AttnStep::Chunk& ch = s.chunk[cur.c];
     const bf16_t* base = (const bf16_t*)(is_v ? ch.v : ch.k) + b * ch.ks0 + h * ch.ks1;
