@@ -393,6 +393,28 @@ def test_one_launch_over_resident_chunks(Sq, lens, kernel):
     assert np.abs(o - os_).max() <= 2.0 ** -6 and np.abs(l - ls_).max() <= 1e-5
 
 
+@pytest.mark.parametrize("kernel", ["wide", "split"])
+def test_one_launch_with_transfers_inside_batch_of_two(kernel):
+    """The ring as one launch whose first work-groups play the transfers, both work decompositions,
+    two batch entries, poisoned workspace: parity, and the same bits as the call on resident chunks."""
+    P = _P()
+    wl = W.Workload("pipe1_b2", 44, 2, 3, 128, 260, (128, 64, 192), "bf16")
+    inp = W.make_attention_inputs(wl)
+    q = dev_bf16(inp.q); ks = [dev_bf16(k) for k in inp.k]; vs = [dev_bf16(v) for v in inp.v]
+    flags = _KERNEL_FLAG[kernel]
+    ref_o, ref_l = P.usp_ring_attn_fwd(q, ks, vs, softmax_scale=float(inp.softmax_scale), flags=flags)
+    out = torch.empty_like(q)
+    desc = P.make_attn_desc(q, ks, out, float(inp.softmax_scale), flags | 16)
+    ws = torch.full((P.usp_ring_attn_workspace_bytes(desc),), 0xFF, dtype=torch.uint8, device=DEV)
+    for _ in range(2):
+        o, l = P.usp_ring_attn_fwd(q, ks, vs, softmax_scale=float(inp.softmax_scale), flags=flags | 16,
+                                   out=out, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(o, ref_o) and torch.equal(l, ref_l)
+    ro, rl = _oracle(inp)
+    _assert_parity(host_f64(o), host_f64(l), ro, rl)
+
+
 def test_one_launch_falls_back_beyond_sixteen_chunks_and_for_masks():
     wl = W.Workload("multi_17", 42, 1, 2, 128, 150, (64,) * 17, "bf16")
     inp = W.make_attention_inputs(wl)
