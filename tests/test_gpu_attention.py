@@ -415,6 +415,36 @@ def test_one_launch_with_transfers_inside_batch_of_two(kernel):
     _assert_parity(host_f64(o), host_f64(l), ro, rl)
 
 
+def test_one_launch_with_transfers_inside_alternating_inputs_share_a_workspace():
+    """Two different rings of the same shape take turns through one workspace: a staging line left in
+    some cache by the previous call would surface as the other ring's keys."""
+    P = _P()
+    shape = (1, 6, 128, 700, (512, 256, 320))
+    runs = []
+    for seed in (45, 46):
+        inp = W.make_attention_inputs(W.Workload("pipe1_alt", seed, *shape, "bf16"))
+        q = dev_bf16(inp.q); ks = [dev_bf16(k) for k in inp.k]; vs = [dev_bf16(v) for v in inp.v]
+        ref = P.usp_ring_attn_fwd(q, ks, vs, softmax_scale=float(inp.softmax_scale))
+        runs.append((inp, q, ks, vs, ref))
+    torch.cuda.synchronize()
+    assert not torch.equal(runs[0][4][0], runs[1][4][0])
+    desc = P.make_attn_desc(runs[0][1], runs[0][2], torch.empty_like(runs[0][1]), float(runs[0][0].softmax_scale), 16)
+    ws = torch.full((P.usp_ring_attn_workspace_bytes(desc),), 0xFF, dtype=torch.uint8, device=DEV)
+    for it in range(6):
+        inp, q, ks, vs, (ref_o, ref_l) = runs[it & 1]
+        o, l = P.usp_ring_attn_fwd(q, ks, vs, softmax_scale=float(inp.softmax_scale), flags=16, workspace=ws)
+        torch.cuda.synchronize()
+        assert torch.equal(o, ref_o) and torch.equal(l, ref_l), it
+    # back to back without synchronising in between
+    outs = []
+    for it in range(6):
+        inp, q, ks, vs, _ = runs[it & 1]
+        outs.append(P.usp_ring_attn_fwd(q, ks, vs, softmax_scale=float(inp.softmax_scale), flags=16, workspace=ws))
+    torch.cuda.synchronize()
+    for it, (o, l) in enumerate(outs):
+        assert torch.equal(o, runs[it & 1][4][0]) and torch.equal(l, runs[it & 1][4][1]), it
+
+
 def test_one_launch_falls_back_beyond_sixteen_chunks_and_for_masks():
     wl = W.Workload("multi_17", 42, 1, 2, 128, 150, (64,) * 17, "bf16")
     inp = W.make_attention_inputs(wl)
