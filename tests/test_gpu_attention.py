@@ -505,6 +505,15 @@ def test_flux2048_u2r8_full_size_sampled_rows():
     ro, rl = _oracle(inp, rows)
     _assert_parity(o[:, :, rows], l[:, :, rows], ro, rl)
     assert np.all(np.isfinite(o)) and np.all(np.isfinite(l))
+    # the other launch configurations bench.py times on this shard
+    os_, ls_ = _run(inp, flags=64)               # resident chunks, one launch per chunk
+    np.testing.assert_array_equal(os_, o); np.testing.assert_array_equal(ls_, l)
+    of, lf = _run(inp, flags=16 | 64)            # ... each carrying the next transfer
+    np.testing.assert_array_equal(of, o); np.testing.assert_array_equal(lf, l)
+    o1, l1 = _run(inp)                           # the eight resident chunks in one launch
+    _assert_parity(o1[:, :, rows], l1[:, :, rows], ro, rl)
+    op, lp = _run(inp, flags=16)                 # one launch with the seven transfers inside
+    np.testing.assert_array_equal(op, o1); np.testing.assert_array_equal(lp, l1)
 
 
 def test_qwen_r2_full_size_fp8_kv_masked_sampled_rows():
