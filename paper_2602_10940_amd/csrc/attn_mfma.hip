@@ -233,6 +233,14 @@ __device__ __forceinline__ void finish_and_store(const AttnStep& s, f32x16 (&oac
 // softmax phase, which issues from a single wave per SIMD, the longer of the two phases.  K keeps
 // its exact codes: its scale costs nothing inside the exponent's FMA, and rounding K would move
 // the scores themselves.
+//
+// Template parameter kMulti (plain kernels only) lets one launch cover a whole ring (Algorithm 2):
+// the 64-key tiles of up to 16 chunks form one stream in ring order, a cursor maps a tile index to
+// its chunk's pointer, and the running (O~, m, l) stays in registers from the first tile to the
+// last, which is the merge of section 3.4 applied tile by tile.  With AttnStep::arrive set the
+// launch also plays the ring's transfers: its first work-groups copy the chunks into staging
+// buffers and count themselves on a per-chunk arrival counter (prefetch_copy.h), and an attention
+// work-group waits for a chunk's count before it loads the chunk's first tile (wait_arrival).
 // =============================================================================================
 __device__ __forceinline__ void lds_dma16(const void* gbase, uint32_t lane_off, uint32_t lds_base) {
   // 64 lanes x 16 bytes from gbase (wave-uniform) + lane_off (per lane): lane i's 16 bytes land at
