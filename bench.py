@@ -327,9 +327,63 @@ def ring_leg(P, W, torch, dev, up_bf16, name="flux1024_r4", reps=600):
 
     t_c, t_m, t_p, t_f, t_s, t_1, t_r1 = (timed(f) for f in (resident, copies_only, pipelined, fused, serial, one_launch,
                                                             ring_one_launch))
-    hid = lambda t: round(max(0.0, min(1.0, 1.0 - (t - t_c) / t_m)), 3) if t_m > 0 else None
     flops = wl.attn_flops()
     tf = lambda t: round(flops / (t * 1e-3) * 1e-12, 1)
+
+    # The same ring with FP8 E4M3 K/V chunks and per-(head, token) scales (Algorithm 1 applied to the
+    # ring payloads): half the bytes to move, a widening pass per chunk on arrival.
+    kq, ksc, vq, vsc = [], [], [], []
+    for k, v in zip(ks, vs):
+        B, H, L, d = k.shape
+        a, sa = P.usp_fp8_quant(k.reshape(B * H * L, d))
+        b, sb = P.usp_fp8_quant(v.reshape(B * H * L, d))
+        kq.append(a.reshape(B, H, L, d)); ksc.append(sa.reshape(B, H, L))
+        vq.append(b.reshape(B, H, L, d)); vsc.append(sb.reshape(B, H, L))
+    ws8 = torch.empty((max(P.usp_ring_attn_workspace_bytes(P.make_attn_desc(q, kq, out, scale, f))
+                           for f in (P.USP_ATTN_STEPWISE, P.USP_ATTN_DOUBLE_BUFFER, P.USP_ATTN_FUSED_PREFETCH,
+                                     P.USP_ATTN_FUSED_PREFETCH | P.USP_ATTN_STEPWISE)),),
+                      dtype=torch.uint8, device=dev)
+    st8 = [[torch.empty_like(kq[0]), torch.empty_like(ksc[0]), torch.empty_like(vq[0]), torch.empty_like(vsc[0])]
+           for _ in range(2)]
+
+    def fp8_call(flags, **kw):
+        P.usp_ring_attn_fwd(q, kq, vq, k_scales=ksc, v_scales=vsc, softmax_scale=scale, flags=flags, out=out, lse=lse,
+                            workspace=ws8, **kw)
+
+    def fp8_copies_only():
+        for r in range(1, wl.W):
+            for dst, src in zip(st8[0], (kq[r], ksc[r], vq[r], vsc[r])):
+                dst.copy_(src, non_blocking=True)
+
+    def fp8_serial():
+        kk, sk, vv, sv = [kq[0]], [ksc[0]], [vq[0]], [vsc[0]]
+        for r in range(1, wl.W):
+            bufs = st8[r & 1]
+            for dst, src in zip(bufs, (kq[r], ksc[r], vq[r], vsc[r])):
+                dst.copy_(src, non_blocking=True)
+            kk.append(bufs[0]); sk.append(bufs[1]); vv.append(bufs[2]); sv.append(bufs[3])
+        P.usp_ring_attn_fwd(q, kk, vv, k_scales=sk, v_scales=sv, softmax_scale=scale, flags=P.USP_ATTN_STEPWISE,
+                            out=out, lse=lse, workspace=ws8)
+
+    t8_c, t8_m, t8_p, t8_f, t8_s, t8_1 = (timed(f) for f in (
+        lambda: fp8_call(P.USP_ATTN_STEPWISE), fp8_copies_only,
+        lambda: fp8_call(P.USP_ATTN_DOUBLE_BUFFER, copy_stream=side),
+        lambda: fp8_call(P.USP_ATTN_FUSED_PREFETCH | P.USP_ATTN_STEPWISE), fp8_serial,
+        lambda: fp8_call(P.USP_ATTN_FUSED_PREFETCH)))
+    kv_bytes = lambda ts, ss: sum(t.numel() * t.element_size() for t in ts[1:]) + sum(t.numel() * 4 for t in ss[1:])
+    fp8 = {"t_compute_ms": round(t8_c, 4), "t_copies_ms": round(t8_m, 4), "t_side_stream_ms": round(t8_p, 4),
+           "t_fused_prefetch_ms": round(t8_f, 4), "t_serial_ms": round(t8_s, 4),
+           "hidden_fraction_fused_prefetch": round(max(0.0, min(1.0, 1.0 - (t8_f - t8_c) / t8_m)), 3) if t8_m > 0 else None,
+           "serial_over_fused_prefetch": round(t8_s / t8_f, 3),
+           "t_one_launch_ms": round(t8_1, 4), "tflops_one_launch": tf(t8_1),
+           "serial_over_one_launch": round(t8_s / t8_1, 3), "one_launch_over_bf16_one_launch": round(t8_1 / t_r1, 3),
+           "bytes_moved_bf16": 2 * kv_bytes(ks, []), "bytes_moved_fp8": kv_bytes(kq, ksc) + kv_bytes(vq, vsc),
+           "compute_over_bf16": round(t8_c / t_c, 3),
+           "note": "per-chunk forms: each chunk's codes are widened to bf16 (scales folded into the per-key records) "
+                   "by launches of their own before its attention launch; one launch: copy work-groups of the "
+                   "attention launch decode chunk r+1 while chunk r is computed on (the plain call and "
+                   "USP_ATTN_FUSED_PREFETCH give this same launch)"}
+    hid = lambda t: round(max(0.0, min(1.0, 1.0 - (t - t_c) / t_m)), 3) if t_m > 0 else None
     return {"workload": "%s: Sq=%d, %d chunks of %d, H=%d d=%d bf16" % (name, wl.Sq, wl.W, wl.chunk_len[0], wl.H, wl.d),
             "t_compute_ms": round(t_c, 4), "t_copies_ms": round(t_m, 4),
             "t_side_stream_ms": round(t_p, 4), "t_fused_prefetch_ms": round(t_f, 4), "t_serial_ms": round(t_s, 4),
@@ -341,6 +395,7 @@ def ring_leg(P, W, torch, dev, up_bf16, name="flux1024_r4", reps=600):
             "t_pipelined_one_launch_ms": round(t_r1, 4), "tflops_pipelined_one_launch": tf(t_r1),
             "hidden_fraction_one_launch": round(max(0.0, min(1.0, 1.0 - (t_r1 - t_1) / t_m)), 3) if t_m > 0 else None,
             "serial_over_pipelined_one_launch": round(t_s / t_r1, 3),
+            "fp8_kv": fp8,
             "note": "on-device copies stand in for ring recv; an xGMI link is ~50x slower"}
 
 

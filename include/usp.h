@@ -51,8 +51,8 @@ typedef enum {
 #define USP_ATTN_FUSED_PREFETCH 16u /* Algorithm 2 without a second stream: the transfers are done by extra
                                       work-groups of the attention launches on compute_stream;
                                       copy_stream is ignored.  Excludes USP_ATTN_DOUBLE_BUFFER.  Two forms:
-                                      - one launch per chunk (always with USP_ATTN_STEPWISE, FP8 K/V, a
-                                        key mask or a chunk length that is not a multiple of 64): step
+                                      - one launch per chunk (always with USP_ATTN_STEPWISE, a key mask
+                                        or a chunk length that is not a multiple of 64): step
                                         r's launch carries the transfer of chunk r+1 into the idle one
                                         of two internal buffers, in work-groups that occupy the CUs the
                                         attention grid leaves free.  Same buffers and results as
@@ -62,7 +62,11 @@ typedef enum {
                                         buffer of its own, and count themselves on a per-chunk arrival
                                         counter; an attention work-group waits for a chunk's count
                                         before it loads that chunk's first keys.  Same result as the
-                                        plain call on resident chunks. */
+                                        plain call on resident chunks.  FP8 K/V (Algorithm 1 line 4 on
+                                        arrival): the same work-groups decode each chunk while they
+                                        copy it, into bf16 K (the codes as they are), bf16 V (codes
+                                        times scales) and K's scales as per-key factors of the exponent;
+                                        the first chunk is decoded by a launch of its own in front. */
 /* Work decomposition of the bf16 d=128 matrix-core kernel on unmasked chunks whose length is a
  * multiple of 64.  Default (neither bit): chosen from the number of work-groups the Q shard gives.
  * All variants meet the same accuracy bar; the bits exist for tuning and for tests. */
@@ -71,11 +75,14 @@ typedef enum {
                                      64-key tiles and combine their partial results at the end */
 #define USP_ATTN_STEPWISE 64u     /* one attention launch per chunk even where one launch could cover the
                                      whole ring: without USP_ATTN_DOUBLE_BUFFER and USP_ATTN_UNFUSED_MERGE,
-                                     bf16 chunks with d = 128 that need no mask and whose lengths are
-                                     multiples of 64 (2 to 16 of them non-empty) are otherwise taken as one
-                                     stream of key tiles by a single launch, the running softmax state
-                                     staying in registers from the first chunk to the last (no carried
-                                     state in the workspace).  Same result up to rounding order. */
+                                     bf16 or FP8 chunks (bf16 Q, d = 128) that need no mask and whose
+                                     lengths are multiples of 64 (2 to 16 of them non-empty) are otherwise
+                                     taken as one stream of key tiles by a single launch, the running
+                                     softmax state staying in registers from the first chunk to the last
+                                     (no carried state in the workspace); FP8 chunks are decoded by
+                                     work-groups of that launch as described under
+                                     USP_ATTN_FUSED_PREFETCH, which for them is the same launch.  Same
+                                     result up to rounding order. */
 #define USP_ATTN_KERNEL_MIXED 32u /* one launch of both: 256-query work-groups, and the blocks of the
                                      last, partly filled round as pairs of key-split work-groups
                                      (forced: the second half of all blocks) */

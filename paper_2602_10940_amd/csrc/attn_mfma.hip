@@ -332,11 +332,15 @@ __device__ __forceinline__ bool wait_arrival(const int* counter, int need) {
 __global__ __launch_bounds__(64) void attn_arrive_reset_kernel(int* arrive) {
   if (threadIdx.x < AttnStep::kMaxMulti) arrive[threadIdx.x] = 0;
 }
+// Chunk c of a launch over several FP8 chunks, decoded by a launch of its own (the first chunk,
+// which no attention work-group could overlap with anything).
+__global__ __launch_bounds__(256) void attn_fp8_chunk_prepare_kernel(AttnStep s, int c) {
+  fp8_chunk_prepare<false>(s, c, (int64_t)blockIdx.x * 256 + threadIdx.x, (int64_t)gridDim.x * 256);
+}
 
 // One work-group's share: the queries q_base .. q_base + 255 (wide) or + 127 (split) of (batch, head) bh_.
 template <bool kSplit, bool kExt, bool kMulti = false>
 __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* smem_raw, int bh_, int q_base) {
-  static_assert(!(kExt && kMulti), "several chunks per launch: plain chunks only");
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it in an SGPR
@@ -353,13 +357,14 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
   const float scale2 = s.scale * 1.44269504088896340736f;
   // plain: the host guarantees Sc % 64 == 0 and Sc > 0.  extended: tiles up to the last live key;
   // the last tile of the chunk may be ragged (tail_tile), none may be left (nt == 0).
-  const int nt_all = (s.Sc + kTile - 1) / kTile;
+  // several chunks per launch: full tiles only; with records (kExt) these follow the tile stream
   int nt_multi = 0;
   if (kMulti)
     for (int c = 0; c < s.n_multi; ++c) nt_multi += s.chunk[c].Sc / kTile;
+  const int nt_all = kMulti ? nt_multi : (s.Sc + kTile - 1) / kTile;
   const int nt = kMulti ? nt_multi
                         : kExt ? min(nt_all, __builtin_amdgcn_readfirstlane(s.n_live[b])) : s.Sc / kTile;
-  const int tail_tile = (kExt && (s.Sc % kTile) != 0) ? nt_all - 1 : -1;
+  const int tail_tile = (kExt && !kMulti && (s.Sc % kTile) != 0) ? nt_all - 1 : -1;
   const int tail_last_row = s.Sc - (nt_all - 1) * kTile - 1;   // last valid row of the ragged tile
 
   f32x16 oacc[4];
@@ -411,7 +416,20 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
   // extended path: the four 64-float vectors of a tile's record, one per wave of the loading group
   const unsigned char* extb = kExt ? (const unsigned char*)(s.ext + (int64_t)bh_ * nt_all * (kExtTileB / 4)) : nullptr;
   const uint32_t lds_ext = lds_base + 2 * kStages * kTileB;
+  // kMulti: the record of a tile is written by the copy work-groups together with its chunk
+  int xcur_c = 0, xcur_first = 0;
+  auto await_record = [&](int idx) {
+    while (idx >= xcur_first + s.chunk[xcur_c].Sc / kTile) {
+      xcur_first += s.chunk[xcur_c].Sc / kTile;
+      ++xcur_c;
+      if (s.arrive != nullptr && xcur_c > arrived_upto) {
+        if (!wait_arrival(s.arrive + xcur_c, s.copy_wgs)) late = true;
+        arrived_upto = xcur_c;
+      }
+    }
+  };
   auto issue_ext = [&](int tile_idx, int stage) {
+    if (kMulti) await_record(tile_idx);
     lds_dma4(extb + (int64_t)tile_idx * kExtTileB + (wave & 3) * 256, lane * 4,
              lds_ext + stage * kExtTileB + (wave & 3) * 256);
   };
@@ -965,7 +983,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_pp_kernel(AttnStep s) {
   int lead = 0;
   if (kMulti && s.arrive != nullptr) {   // the whole ring's transfers ride in this launch, in its first work-groups
     if ((int)blockIdx.x < s.copy_wgs) {
-      stream_chunks(s, blockIdx.x, threadIdx.x, kThreads);
+      if (kExt) {
+        if (s.multi_fp8) stream_chunks_fp8(s, blockIdx.x, threadIdx.x, kThreads);
+      } else {
+        stream_chunks(s, blockIdx.x, threadIdx.x, kThreads);
+      }
       return;
     }
     lead = s.copy_wgs;
@@ -1032,6 +1054,19 @@ usp_status launch_attn_ext_prepare(const AttnStep& s, hipStream_t st) {
   return USP_OK;
 }
 
+usp_status launch_attn_fp8_chunk_prepare(const AttnStep& s, int c, hipStream_t st) {
+  if (!s.multi_fp8 || c < 0 || c >= s.n_multi || !s.ext) {
+    set_error("FP8 chunk preparation needs a step over several FP8 chunks with its records");
+    return USP_ERR_INVALID_ARG;
+  }
+  const int64_t units = (int64_t)s.B * s.H * s.chunk[c].Sc * 8;      // 16 codes each
+  const int64_t blocks = (units + 4 * 256 - 1) / (4 * 256);            // about four units per thread
+  hipLaunchKernelGGL(attn_fp8_chunk_prepare_kernel, dim3((unsigned)(blocks < 1 ? 1 : blocks > 4096 ? 4096 : blocks)), dim3(256),
+                     0, st, s, c);
+  USP_CHECK_HIP(hipGetLastError());
+  return USP_OK;
+}
+
 usp_status launch_attn_arrive_reset(int* arrive, hipStream_t st) {
   hipLaunchKernelGGL(attn_arrive_reset_kernel, dim3(1), dim3(64), 0, st, arrive);
   USP_CHECK_HIP(hipGetLastError());
@@ -1057,7 +1092,11 @@ usp_status launch_attn_mfma(const AttnStep& step, hipStream_t st) {
   if (s.n_multi > 0) {
     // several resident chunks, one launch: the same two work decompositions, by the same rule
     if (s.n_multi > AttnStep::kMaxMulti || s.mode != 0 || s.n_copy != 0 || s.key_mask || s.k_scale || s.v_scale) {   // (n_copy: the per-step form of the transfers)
-      set_error("a launch over several chunks takes at most %d plain chunks and finishes the result", AttnStep::kMaxMulti);
+      set_error("a launch over several chunks takes at most %d unmasked chunks and finishes the result", AttnStep::kMaxMulti);
+      return USP_ERR_INVALID_ARG;
+    }
+    if (s.multi_fp8 && (!s.arrive || !s.ext)) {
+      set_error("a launch over several FP8 chunks needs arrival counters and per-tile records");
       return USP_ERR_INVALID_ARG;
     }
     for (int c = 0; c < s.n_multi; ++c)
@@ -1070,9 +1109,10 @@ usp_status launch_attn_mfma(const AttnStep& step, hipStream_t st) {
     const unsigned wgs = split ? wg_grid_size((s.Sq + kQPerWGSplit - 1) / kQPerWGSplit, s.B * s.H) : w256;
     s.copy_wgs = 0;
     if (s.arrive != nullptr) {
-      for (int c = 1; c < s.n_multi; ++c)
+      for (int c = s.multi_fp8 ? 0 : 1; c < s.n_multi; ++c)
         if (!s.chunk[c].k_src || !s.chunk[c].v_src || s.chunk[c].bytes <= 0 || s.chunk[c].bytes % 16 != 0 ||
-            !aligned16(s.chunk[c].k_src) || !aligned16(s.chunk[c].v_src) || !aligned16(s.chunk[c].k) || !aligned16(s.chunk[c].v)) {
+            !aligned16(s.chunk[c].k_src) || !aligned16(s.chunk[c].v_src) || !aligned16(s.chunk[c].k) || !aligned16(s.chunk[c].v) ||
+            (s.multi_fp8 && (!s.chunk[c].k_scale_src || !s.chunk[c].v_scale_src || !aligned16(s.chunk[c].k_scale_src)))) {
           set_error("transfers inside a launch over several chunks need 16-byte aligned sources and buffers");
           return USP_ERR_INVALID_ARG;
         }
@@ -1080,6 +1120,7 @@ usp_status launch_attn_mfma(const AttnStep& step, hipStream_t st) {
       s.copy_wgs = prefetch_wg_count(s, (int)wgs, 1);
       s.n_copy = 0;
     }
+    if (s.multi_fp8) return split ? launch_pp<true, true, true>(s, wgs, st) : launch_pp<false, true, true>(s, wgs, st);
     if (split) return launch_pp<true, false, true>(s, wgs, st);
     return launch_pp<false, false, true>(s, wgs, st);
   }

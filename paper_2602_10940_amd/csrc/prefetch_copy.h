@@ -50,6 +50,67 @@ __device__ __forceinline__ void store16_device_scope(uint4* p, const uint4& v) {
   const vec4u x = {v.x, v.y, v.z, v.w};
   asm volatile("global_store_dwordx4 %0, %1, off sc1" :: "v"(p), "v"(x) : "memory");
 }
+// Algorithm 1 line 4 for chunk c of a launch over several FP8 chunks: unit `first`, first + stride, ..
+// of the chunk (16 codes of K and of V each; then 4 keys of the records).  The arithmetic is the
+// dequantiser's: E4M3 code -> fp32 (exact), times the scale in fp32, RNE to bf16; K keeps scale 1
+// and hands its scales to the records as per-key factors of the exponent.
+template <bool kDeviceScope>
+__device__ __forceinline__ void put16(uint4* p, const uint4& v) {
+  if (kDeviceScope) store16_device_scope(p, v);
+  else *p = v;
+}
+__device__ __forceinline__ uint4 decode8_bf16(uint32_t w0, uint32_t w1, float sc) {
+  typedef float f32x2_t __attribute__((ext_vector_type(2)));
+  const f32x2_t a = __builtin_amdgcn_cvt_pk_f32_fp8((int)w0, false), b = __builtin_amdgcn_cvt_pk_f32_fp8((int)w0, true);
+  const f32x2_t c = __builtin_amdgcn_cvt_pk_f32_fp8((int)w1, false), e = __builtin_amdgcn_cvt_pk_f32_fp8((int)w1, true);
+  return make_uint4(pack_bf16x2(a.x * sc, a.y * sc), pack_bf16x2(b.x * sc, b.y * sc),
+                    pack_bf16x2(c.x * sc, c.y * sc), pack_bf16x2(e.x * sc, e.y * sc));
+}
+template <bool kDeviceScope>
+__device__ __forceinline__ void fp8_chunk_prepare(const AttnStep& s, int c, int64_t first, int64_t stride) {
+  const AttnStep::Chunk& ch = s.chunk[c];
+  int tile0 = 0, nt_total = 0;                          // first tile of the chunk, tiles of all chunks
+  for (int i = 0; i < s.n_multi; ++i) {
+    if (i < c) tile0 += s.chunk[i].Sc / 64;
+    nt_total += s.chunk[i].Sc / 64;
+  }
+  const int64_t rows = (int64_t)s.B * s.H * ch.Sc;      // (head, token) rows of 128 codes
+  const uint4* kc = (const uint4*)ch.k_src;
+  const uint4* vc = (const uint4*)ch.v_src;
+  uint4* kd = (uint4*)ch.k;
+  uint4* vd = (uint4*)ch.v;
+  for (int64_t u = first; u < rows * 8; u += stride) {
+    const uint4 a = kc[u], b = vc[u];
+    const float vs = ch.v_scale_src[u >> 3];
+    put16<kDeviceScope>(kd + 2 * u, decode8_bf16(a.x, a.y, 1.0f));
+    put16<kDeviceScope>(kd + 2 * u + 1, decode8_bf16(a.z, a.w, 1.0f));
+    put16<kDeviceScope>(vd + 2 * u, decode8_bf16(b.x, b.y, vs));
+    put16<kDeviceScope>(vd + 2 * u + 1, decode8_bf16(b.z, b.w, vs));
+  }
+  const float scale2 = s.scale * 1.44269504088896340736f;
+  const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
+  for (int64_t u = first; u < rows / 4; u += stride) {  // chunk lengths are multiples of 64
+    const int64_t row = 4 * u;
+    const int64_t bh = row / ch.Sc;
+    const int key = (int)(row - bh * ch.Sc);
+    const float4 ks = ((const float4*)ch.k_scale_src)[u];
+    float* rec = s.ext + ((bh * nt_total + tile0 + (key >> 6)) << 8) + (key & 63);
+    put16<kDeviceScope>((uint4*)rec, make_uint4(__float_as_uint(ks.x * scale2), __float_as_uint(ks.y * scale2),
+                                               __float_as_uint(ks.z * scale2), __float_as_uint(ks.w * scale2)));
+    put16<kDeviceScope>((uint4*)(rec + 64), zero);      // no dead keys: bias 0, flag 0
+    put16<kDeviceScope>((uint4*)(rec + 128), zero);
+    put16<kDeviceScope>((uint4*)(rec + 192), zero);
+  }
+}
+// The copy work-groups of a launch over several FP8 chunks: chunk 1, 2, .. decoded and counted.
+__device__ __forceinline__ void stream_chunks_fp8(const AttnStep& s, int wg, int tid, int nthr) {
+  for (int c = 1; c < s.n_multi; ++c) {
+    fp8_chunk_prepare<true>(s, c, (int64_t)wg * nthr + tid, (int64_t)s.copy_wgs * nthr);
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this thread's stores have been acknowledged
+    __syncthreads();
+    if (tid == 0) __hip_atomic_fetch_add(s.arrive + c, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
 __device__ __forceinline__ void stream_chunks(const AttnStep& s, int wg, int tid, int nthr) {
   const int64_t stride = (int64_t)s.copy_wgs * nthr;
   const int64_t first = (int64_t)wg * nthr + tid;

@@ -65,6 +65,8 @@ struct Plan {
   size_t off_ext = 0, off_nlive = 0;    // per-tile key records and live tile counts (MFMA kernel, masks / scales / ragged chunks)
   bool ring1 = false;                   // fused prefetch as one launch over the whole ring: a staging buffer per chunk
   size_t off_ring1 = 0, off_arrive = 0; // K | V of chunk 1, K | V of chunk 2, ... (dense, 256-byte aligned each); arrival counters
+  bool ring8 = false;                   // FP8 chunks decoded inside one launch over the whole ring
+  size_t off_ring8 = 0, off_ext8 = 0;   // bf16 K | V of every live chunk; records of all their tiles
   bool ext = false;
   size_t total = 0;
 };
@@ -177,6 +179,28 @@ usp_status make_plan(const usp_attn_desc* d, Plan* p) {
     p->off_ring1 = off;
     for (int r = 1; r < p->W; ++r) off += 2 * align_up((size_t)d->B * d->H * d->chunk_len[r] * d->d * 2);
     p->off_arrive = off; off += align_up(AttnStep::kMaxMulti * sizeof(int));
+  }
+  // FP8 chunks, all of them at hand or with the transfers inside the launches: the decoding of
+  // Algorithm 1 line 4 rides in the one launch over the ring (copy work-groups decode chunk r+1
+  // while chunk r is computed on), each live chunk into bf16 buffers of its own.  A key mask, known
+  // only at the call, sends the call back to one launch per chunk.
+  p->ring8 = p->fp8 && p->mfma && !p->unfused && !(d->flags & (USP_ATTN_STEPWISE | USP_ATTN_DOUBLE_BUFFER));
+  if (p->ring8) {
+    int live = 0;
+    size_t tiles = 0;
+    for (int r = 0; r < p->W; ++r) {
+      if (d->chunk_len[r] == 0) continue;
+      if (d->chunk_len[r] % 64 != 0) p->ring8 = false;
+      tiles += (size_t)d->chunk_len[r] / 64;
+      ++live;
+    }
+    if (live < 2 || live > AttnStep::kMaxMulti) p->ring8 = false;
+    if (p->ring8) {
+      p->off_ring8 = off;
+      for (int r = 0; r < p->W; ++r) off += 2 * align_up((size_t)d->B * d->H * d->chunk_len[r] * d->d * 2);
+      p->off_ext8 = off; off += align_up((size_t)d->B * d->H * tiles * 1024);
+      p->off_arrive = off; off += align_up(AttnStep::kMaxMulti * sizeof(int));
+    }
   }
   p->total = off;
   p->valid = true;
@@ -421,6 +445,43 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
         a.arrive = (int*)(ws + p.off_arrive);
         if ((st = launch_attn_arrive_reset(a.arrive, cs)) != USP_OK) return st;
       }
+      return launch_attn_mfma(a, cs);
+    }
+  }
+
+  // FP8 chunks without key masks: one launch over the ring that decodes them as it goes
+  if (p.ring8) {
+    bool ok = true;
+    for (int r = 0; r < p.W; ++r)
+      if (desc->chunk_len[r] > 0 && ((key_mask && key_mask[r]) || ((uintptr_t)k_scales[r] & 15) != 0)) ok = false;
+    if (ok) {
+      AttnStep a;
+      memset(&a, 0, sizeof(a));
+      a.B = desc->B; a.H = desc->H; a.d = d; a.Sq = desc->Sq;
+      a.qo_dtype = desc->qo_dtype; a.kv_dtype = USP_BF16;   // what the attention work-groups read
+      a.q = q; a.out = out; a.lse = lse; a.scale = scale; a.mode = 0;
+      for (int i = 0; i < 3; ++i) { a.qs[i] = desc->q_stride[i]; a.os[i] = desc->o_stride[i]; }
+      a.ks[2] = d;
+      a.variant = (desc->flags & USP_ATTN_KERNEL_SPLIT) ? 2 : (desc->flags & USP_ATTN_KERNEL_WIDE) ? 1 : 0;
+      a.multi_fp8 = 1;
+      a.ext = (float*)(ws + p.off_ext8);
+      a.arrive = (int*)(ws + p.off_arrive);
+      size_t stage = p.off_ring8;
+      for (int r = 0; r < p.W; ++r) {
+        const int len = desc->chunk_len[r];
+        const size_t bytes = (size_t)desc->B * desc->H * len * d * 2;
+        if (len > 0) {
+          AttnStep::Chunk& c = a.chunk[a.n_multi++];
+          c.Sc = len;
+          c.ks0 = (int64_t)desc->H * len * d; c.ks1 = (int64_t)len * d;
+          c.k = ws + stage; c.v = ws + stage + align_up(bytes);
+          c.k_src = k_chunks[r]; c.v_src = v_chunks[r]; c.bytes = (int64_t)(bytes / 2);
+          c.k_scale_src = k_scales[r]; c.v_scale_src = v_scales[r];
+        }
+        stage += 2 * align_up(bytes);
+      }
+      if ((st = launch_attn_arrive_reset(a.arrive, cs)) != USP_OK) return st;
+      if ((st = launch_attn_fp8_chunk_prepare(a, 0, cs)) != USP_OK) return st;
       return launch_attn_mfma(a, cs);
     }
   }

@@ -110,9 +110,21 @@ struct AttnStep {
   // c is visible device-wide; an attention work-group waits for arrive[c] == copy_wgs before it
   // loads the first tile of chunk c.  Dependencies only point from the attention work-groups to the
   // copy work-groups, which are dispatched first and wait for nothing.
-  struct Chunk { const void* k; const void* v; int64_t ks0, ks1; int Sc; const void* k_src; const void* v_src; int64_t bytes; };
+  //
+  // multi_fp8: the sources are FP8 E4M3 chunks ([B,H,Sc,128] codes at k_src / v_src, per-(head, token)
+  // scales at k_scale_src / v_scale_src; Algorithm 1 line 4 on arrival).  A copy work-group then
+  // decodes while it copies: K's codes widened to bf16 as they are, V's multiplied by their scales,
+  // and the per-tile records of the chunk (K's scales as per-key factors) written into `ext`, laid
+  // out [B*H][tiles of all chunks in ring order].  Chunk 0 is decoded by a launch of its own
+  // (launch_attn_fp8_chunk_prepare) before the attention launch.
+  struct Chunk {
+    const void* k; const void* v; int64_t ks0, ks1; int Sc;
+    const void* k_src; const void* v_src; int64_t bytes;
+    const float* k_scale_src; const float* v_scale_src;
+  };
   static constexpr int kMaxMulti = 16;
   int n_multi;
+  int multi_fp8;
   int* arrive;               // [kMaxMulti] counters, zero when the launch starts; or null
   Chunk chunk[kMaxMulti];
   // Prefetch carried by this launch (Algorithm 2, the transfer of the next chunk): the last
@@ -141,5 +153,6 @@ bool attn_mfma_needs_ext(const AttnStep& s);
 size_t attn_mfma_ext_bytes(int B, int H, int Sc);
 usp_status launch_attn_ext_prepare(const AttnStep& s, hipStream_t st);
 usp_status launch_attn_arrive_reset(int* arrive, hipStream_t st);
+usp_status launch_attn_fp8_chunk_prepare(const AttnStep& s, int c, hipStream_t st);
 
 }  // namespace usp

@@ -88,6 +88,17 @@ def test_workspace_sizes_and_descriptor_checks():
     d.kv_dtype = b.USP_FP8_E4M3FN
     fp8 = b.usp_ring_attn_workspace_bytes(d)
     assert fp8 == rows * 128 * 4 + 2 * (2 * rows * 128 + 2 * rows * 4) + 2 * rows * 128 * 2 + recs
+    # FP8 chunks decoded inside one launch over the ring (plain call or fused prefetch): on top of the
+    # per-chunk form's buffers (fp32 carried O, one decoded K | V, records), bf16 K | V of every chunk,
+    # the records of all 4 * 18 tiles per head and the arrival counters
+    per_chunk = rows * 128 * 4 + 2 * rows * 128 * 2 + recs
+    one_launch = 4 * 2 * rows * 128 * 2 + 24 * 72 * 1024 + 256
+    d.flags = 0
+    assert b.usp_ring_attn_workspace_bytes(d) == per_chunk + one_launch
+    d.flags = b.USP_ATTN_STEPWISE
+    assert b.usp_ring_attn_workspace_bytes(d) == per_chunk
+    d.flags = b.USP_ATTN_FUSED_PREFETCH
+    assert b.usp_ring_attn_workspace_bytes(d) == fp8 + one_launch
     d.n_chunks = 1; d.flags = 0; d.kv_dtype = b.USP_BF16
     assert b.usp_ring_attn_workspace_bytes(d) == recs
     d.d = 64                                                               # generic kernel: nothing

@@ -1,0 +1,127 @@
+"""FP8 K/V rings through usp_ring_attn_fwd in its one-launch form (Algorithm 2 with the payloads of
+Algorithm 1): the chunks travel as E4M3 codes + per-(batch, head, token) scales and are decoded by
+work-groups of the attention launch itself.  Parity against the fp64 oracle attending over
+decode(code) * scale exactly; agreement with the one-launch-per-chunk form of the same call."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import usp_oracle as orc
+from paper_2602_10940_amd import workloads as W
+from tests.gpu_util import DEV, dev_bf16, host_f64
+from tests.test_gpu_attention import _assert_parity
+
+pytestmark = pytest.mark.gpu
+
+STEPWISE, FUSED, WIDE, SPLIT = 64, 16, 4, 8
+
+
+def _P():
+    import paper_2602_10940_amd as P
+    return P
+
+
+def _fp8_ring(wl):
+    """Inputs of the workload with K/V quantised by the library; the oracle's exact dequantisation."""
+    P = _P()
+    inp = W.make_attention_inputs(wl)
+    q = dev_bf16(inp.q)
+    kq, ksc, vq, vsc, kx, vx = [], [], [], [], [], []
+    for k, v in zip(inp.k, inp.v):
+        B, H, L, d = k.shape
+        a, sa = P.usp_fp8_quant(dev_bf16(k).reshape(B * H * L, d))
+        b, sb = P.usp_fp8_quant(dev_bf16(v).reshape(B * H * L, d))
+        kq.append(a.reshape(B, H, L, d)); ksc.append(sa.reshape(B, H, L))
+        vq.append(b.reshape(B, H, L, d)); vsc.append(sb.reshape(B, H, L))
+        kx.append(orc.dequant_exact_f64(a.cpu().numpy().reshape(B, H, L, d), sa.cpu().numpy().reshape(B, H, L)))
+        vx.append(orc.dequant_exact_f64(b.cpu().numpy().reshape(B, H, L, d), sb.cpu().numpy().reshape(B, H, L)))
+    return inp, q, kq, ksc, vq, vsc, kx, vx
+
+
+def _call(q, kq, ksc, vq, vsc, scale, flags, **kw):
+    P = _P()
+    o, l = P.usp_ring_attn_fwd(q, kq, vq, k_scales=ksc, v_scales=vsc, softmax_scale=scale, flags=flags, **kw)
+    torch.cuda.synchronize()
+    return o, l
+
+
+@pytest.mark.parametrize("B,H,Sq,lens", [
+    (1, 3, 160, (192, 64, 128, 128)),          # four chunks, one work-group round
+    (2, 2, 300, (128, 256)),                   # a batch of two, a ragged last query block
+    (1, 2, 1100, (64, 0, 448, 64, 0, 256)),    # empty chunks in between; enough queries for 256-query work-groups
+    (1, 1, 130, (64,) * 16),                   # the most chunks one launch takes
+])
+def test_fp8_ring_one_launch_against_oracle(B, H, Sq, lens):
+    wl = W.Workload("fp8_one", 61, B, H, 128, Sq, tuple(lens), "bf16", outlier_frac=0.01, outlier_mul=20.0)
+    inp, q, kq, ksc, vq, vsc, kx, vx = _fp8_ring(wl)
+    scale = float(inp.softmax_scale)
+    ro, rl = orc.ring_attention(inp.q, kx, vx, scale)
+    so, sl = _call(q, kq, ksc, vq, vsc, scale, STEPWISE)            # one launch per chunk
+    _assert_parity(host_f64(so), host_f64(sl), ro, rl)
+    for flags in (0, FUSED, WIDE, SPLIT, FUSED | SPLIT):
+        o, l = _call(q, kq, ksc, vq, vsc, scale, flags)
+        _assert_parity(host_f64(o), host_f64(l), ro, rl)
+        # the two forms differ only in where the running state is rounded
+        assert float((o.float() - so.float()).abs().max()) <= 2.0 ** -6 * max(1.0, float(so.float().abs().max()))
+        assert float((l - sl).abs().max()) <= 1e-4
+
+
+def test_fp8_ring_one_launch_poisoned_workspace_and_alternating_inputs():
+    """The decoded chunks, their records and the arrival counters live in the workspace: a call must not
+    depend on what the previous call (or nobody) left there."""
+    P = _P()
+    shape = (1, 6, 128, 700, (512, 256, 320))
+    runs = []
+    for seed in (71, 72):
+        inp, q, kq, ksc, vq, vsc, kx, vx = _fp8_ring(W.Workload("fp8_alt", seed, *shape, "bf16"))
+        ref = _call(q, kq, ksc, vq, vsc, float(inp.softmax_scale), 0)
+        ro, rl = orc.ring_attention(inp.q, kx, vx, float(inp.softmax_scale))
+        _assert_parity(host_f64(ref[0]), host_f64(ref[1]), ro, rl)
+        runs.append((inp, q, kq, ksc, vq, vsc, ref))
+    assert not torch.equal(runs[0][6][0], runs[1][6][0])
+    desc = P.make_attn_desc(runs[0][1], runs[0][2], torch.empty_like(runs[0][1]), float(runs[0][0].softmax_scale), FUSED)
+    ws = torch.full((P.usp_ring_attn_workspace_bytes(desc),), 0xFF, dtype=torch.uint8, device=DEV)
+    for it in range(6):
+        inp, q, kq, ksc, vq, vsc, (ref_o, ref_l) = runs[it & 1]
+        o, l = _call(q, kq, ksc, vq, vsc, float(inp.softmax_scale), FUSED, workspace=ws)
+        assert torch.equal(o, ref_o) and torch.equal(l, ref_l), it
+    outs = []                                                       # back to back, no synchronisation between
+    for it in range(6):
+        inp, q, kq, ksc, vq, vsc, _ = runs[it & 1]
+        outs.append(P.usp_ring_attn_fwd(q, kq, vq, k_scales=ksc, v_scales=vsc, softmax_scale=float(inp.softmax_scale),
+                                        flags=FUSED, workspace=ws))
+    torch.cuda.synchronize()
+    for it, (o, l) in enumerate(outs):
+        assert torch.equal(o, runs[it & 1][6][0]) and torch.equal(l, runs[it & 1][6][1]), it
+
+
+def test_fp8_ring_with_a_key_mask_takes_the_per_chunk_form():
+    """A key mask is known only at the call: the same descriptor (and workspace size) then runs one
+    launch per chunk, and the result still matches the oracle."""
+    P = _P()
+    wl = W.Workload("fp8_masked", 73, 1, 2, 128, 150, (128, 192), "bf16", masked_keys=(250, 320))
+    inp, q, kq, ksc, vq, vsc, kx, vx = _fp8_ring(wl)
+    km = [torch.from_numpy(m).to(DEV) for m in inp.key_mask]
+    ro, rl = orc.ring_attention(inp.q, kx, vx, float(inp.softmax_scale), inp.key_mask)
+    for flags in (0, FUSED):
+        o, l = P.usp_ring_attn_fwd(q, kq, vq, k_scales=ksc, v_scales=vsc, key_mask=km,
+                                   softmax_scale=float(inp.softmax_scale), flags=flags)
+        torch.cuda.synchronize()
+        _assert_parity(host_f64(o), host_f64(l), ro, rl)
+
+
+def test_fp8_ring_flux1024_r4_full_size_sampled_rows():
+    """The configuration bench.py times for the FP8 ring (flags 0 and FUSED_PREFETCH give the same
+    launch): sampled query rows against the oracle, the whole output against the per-chunk form."""
+    wl = W.WORKLOADS["flux1024_r4"]
+    inp, q, kq, ksc, vq, vsc, kx, vx = _fp8_ring(wl)
+    scale = float(inp.softmax_scale)
+    o, l = _call(q, kq, ksc, vq, vsc, scale, FUSED)
+    o0, l0 = _call(q, kq, ksc, vq, vsc, scale, 0)
+    assert torch.equal(o, o0) and torch.equal(l, l0)
+    so, sl = _call(q, kq, ksc, vq, vsc, scale, STEPWISE)
+    assert float((o.float() - so.float()).abs().max()) <= 2.0 ** -6
+    assert float((l - sl).abs().max()) <= 1e-4
+    rows = np.array([0, 1, 63, 64, 255, 256, 511, 777, 1000, 1151])
+    ro, rl = orc.ring_attention(inp.q[:, :, rows, :], kx, vx, scale)
+    _assert_parity(host_f64(o)[:, :, rows, :], host_f64(l)[:, :, rows], ro, rl)
