@@ -339,7 +339,9 @@ __global__ __launch_bounds__(256) void attn_fp8_chunk_prepare_kernel(AttnStep s,
 }
 
 // One work-group's share: the queries q_base .. q_base + 255 (wide) or + 127 (split) of (batch, head) bh_.
-template <bool kSplit, bool kExt, bool kMulti = false>
+// kNoDead (with kExt): the records carry per-key factors only, no key of the launch is dead (FP8
+// scales on unmasked chunks of whole tiles): the per-tile flag is not read at all.
+template <bool kSplit, bool kExt, bool kMulti = false, bool kNoDead = false>
 __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* smem_raw, int bh_, int q_base) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -701,16 +703,27 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
   // instead of a second round of exponentials on most tiles; ordinary scores never arm it.
   constexpr int kMaxFirstTiles = 8;
   int max_first = 0;
+  // "some key of the tile is dead", read from the tile's record in global memory through the scalar
+  // path (uniform address, written by an earlier launch) one softmax phase ahead of its use, so that
+  // no softmax phase starts by waiting for it
+  auto tile_flag = [&](int tile) -> float {
+    typedef const __attribute__((address_space(4))) float* const_fptr;
+    const float* p = s.ext + ((int64_t)bh_ * nt_all + min(tile, nt_all - 1)) * (kExtTileB / 4) + 128;
+    return *(const_fptr)(uintptr_t)p;
+  };
+  int sm_tile = (kSplit && !grpA) ? 1 : 0;   // tile of this wave's next softmax phase
+  float flag_next = 0.0f;
   // SM of the tile whose record sits in stage xs; loads K tile kpre_idx into stage sk (if do_k, with
   // the record of tile xpre_idx into stage xst if do_x) and V tile vpre_idx into stage sv (if do_v)
   auto SM = [&](int xs, int sk, int sv, bool do_k, bool do_v, bool do_x, int xpre_idx, int xst) {
     float psum = 0.0f;
     bool dead_keys = false;
-    if (kExt) {
-      const float f = *reinterpret_cast<const __attribute__((address_space(3))) float*>(
-          (lds_cptr)(uintptr_t)(lds_ext + xs * kExtTileB + 512));
-      x_load(0, xs, 0, 0);
-      dead_keys = __builtin_amdgcn_readfirstlane(__float_as_uint(f)) != 0u;
+    if (kExt) x_load(0, xs, 0, 0);
+    if (kExt && !kNoDead) {
+      // this tile's flag was fetched during the wave's previous softmax phase; fetch the next one
+      dead_keys = flag_next != 0.0f;
+      sm_tile += kPreStep;
+      flag_next = tile_flag(sm_tile);
     }
     if (max_first > 0) {
       --max_first;
@@ -801,6 +814,7 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
     asm volatile("" : "+v"(lsum));
   };
   auto nxt = [](int x) { return x == 2 ? 0 : x + 1; };
+  if (kExt && !kNoDead) flag_next = tile_flag(sm_tile);
   auto first_scores = [&](int stage) {
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
@@ -971,7 +985,7 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
   else finish_and_store(s, oacc, m, lsum, b, h, q0, n, g, smem_raw + wave * kEpiWaveB);
 }
 
-template <bool kSplit, bool kExt, bool kMulti = false>
+template <bool kSplit, bool kExt, bool kMulti = false, bool kNoDead = false>
 __global__ __launch_bounds__(kThreads, 2) void attn_pp_kernel(AttnStep s) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   if (!kMulti && s.copy_wgs > 0 && blockIdx.x >= gridDim.x - s.copy_wgs) {   // prefetch work-group: copy and leave
@@ -993,7 +1007,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_pp_kernel(AttnStep s) {
     lead = s.copy_wgs;
   }
   if (!wg_to_tile(s.copy_wgs, (s.Sq + kQBlock - 1) / kQBlock, s.B * s.H, bh_, qb_, lead)) return;   // whole work-group
-  attn_pp_body<kSplit, kExt, kMulti>(s, smem_raw, bh_, qb_ * kQBlock);
+  attn_pp_body<kSplit, kExt, kMulti, kNoDead>(s, smem_raw, bh_, qb_ * kQBlock);
 }
 
 // Mixed launch: when the 256-query blocks do not fill the last round of work-groups on the 256 CUs
@@ -1074,14 +1088,14 @@ usp_status launch_attn_arrive_reset(int* arrive, hipStream_t st) {
 }
 
 namespace {
-template <bool kSplit, bool kExt, bool kMulti = false>
+template <bool kSplit, bool kExt, bool kMulti = false, bool kNoDead = false>
 usp_status launch_pp(const AttnStep& s, unsigned wgs, hipStream_t st) {
   static_assert(kLdsBytes >= (int)sizeof(SmemPPExt) && kLdsBytes <= 160 * 1024, "LDS plan");
   constexpr int lds = kLdsBytes;
-  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_pp_kernel<kSplit, kExt, kMulti>),
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_pp_kernel<kSplit, kExt, kMulti, kNoDead>),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   USP_CHECK_HIP(attr);
-  hipLaunchKernelGGL((attn_pp_kernel<kSplit, kExt, kMulti>), dim3(wgs + s.copy_wgs), dim3(kThreads), lds, st, s);
+  hipLaunchKernelGGL((attn_pp_kernel<kSplit, kExt, kMulti, kNoDead>), dim3(wgs + s.copy_wgs), dim3(kThreads), lds, st, s);
   USP_CHECK_HIP(hipGetLastError());
   return USP_OK;
 }
@@ -1120,7 +1134,7 @@ usp_status launch_attn_mfma(const AttnStep& step, hipStream_t st) {
       s.copy_wgs = prefetch_wg_count(s, (int)wgs, 1);
       s.n_copy = 0;
     }
-    if (s.multi_fp8) return split ? launch_pp<true, true, true>(s, wgs, st) : launch_pp<false, true, true>(s, wgs, st);
+    if (s.multi_fp8) return split ? launch_pp<true, true, true, true>(s, wgs, st) : launch_pp<false, true, true, true>(s, wgs, st);
     if (split) return launch_pp<true, false, true>(s, wgs, st);
     return launch_pp<false, false, true>(s, wgs, st);
   }
@@ -1165,6 +1179,9 @@ usp_status launch_attn_mfma(const AttnStep& step, hipStream_t st) {
   }
   const unsigned wgs = split ? wg_grid_size((s.Sq + kQPerWGSplit - 1) / kQPerWGSplit, s.B * s.H) : wgs256;
   s.copy_wgs = prefetch_wg_count(s, (int)wgs, 1);
+  // records only because of FP8 scales: no key is dead
+  if (ext && !s.key_mask && s.Sc % kTile == 0)
+    return split ? launch_pp<true, true, false, true>(s, wgs, st) : launch_pp<false, true, false, true>(s, wgs, st);
   if (split) return ext ? launch_pp<true, true>(s, wgs, st) : launch_pp<true, false>(s, wgs, st);
   return ext ? launch_pp<false, true>(s, wgs, st) : launch_pp<false, false>(s, wgs, st);
 }
