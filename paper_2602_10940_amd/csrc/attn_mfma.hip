@@ -334,7 +334,8 @@ __global__ __launch_bounds__(64) void attn_arrive_reset_kernel(int* arrive) {
 }
 // Chunk c of a launch over several FP8 chunks, decoded by a launch of its own (the first chunk,
 // which no attention work-group could overlap with anything).
-__global__ __launch_bounds__(256) void attn_fp8_chunk_prepare_kernel(AttnStep s, int c) {
+__global__ __launch_bounds__(256) void attn_fp8_chunk_prepare_kernel(AttnStep s, int c, int reset_arrive) {
+  if (reset_arrive && blockIdx.x == 0 && threadIdx.x < AttnStep::kMaxMulti) s.arrive[threadIdx.x] = 0;
   fp8_chunk_prepare<false>(s, c, (int64_t)blockIdx.x * 256 + threadIdx.x, (int64_t)gridDim.x * 256);
 }
 
@@ -1068,15 +1069,15 @@ usp_status launch_attn_ext_prepare(const AttnStep& s, hipStream_t st) {
   return USP_OK;
 }
 
-usp_status launch_attn_fp8_chunk_prepare(const AttnStep& s, int c, hipStream_t st) {
-  if (!s.multi_fp8 || c < 0 || c >= s.n_multi || !s.ext) {
+usp_status launch_attn_fp8_chunk_prepare(const AttnStep& s, int c, bool reset_arrive, hipStream_t st) {
+  if (!s.multi_fp8 || c < 0 || c >= s.n_multi || !s.ext || (reset_arrive && !s.arrive)) {
     set_error("FP8 chunk preparation needs a step over several FP8 chunks with its records");
     return USP_ERR_INVALID_ARG;
   }
   const int64_t units = (int64_t)s.B * s.H * s.chunk[c].Sc * 8;      // 16 codes each
   const int64_t blocks = (units + 4 * 256 - 1) / (4 * 256);            // about four units per thread
   hipLaunchKernelGGL(attn_fp8_chunk_prepare_kernel, dim3((unsigned)(blocks < 1 ? 1 : blocks > 4096 ? 4096 : blocks)), dim3(256),
-                     0, st, s, c);
+                     0, st, s, c, reset_arrive ? 1 : 0);
   USP_CHECK_HIP(hipGetLastError());
   return USP_OK;
 }

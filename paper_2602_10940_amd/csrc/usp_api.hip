@@ -480,8 +480,7 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
         }
         stage += 2 * align_up(bytes);
       }
-      if ((st = launch_attn_arrive_reset(a.arrive, cs)) != USP_OK) return st;
-      if ((st = launch_attn_fp8_chunk_prepare(a, 0, cs)) != USP_OK) return st;
+      if ((st = launch_attn_fp8_chunk_prepare(a, 0, true, cs)) != USP_OK) return st;   // also zeroes the counters
       return launch_attn_mfma(a, cs);
     }
   }

@@ -153,6 +153,8 @@ bool attn_mfma_needs_ext(const AttnStep& s);
 size_t attn_mfma_ext_bytes(int B, int H, int Sc);
 usp_status launch_attn_ext_prepare(const AttnStep& s, hipStream_t st);
 usp_status launch_attn_arrive_reset(int* arrive, hipStream_t st);
-usp_status launch_attn_fp8_chunk_prepare(const AttnStep& s, int c, hipStream_t st);
+// chunk c of a step over several FP8 chunks decoded by a launch of its own; reset_arrive: the same
+// launch zeroes the arrival counters (it precedes the attention launch on the stream)
+usp_status launch_attn_fp8_chunk_prepare(const AttnStep& s, int c, bool reset_arrive, hipStream_t st);
 
 }  // namespace usp
