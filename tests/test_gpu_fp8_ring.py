@@ -125,3 +125,39 @@ def test_fp8_ring_flux1024_r4_full_size_sampled_rows():
     rows = np.array([0, 1, 63, 64, 255, 256, 511, 777, 1000, 1151])
     ro, rl = orc.ring_attention(inp.q[:, :, rows, :], kx, vx, scale)
     _assert_parity(host_f64(o)[:, :, rows, :], host_f64(l)[:, :, rows], ro, rl)
+
+
+@pytest.mark.parametrize("flags", [0, STEPWISE])
+def test_fp8_ring_call_replays_from_a_hip_graph(flags):
+    """The FP8 ring call (one launch, and one launch per chunk) captured into a HIP graph: every replay,
+    with the workspace scrubbed and eager calls of the program in between, reproduces the eager result."""
+    P = _P()
+    wl = W.Workload("fp8_graph", 81, 1, 3, 128, 200, (192, 64, 128, 128), "bf16")
+    inp, q, kq, ksc, vq, vsc, kx, vx = _fp8_ring(wl)
+    scale = float(inp.softmax_scale)
+    out = torch.empty_like(q)
+    lse = torch.empty((1, 3, 200), dtype=torch.float32, device=DEV)
+    desc = P.make_attn_desc(q, kq, out, scale, flags)
+    ws = torch.empty((P.usp_ring_attn_workspace_bytes(desc),), dtype=torch.uint8, device=DEV)
+    call = lambda: P.usp_ring_attn_fwd(q, kq, vq, k_scales=ksc, v_scales=vsc, softmax_scale=scale, flags=flags,
+                                       out=out, lse=lse, workspace=ws)
+    call()
+    torch.cuda.synchronize()
+    ref_o, ref_l = out.clone(), lse.clone()
+    ro, rl = orc.ring_attention(inp.q, kx, vx, scale)
+    _assert_parity(host_f64(ref_o), host_f64(ref_l), ro, rl)
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            call()
+    torch.cuda.synchronize()
+    for _ in range(3):
+        out.zero_(); lse.zero_(); ws.fill_(0xFF)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref_o) and torch.equal(lse, ref_l)
+        call()
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref_o) and torch.equal(lse, ref_l)
