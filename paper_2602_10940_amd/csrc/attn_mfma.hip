@@ -626,7 +626,9 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
   // softmax phase: sacc (scores of one tile) -> pk (bf16 P), running reference m and sum l.
   // Fast path: exponentials are taken against the current reference m without first looking for
   // the tile's maximum; the row sum then certifies the result: if this lane's sum of P is at most
-  // 2^16, no P exceeded 2^16, which fp32 accumulators and bf16 operands hold comfortably.  Only
+  // 2^60, no P exceeded 2^60, and neither l (at most 2^60 per key) nor O~ (at most 2^60 |v| per key)
+  // can leave the fp32 range over any sequence that fits the device; a reference that lags the
+  // maximum by D only scales P, l and O~ by 2^D, which floating point carries without loss.  Only
   // when some lane fails that test (always on the first tile, where m = -inf makes every P inf)
   // does the wave find the true maximum, move m, rescale O and l, and redo the exponentials.
   // While it runs, the wave also issues its tile loads, spread between the exponential blocks so
@@ -702,6 +704,7 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
   // maximum before the exponentials and move the reference if it is outgrown by more than 2^8; every
   // such move re-arms the counter.  Scores with heavy tails then cost one maximum pass per tile
   // instead of a second round of exponentials on most tiles; ordinary scores never arm it.
+  constexpr float kCertifiedSum = 1152921504606846976.0f;   // 2^60
   constexpr int kMaxFirstTiles = 8;
   int max_first = 0;
   // "some key of the tile is dead", read from the tile's record in global memory through the scalar
@@ -780,7 +783,7 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
     if (!kMulti) { kpre += kPreStep * tileB; vpre += kPreStep * tileB; }
     kpre_idx += kPreStep;
     vpre_idx += kPreStep;
-    if (__builtin_amdgcn_ballot_w64(!(psum <= 65536.0f)) != 0ull) {
+    if (__builtin_amdgcn_ballot_w64(!(psum <= kCertifiedSum)) != 0ull) {
       LAB_COUNT_SLOW();
       // a reference that was already set and still failed: scores with heavy tails; look for the
       // maximum first on the next tiles instead of paying for the exponentials twice
