@@ -1078,8 +1078,8 @@ usp_status launch_attn_fp8_chunk_prepare(const AttnStep& s, int c, bool reset_ar
     return USP_ERR_INVALID_ARG;
   }
   const int64_t units = (int64_t)s.B * s.H * s.chunk[c].Sc * 8;      // 16 codes each
-  const int64_t blocks = (units + 4 * 256 - 1) / (4 * 256);            // about four units per thread
-  hipLaunchKernelGGL(attn_fp8_chunk_prepare_kernel, dim3((unsigned)(blocks < 1 ? 1 : blocks > 4096 ? 4096 : blocks)), dim3(256),
+  const int64_t blocks = (units + 255) / 256;                          // one unit per thread while the chunk is small
+  hipLaunchKernelGGL(attn_fp8_chunk_prepare_kernel, dim3((unsigned)(blocks < 1 ? 1 : blocks > 8192 ? 8192 : blocks)), dim3(256),
                      0, st, s, c, reset_arrive ? 1 : 0);
   USP_CHECK_HIP(hipGetLastError());
   return USP_OK;
