@@ -16,7 +16,7 @@ OBJ_DIR = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libusp.so")
 
 SOURCES = ["usp_api.hip", "fp8_kernels.hip", "merge_kernel.hip", "attn_generic.hip", "attn_mfma.hip",
-           "probe_kernels.hip"]
+           "probe_kernels.hip", "layout_kernels.hip"]
 
 # -packed-fp32-ops off: keep the compiler from forming packed fp32 VALU ops.
 # IEEE fp32 division / denormals are required by the FP8 scale arithmetic (no fast-math).

@@ -68,6 +68,10 @@ struct Plan {
   bool ring8 = false;                   // FP8 chunks decoded inside one launch over the whole ring
   size_t off_ring8 = 0, off_ext8 = 0;   // bf16 K | V of every live chunk; records of all their tiles
   bool ext = false;
+  // bf16 with d = 64: zero-padded to d = 128 copies in the workspace (Q, O, K | V of every chunk),
+  // then the d = 128 path on those with a workspace of its own behind them
+  bool pad64 = false;
+  size_t off_pad_q = 0, off_pad_o = 0, off_pad_kv = 0, off_pad_inner = 0, inner_total = 0;
   size_t total = 0;
 };
 
@@ -82,6 +86,17 @@ bool kv_dense(const usp_attn_desc* d, int len) {
 bool o_dense(const usp_attn_desc* d) {
   return d->o_stride[2] == d->d && d->o_stride[1] == (int64_t)d->Sq * d->d &&
          d->o_stride[0] == (int64_t)d->H * d->Sq * d->d;
+}
+
+// The descriptor of the d = 128 call that stands in for a bf16 d = 64 call: dense padded tensors,
+// the scale of the original head dimension.
+usp_attn_desc padded_desc(const usp_attn_desc* d) {
+  usp_attn_desc in = *d;
+  in.d = 128;
+  const int64_t dense[3] = {(int64_t)d->H * d->Sq * 128, (int64_t)d->Sq * 128, 128};
+  for (int i = 0; i < 3; ++i) { in.q_stride[i] = dense[i]; in.o_stride[i] = dense[i]; in.kv_stride[i] = 0; }
+  in.softmax_scale = d->softmax_scale > 0.0f ? d->softmax_scale : 0.125f;   // 1 / sqrt(64)
+  return in;
 }
 
 usp_status make_plan(const usp_attn_desc* d, Plan* p) {
@@ -115,6 +130,24 @@ usp_status make_plan(const usp_attn_desc* d, Plan* p) {
   p->fp8 = d->kv_dtype == USP_FP8_E4M3FN;
   USP_CHECK_ARG(!((d->flags & USP_ATTN_DOUBLE_BUFFER) && (d->flags & USP_ATTN_FUSED_PREFETCH)),
                 "USP_ATTN_DOUBLE_BUFFER and USP_ATTN_FUSED_PREFETCH exclude each other");
+  p->pad64 = d->qo_dtype == USP_BF16 && d->kv_dtype == USP_BF16 && d->d == 64;
+  if (p->pad64) {
+    const usp_attn_desc in = padded_desc(d);
+    Plan ip;
+    const usp_status st = make_plan(&in, &ip);
+    if (st != USP_OK) return st;
+    p->rows_q = (size_t)d->B * d->H * d->Sq;
+    size_t off = 0;
+    p->off_pad_q = off; off += align_up(p->rows_q * 128 * 2);
+    p->off_pad_o = off; off += align_up(p->rows_q * 128 * 2);
+    p->off_pad_kv = off;
+    for (int r = 0; r < p->W; ++r) off += 2 * align_up((size_t)d->B * d->H * d->chunk_len[r] * 128 * 2);
+    p->off_pad_inner = off; off += ip.total;
+    p->inner_total = ip.total;
+    p->total = off;
+    p->valid = true;
+    return USP_OK;
+  }
   p->dbuf = (d->flags & (USP_ATTN_DOUBLE_BUFFER | USP_ATTN_FUSED_PREFETCH)) != 0 && p->W > 1;
   p->fused_pf = p->dbuf && (d->flags & USP_ATTN_FUSED_PREFETCH) != 0;
   p->unfused = (d->flags & USP_ATTN_UNFUSED_MERGE) != 0 && p->W > 1;
@@ -359,6 +392,28 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
 
   char* ws = (char*)workspace;
   const int d = desc->d;
+  if (p.pad64) {
+    const usp_attn_desc in = padded_desc(desc);
+    if ((st = launch_pad64(q, ws + p.off_pad_q, desc->B, desc->H, desc->Sq, desc->q_stride, cs)) != USP_OK) return st;
+    std::vector<const void*> kp(p.W), vp(p.W);
+    size_t off = p.off_pad_kv;
+    for (int r = 0; r < p.W; ++r) {
+      const int len = desc->chunk_len[r];
+      const size_t bytes = align_up((size_t)desc->B * desc->H * len * 128 * 2);
+      kp[r] = ws + off; vp[r] = ws + off + bytes;
+      if (len > 0) {
+        const int64_t dense[3] = {(int64_t)desc->H * len * 64, (int64_t)len * 64, 64};
+        const int64_t* ks = kv_auto(desc) ? dense : desc->kv_stride;
+        if ((st = launch_pad64(k_chunks[r], ws + off, desc->B, desc->H, len, ks, cs)) != USP_OK) return st;
+        if ((st = launch_pad64(v_chunks[r], ws + off + bytes, desc->B, desc->H, len, ks, cs)) != USP_OK) return st;
+      }
+      off += 2 * bytes;
+    }
+    st = usp_ring_attn_fwd(&in, ws + p.off_pad_q, kp.data(), vp.data(), nullptr, nullptr, key_mask, ws + p.off_pad_o, lse,
+                           p.inner_total ? ws + p.off_pad_inner : nullptr, p.inner_total, compute_stream, copy_stream);
+    if (st != USP_OK) return st;
+    return launch_unpad64(ws + p.off_pad_o, out, desc->B, desc->H, desc->Sq, desc->o_stride, cs);
+  }
   const float scale = desc->softmax_scale > 0.0f ? desc->softmax_scale : 1.0f / sqrtf((float)d);
   const size_t kv_es = elt_size(desc->kv_dtype);
 
