@@ -342,7 +342,10 @@ __global__ __launch_bounds__(256) void attn_fp8_chunk_prepare_kernel(AttnStep s,
 // One work-group's share: the queries q_base .. q_base + 255 (wide) or + 127 (split) of (batch, head) bh_.
 // kNoDead (with kExt): the records carry per-key factors only, no key of the launch is dead (FP8
 // scales on unmasked chunks of whole tiles): the per-tile flag is not read at all.
-template <bool kSplit, bool kExt, bool kMulti = false, bool kNoDead = false>
+// kHalfD: head dimension 64 held in the d = 128 layout (columns 64..127 of Q, K and V are zero): the
+// MFMAs that would only multiply zeros are left out, i.e. the scores run over the first four
+// 16-wide slices of the head dimension and P.V over the first two 32-wide slices.
+template <bool kSplit, bool kExt, bool kMulti = false, bool kNoDead = false, bool kHalfD = false>
 __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* smem_raw, int bh_, int q_base) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -568,11 +571,12 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
     return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(
         k_rd[4 * (blk & 1) + i] + stage * kTileB + 32 * (blk >> 1) * kRowB);
   };
+  constexpr int kDT = kHalfD ? 2 : 4;   // 32-wide slices of the head dimension that P.V produces
   auto MM_full = [&](int sv, int sk) {
     __builtin_amdgcn_s_setprio(2);
     bf16x8 va[2][4], ka[2][4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) va[0][i] = v_operand(sv, 0, i);
+    for (int i = 0; i < kDT; ++i) va[0][i] = v_operand(sv, 0, i);
 #pragma unroll
     for (int i = 0; i < 4; ++i) ka[0][i] = k_operand(sk, 0, i);
     __builtin_amdgcn_sched_barrier(0);
@@ -581,13 +585,20 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
       const int c = blk & 1, kt = blk >> 1;
       const bf16x8 pb = __builtin_bit_cast(bf16x8, pk[blk]);
 #pragma unroll
-      for (int dt = 0; dt < 4; ++dt) {
+      for (int dt = 0; dt < kDT; ++dt) {
         oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[c][dt], pb, oacc[dt], 0, 0, 0);
         if (blk < 3) va[c ^ 1][dt] = v_operand(sv, blk + 1, dt);
+        // half head dimension: the K operands of the next even block are fetched here, behind the
+        // two P.V MFMAs of the odd block before it
+        if (kHalfD && (blk & 1) == 1 && blk < 3) {
+          ka[c ^ 1][2 * dt] = k_operand(sk, blk + 1, 2 * dt);
+          ka[c ^ 1][2 * dt + 1] = k_operand(sk, blk + 1, 2 * dt + 1);
+        }
         __builtin_amdgcn_sched_barrier(0);
       }
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
+        if (kHalfD && (blk & 1) == 1) break;     // head dims 64..127: zeros
         const int ks = 4 * (blk & 1) + i;
         if (ks == 0) {
           f32x16 z;
@@ -597,7 +608,7 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
         } else {
           sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[c][i], qreg[ks], sacc[kt], 0, 0, 0);
         }
-        if (blk < 3) ka[c ^ 1][i] = k_operand(sk, blk + 1, i);
+        if (!kHalfD && blk < 3) ka[c ^ 1][i] = k_operand(sk, blk + 1, i);
         __builtin_amdgcn_sched_barrier(0);
       }
     }
@@ -609,13 +620,13 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
 #pragma unroll
     for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) va[blk][i] = v_operand(sv, blk, i);
+      for (int i = 0; i < kDT; ++i) va[blk][i] = v_operand(sv, blk, i);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int blk = 0; blk < 4; ++blk) {
       const bf16x8 pb = __builtin_bit_cast(bf16x8, pk[blk]);
 #pragma unroll
-      for (int dt = 0; dt < 4; ++dt) {
+      for (int dt = 0; dt < kDT; ++dt) {
         oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[blk][dt], pb, oacc[dt], 0, 0, 0);
         if (blk < 2) va[blk + 2][dt] = v_operand(sv, blk + 2, dt);
         __builtin_amdgcn_sched_barrier(0);
@@ -825,7 +836,7 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
 #pragma unroll
       for (int i = 0; i < 16; ++i) sacc[kt][i] = 0.0f;
       qk_block(stage, kt, 0);
-      qk_block(stage, kt, 4);
+      if (!kHalfD) qk_block(stage, kt, 4);
     }
   };
 
@@ -989,7 +1000,7 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
   else finish_and_store(s, oacc, m, lsum, b, h, q0, n, g, smem_raw + wave * kEpiWaveB);
 }
 
-template <bool kSplit, bool kExt, bool kMulti = false, bool kNoDead = false>
+template <bool kSplit, bool kExt, bool kMulti = false, bool kNoDead = false, bool kHalfD = false>
 __global__ __launch_bounds__(kThreads, 2) void attn_pp_kernel(AttnStep s) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   if (!kMulti && s.copy_wgs > 0 && blockIdx.x >= gridDim.x - s.copy_wgs) {   // prefetch work-group: copy and leave
@@ -1011,7 +1022,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_pp_kernel(AttnStep s) {
     lead = s.copy_wgs;
   }
   if (!wg_to_tile(s.copy_wgs, (s.Sq + kQBlock - 1) / kQBlock, s.B * s.H, bh_, qb_, lead)) return;   // whole work-group
-  attn_pp_body<kSplit, kExt, kMulti, kNoDead>(s, smem_raw, bh_, qb_ * kQBlock);
+  attn_pp_body<kSplit, kExt, kMulti, kNoDead, kHalfD>(s, smem_raw, bh_, qb_ * kQBlock);
 }
 
 // Mixed launch: when the 256-query blocks do not fill the last round of work-groups on the 256 CUs
@@ -1092,16 +1103,21 @@ usp_status launch_attn_arrive_reset(int* arrive, hipStream_t st) {
 }
 
 namespace {
-template <bool kSplit, bool kExt, bool kMulti = false, bool kNoDead = false>
-usp_status launch_pp(const AttnStep& s, unsigned wgs, hipStream_t st) {
+template <bool kSplit, bool kExt, bool kMulti = false, bool kNoDead = false, bool kHalfD = false>
+usp_status launch_pp_d(const AttnStep& s, unsigned wgs, hipStream_t st) {
   static_assert(kLdsBytes >= (int)sizeof(SmemPPExt) && kLdsBytes <= 160 * 1024, "LDS plan");
   constexpr int lds = kLdsBytes;
-  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_pp_kernel<kSplit, kExt, kMulti, kNoDead>),
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_pp_kernel<kSplit, kExt, kMulti, kNoDead, kHalfD>),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   USP_CHECK_HIP(attr);
-  hipLaunchKernelGGL((attn_pp_kernel<kSplit, kExt, kMulti, kNoDead>), dim3(wgs + s.copy_wgs), dim3(kThreads), lds, st, s);
+  hipLaunchKernelGGL((attn_pp_kernel<kSplit, kExt, kMulti, kNoDead, kHalfD>), dim3(wgs + s.copy_wgs), dim3(kThreads), lds, st, s);
   USP_CHECK_HIP(hipGetLastError());
   return USP_OK;
+}
+template <bool kSplit, bool kExt, bool kMulti = false, bool kNoDead = false>
+usp_status launch_pp(const AttnStep& s, unsigned wgs, hipStream_t st) {
+  return s.half_d ? launch_pp_d<kSplit, kExt, kMulti, kNoDead, true>(s, wgs, st)
+                  : launch_pp_d<kSplit, kExt, kMulti, kNoDead, false>(s, wgs, st);
 }
 }  // namespace
 

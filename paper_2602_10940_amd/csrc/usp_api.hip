@@ -48,6 +48,9 @@ struct EventPool {
   }
 };
 thread_local EventPool g_events;
+// set around the d = 128 call that stands in for a bf16 d = 64 call: columns 64..127 of its Q, K and V
+// are zero, and the matrix-core kernels may skip the MFMAs on them
+thread_local bool g_half_d = false;
 
 struct Plan {
   bool valid = false;
@@ -409,8 +412,10 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
       }
       off += 2 * bytes;
     }
+    g_half_d = true;
     st = usp_ring_attn_fwd(&in, ws + p.off_pad_q, kp.data(), vp.data(), nullptr, nullptr, key_mask, ws + p.off_pad_o, lse,
                            p.inner_total ? ws + p.off_pad_inner : nullptr, p.inner_total, compute_stream, copy_stream);
+    g_half_d = false;
     if (st != USP_OK) return st;
     return launch_unpad64(ws + p.off_pad_o, out, desc->B, desc->H, desc->Sq, desc->o_stride, cs);
   }
@@ -473,7 +478,7 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
       AttnStep a;
       memset(&a, 0, sizeof(a));
       a.B = desc->B; a.H = desc->H; a.d = d; a.Sq = desc->Sq;
-      a.qo_dtype = desc->qo_dtype; a.kv_dtype = desc->kv_dtype;
+      a.qo_dtype = desc->qo_dtype; a.half_d = g_half_d ? 1 : 0; a.kv_dtype = desc->kv_dtype;
       a.q = q; a.out = out; a.lse = lse; a.scale = scale; a.mode = 0;
       for (int i = 0; i < 3; ++i) { a.qs[i] = desc->q_stride[i]; a.ks[i] = desc->kv_stride[i]; a.os[i] = desc->o_stride[i]; }
       if (kv_auto(desc)) a.ks[2] = d;
@@ -513,7 +518,7 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
       AttnStep a;
       memset(&a, 0, sizeof(a));
       a.B = desc->B; a.H = desc->H; a.d = d; a.Sq = desc->Sq;
-      a.qo_dtype = desc->qo_dtype; a.kv_dtype = USP_BF16;   // what the attention work-groups read
+      a.qo_dtype = desc->qo_dtype; a.half_d = g_half_d ? 1 : 0; a.kv_dtype = USP_BF16;   // what the attention work-groups read
       a.q = q; a.out = out; a.lse = lse; a.scale = scale; a.mode = 0;
       for (int i = 0; i < 3; ++i) { a.qs[i] = desc->q_stride[i]; a.os[i] = desc->o_stride[i]; }
       a.ks[2] = d;
@@ -566,7 +571,7 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
     AttnStep a;
     memset(&a, 0, sizeof(a));
     a.B = desc->B; a.H = desc->H; a.d = d; a.Sq = desc->Sq; a.Sc = len;
-    a.qo_dtype = desc->qo_dtype; a.kv_dtype = desc->kv_dtype;
+    a.qo_dtype = desc->qo_dtype; a.half_d = g_half_d ? 1 : 0; a.kv_dtype = desc->kv_dtype;
     a.q = q; a.k = kp; a.v = vp; a.k_scale = ksp; a.v_scale = vsp;
     a.key_mask = key_mask ? key_mask[r] : nullptr;
     for (int i = 0; i < 3; ++i) { a.qs[i] = desc->q_stride[i]; a.ks[i] = desc->kv_stride[i]; a.os[i] = desc->o_stride[i]; }
