@@ -423,8 +423,9 @@ def d64_leg(P, torch, dev, reps=200):
     flops = 4.0 * B * H * S * S * d
     return {"workload": "B=1 H=24 d=64 Sq=S=4608 bf16, one chunk", "ms": round(ms, 4),
             "tflops": round(flops / (ms * 1e-3) * 1e-12, 1),
-            "note": "zero-padded to d = 128 in the workspace (pad Q, K, V; the d = 128 kernel in its form that "
-                    "leaves out the MFMAs on the zero columns; unpad O); the tile loads still move the zeros"}
+            "note": "K and V zero-padded to d = 128 in the workspace, then the d = 128 kernel in its form that reads "
+                    "64-wide Q rows, leaves out the MFMAs on the zero columns and writes 64-wide O rows; the tile "
+                    "loads still move the zeros"}
 
 
 def qwen_leg(P, W, torch, dev, up_bf16, reps=200):

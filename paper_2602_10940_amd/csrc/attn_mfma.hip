@@ -122,7 +122,7 @@ __device__ __forceinline__ void finish_and_store_direct(const AttnStep& s, f32x1
       }
       if (s.mode == 1 || s.mode == 2)
         *reinterpret_cast<float4*>(accp + dcol) = make_float4(o[0], o[1], o[2], o[3]);
-      else
+      else if (!s.half_d || dt < 2)   // half_d: the output rows are 64 wide (columns 64..127 are zero)
         *reinterpret_cast<uint2*>(outp + dcol) = make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
     }
   if (g == 0) s.lse[row] = lse_new;
@@ -191,8 +191,10 @@ __device__ __forceinline__ void finish_and_store(const AttnStep& s, f32x16 (&oac
       bf16_t* outp = (bf16_t*)s.out + b * s.os[0] + h * s.os[1] + (int64_t)(q0 + r) * s.os[2];
       // the final output is not read again here: a streaming store leaves no dirty line for the
       // end of the kernel to write back (the fp32 carry above is re-read by the next step and stays cached)
-      { const u32x2 v = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
-        __builtin_nontemporal_store(v, reinterpret_cast<u32x2*>(outp + 4 * c)); }
+      if (!s.half_d || c < 16) {   // half_d: the output rows are 64 wide (columns 64..127 are zero)
+        const u32x2 v = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x2*>(outp + 4 * c));
+      }
     }
   }
 }
@@ -518,9 +520,9 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
     const int qi = min(q0 + n, s.Sq - 1);
     const bf16_t* qr = qb + (int64_t)qi * s.qs[2] + 8 * g;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8*>(qr + 16 * ks);
+    for (int ks = 0; ks < (kHalfD ? 4 : 8); ++ks) qreg[ks] = *reinterpret_cast<const bf16x8*>(qr + 16 * ks);   // kHalfD: Q rows may be 64 wide
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qreg[ks]));
+    for (int ks = 0; ks < (kHalfD ? 4 : 8); ++ks) asm volatile("" : "+v"(qreg[ks]));
   }
 
   f32x16 sacc[2];
@@ -1175,7 +1177,8 @@ usp_status launch_attn_mfma(const AttnStep& step, hipStream_t st) {
   const int items = (int)((s.Sq + kQPerWG - 1) / kQPerWG) * s.B * s.H;
   const int rem = items % 256;
   int mix_blocks = 0;
-  if (s.variant == 4) mix_blocks = (items + 1) / 2;                       // forced: the second half of the blocks
+  if (s.half_d) mix_blocks = 0;                                           // (the mixed kernel has no half-head-dimension form)
+  else if (s.variant == 4) mix_blocks = (items + 1) / 2;                  // forced: the second half of the blocks
   else if (s.variant == 0 && !split && rem > 0 && rem <= 128) mix_blocks = rem;
   if (mix_blocks > 0) {
     s.mix_halves = (mix_blocks + kXcds - 1) / kXcds;

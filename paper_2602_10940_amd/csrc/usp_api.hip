@@ -74,7 +74,7 @@ struct Plan {
   // bf16 with d = 64: zero-padded to d = 128 copies in the workspace (Q, O, K | V of every chunk),
   // then the d = 128 path on those with a workspace of its own behind them
   bool pad64 = false;
-  size_t off_pad_q = 0, off_pad_o = 0, off_pad_kv = 0, off_pad_inner = 0, inner_total = 0;
+  size_t off_pad_o = 0, off_pad_kv = 0, off_pad_inner = 0, inner_total = 0;
   size_t total = 0;
 };
 
@@ -91,13 +91,19 @@ bool o_dense(const usp_attn_desc* d) {
          d->o_stride[0] == (int64_t)d->H * d->Sq * d->d;
 }
 
-// The descriptor of the d = 128 call that stands in for a bf16 d = 64 call: dense padded tensors,
-// the scale of the original head dimension.
+// The descriptor of the d = 128 call that stands in for a bf16 d = 64 call: dense padded K/V chunks,
+// the scale of the original head dimension.  Q and O stay where they are, 64 wide (the kernels read
+// and write only those columns when AttnStep::half_d is set); only with the merge as a separate
+// kernel, which works on dense 128-wide rows, O goes through a padded copy (padded_o).
+bool padded_o(const usp_attn_desc* d) { return (d->flags & USP_ATTN_UNFUSED_MERGE) != 0 && d->n_chunks > 1; }
 usp_attn_desc padded_desc(const usp_attn_desc* d) {
   usp_attn_desc in = *d;
   in.d = 128;
   const int64_t dense[3] = {(int64_t)d->H * d->Sq * 128, (int64_t)d->Sq * 128, 128};
-  for (int i = 0; i < 3; ++i) { in.q_stride[i] = dense[i]; in.o_stride[i] = dense[i]; in.kv_stride[i] = 0; }
+  for (int i = 0; i < 3; ++i) {
+    if (padded_o(d)) in.o_stride[i] = dense[i];
+    in.kv_stride[i] = 0;
+  }
   in.softmax_scale = d->softmax_scale > 0.0f ? d->softmax_scale : 0.125f;   // 1 / sqrt(64)
   return in;
 }
@@ -118,8 +124,11 @@ usp_status make_plan(const usp_attn_desc* d, Plan* p) {
     const int64_t kal = d->kv_dtype == USP_F32 ? 4 : d->kv_dtype == USP_BF16 ? 8 : 16;
     USP_CHECK_ARG(d->kv_stride[i] >= 0 && d->kv_stride[i] % kal == 0, "kv_stride[%d]=%lld must be a non-negative multiple of %lld", i, (long long)d->kv_stride[i], (long long)kal);
   }
-  USP_CHECK_ARG(d->q_stride[2] >= d->d && d->o_stride[2] >= d->d && (kv_auto(d) || d->kv_stride[2] >= d->d),
-                "token strides must be >= d");
+  {
+    const int qo_cols = g_half_d ? 64 : d->d;   // inside the stand-in call for d = 64, Q and O rows are 64 wide
+    USP_CHECK_ARG(d->q_stride[2] >= qo_cols && d->o_stride[2] >= qo_cols && (kv_auto(d) || d->kv_stride[2] >= d->d),
+                  "token strides must be >= d");
+  }
   p->W = d->n_chunks;
   p->max_len = 0;
   for (int r = 0; r < p->W; ++r) {
@@ -137,12 +146,14 @@ usp_status make_plan(const usp_attn_desc* d, Plan* p) {
   if (p->pad64) {
     const usp_attn_desc in = padded_desc(d);
     Plan ip;
+    const bool outer = g_half_d;
+    g_half_d = true;
     const usp_status st = make_plan(&in, &ip);
+    g_half_d = outer;
     if (st != USP_OK) return st;
     p->rows_q = (size_t)d->B * d->H * d->Sq;
     size_t off = 0;
-    p->off_pad_q = off; off += align_up(p->rows_q * 128 * 2);
-    p->off_pad_o = off; off += align_up(p->rows_q * 128 * 2);
+    if (padded_o(d)) { p->off_pad_o = off; off += align_up(p->rows_q * 128 * 2); }
     p->off_pad_kv = off;
     for (int r = 0; r < p->W; ++r) off += 2 * align_up((size_t)d->B * d->H * d->chunk_len[r] * 128 * 2);
     p->off_pad_inner = off; off += ip.total;
@@ -397,7 +408,7 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
   const int d = desc->d;
   if (p.pad64) {
     const usp_attn_desc in = padded_desc(desc);
-    if ((st = launch_pad64(q, ws + p.off_pad_q, desc->B, desc->H, desc->Sq, desc->q_stride, cs)) != USP_OK) return st;
+    const bool pad_o = padded_o(desc);
     std::vector<const void*> kp(p.W), vp(p.W);
     size_t off = p.off_pad_kv;
     for (int r = 0; r < p.W; ++r) {
@@ -413,10 +424,10 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
       off += 2 * bytes;
     }
     g_half_d = true;
-    st = usp_ring_attn_fwd(&in, ws + p.off_pad_q, kp.data(), vp.data(), nullptr, nullptr, key_mask, ws + p.off_pad_o, lse,
+    st = usp_ring_attn_fwd(&in, q, kp.data(), vp.data(), nullptr, nullptr, key_mask, pad_o ? (void*)(ws + p.off_pad_o) : out, lse,
                            p.inner_total ? ws + p.off_pad_inner : nullptr, p.inner_total, compute_stream, copy_stream);
     g_half_d = false;
-    if (st != USP_OK) return st;
+    if (st != USP_OK || !pad_o) return st;
     return launch_unpad64(ws + p.off_pad_o, out, desc->B, desc->H, desc->Sq, desc->o_stride, cs);
   }
   const float scale = desc->softmax_scale > 0.0f ? desc->softmax_scale : 1.0f / sqrtf((float)d);

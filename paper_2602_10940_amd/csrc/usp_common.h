@@ -91,7 +91,8 @@ struct AttnStep {
   int mode;
   int variant;               // matrix-core kernels: 0 = pick by grid size, 1 = 256-query work-groups, 2 = key-split, 4 = mixed
   int mix_halves;            // mixed launch: blocks per XCD run as two key-split halves (set by the launcher)
-  int half_d;                // matrix-core kernels: columns 64..127 of Q, K and V are zero (d = 64 padded to 128)
+  int half_d;                // matrix-core kernels: d = 64 held as d = 128: columns 64..127 of K and V are zero, the
+                             // rows of Q and of `out` are 64 wide (acc stays 128 wide)
   float* acc;                // fp32 [B,H,Sq,d] dense carried O (modes 1-3)
   void* out;                 // qo_dtype by os strides (modes 0, 3)
   float* lse;                // fp32 [B,H,Sq] dense

@@ -20,6 +20,8 @@ pytestmark = pytest.mark.gpu
     (1, 2, 130, (136,) * 3, 1),            # side-stream double buffering
     (1, 4, 520, (320,), 4),                # one chunk, 256-query work-groups
     (1, 2, 150, (200, 136), 2),            # merge as a separate kernel
+    (1, 36, 2048, (128,), 0),              # 288 query blocks: d = 128 would take the mixed launch here
+    (1, 3, 300, (128, 64), 32),            # the mixed launch asked for by flag
 ])
 def test_bf16_d64_against_oracle(B, H, Sq, lens, flags):
     wl = W.Workload("d64", 91, B, H, 64, Sq, tuple(lens), "bf16")
