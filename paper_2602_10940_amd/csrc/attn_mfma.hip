@@ -18,6 +18,8 @@
 #include "usp_common.h"
 #include "prefetch_copy.h"
 
+// Instrumentation points of the tile loop (phase boundaries, slow-path count, work-group begin and
+// end): empty in the library; a timing harness that includes this file defines them before it does.
 #ifndef LAB_STAMP
 #define LAB_STAMP(slot)
 #endif
@@ -861,11 +863,7 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
     // barrier in front of its first reader.  The second barrier only kept the groups in step, which
     // equal phase lengths do by themselves.  (The key records are read in the softmax phases of both
     // halves; with three stages they need both barriers.)
-#ifdef USP_TWO_BARRIERS
-    constexpr bool kOneBarrier = false;
-#else
     constexpr bool kOneBarrier = !kExt;
-#endif
     auto phase_barrier = [&](int wait_mode, bool needed = true) {   // 0: no wait, 1: all but the last full batch, 2: vmcnt(0)
       __builtin_amdgcn_sched_barrier(0);
       if (wait_mode == 1) {
