@@ -272,7 +272,7 @@ constexpr int kLdsBytes = 8 * kEpiWaveB;
 struct SmemPPExt {
   unsigned char k[kStages][kTileB];
   unsigned char v[kStages][kTileB];
-  unsigned char ext[kStages][kExtTileB];
+  unsigned char ext[4][kExtTileB];   // the 256-query kernel rotates its records over four stages
 };
 
 // LDS transposing read: the 16 lanes of a group each name 8 bytes; seen as a 4 x 16 matrix of
@@ -857,20 +857,21 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
     // A wave waits for its own tile loads at the end of its softmax phases: the batch issued one
     // softmax phase earlier must have landed, the batch just issued (if full: 4 loads, 5 with a
     // record) may be in flight.
-    // Only the barrier in front of A's matrix phase / B's softmax phase is needed (kOneBarrier): with
+    // Only the barrier in front of A's matrix phase / B's softmax phase is needed (the other phase
+    // boundaries pass needed = false and only order the instruction stream): with
     // three stages no load of the half-period after it overwrites what that half-period or the one
     // before the next barrier still reads, and every tile is waited for by its loaders before the
     // barrier in front of its first reader.  The second barrier only kept the groups in step, which
-    // equal phase lengths do by themselves.  (The key records are read in the softmax phases of both
-    // halves; with three stages they need both barriers.)
-    constexpr bool kOneBarrier = !kExt;
+    // equal phase lengths do by themselves.  The key records are read in the softmax phases of both
+    // halves, so they go round four stages (tile j in stage j % 4): record j+2 then replaces record
+    // j-2, last read in phase 2j-3, in phase 2j, with the barrier of tile j-1 between the two.
     auto phase_barrier = [&](int wait_mode, bool needed = true) {   // 0: no wait, 1: all but the last full batch, 2: vmcnt(0)
       __builtin_amdgcn_sched_barrier(0);
       if (wait_mode == 1) {
         if (kExt && grpA) __builtin_amdgcn_s_waitcnt(0x0F75);   // vmcnt(5)
         else __builtin_amdgcn_s_waitcnt(0x0F74);                // vmcnt(4)
       } else if (wait_mode == 2) __builtin_amdgcn_s_waitcnt(0x0F70);
-      if (needed || !kOneBarrier) __builtin_amdgcn_s_barrier();
+      if (needed) __builtin_amdgcn_s_barrier();
       __builtin_amdgcn_sched_barrier(0);
     };
     int st = 0;                            // LDS stage of tile j, j % 3
@@ -880,7 +881,7 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
       for (int j = 0; j < nt - 1; ++j) {
         const int s1 = nxt(st), s2 = nxt(s1);
         LAB_STAMP(6 * j);
-        SM(st, s2, s1, j + 2 < nt, true, j + 2 < nt, j + 2, s2);
+        SM(j & 3, s2, s1, j + 2 < nt, true, j + 2 < nt, j + 2, (j + 2) & 3);
         LAB_STAMP(6 * j + 1);
         phase_barrier(j + 2 < nt ? 1 : 2);
         LAB_STAMP(6 * j + 3);
@@ -889,7 +890,7 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
         phase_barrier(0, false);
         st = s1;
       }
-      SM(st, 0, 0, false, false, false, 0, 0);
+      SM((nt - 1) & 3, 0, 0, false, false, false, 0, 0);
       phase_barrier(2);
       MM_last(st);
       phase_barrier(0, false);
@@ -909,7 +910,7 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
         LAB_STAMP(6 * j + 1);
         phase_barrier(0);
         LAB_STAMP(6 * j + 3);
-        SM(st, st, sp, j + 3 < nt, j + 2 < nt, false, 0, 0);   // st+2 == sp (mod 3)
+        SM(j & 3, st, sp, j + 3 < nt, j + 2 < nt, false, 0, 0);   // st+2 == sp (mod 3)
         LAB_STAMP(6 * j + 5);
         phase_barrier(j + 3 < nt ? 1 : 2, false);
       }
