@@ -126,7 +126,10 @@ size_t usp_ring_attn_workspace_bytes(const usp_attn_desc* desc);
  *   q          [B,H,Sq,d] by q_stride, dtype qo_dtype
  *   k_chunks   HOST array of n_chunks device pointers; chunk r is [B,H,chunk_len[r],d]
  *              by kv_stride, dtype kv_dtype.  With FP8 the bytes are dense E4M3 codes.
- *   v_chunks   same for V
+ *   v_chunks   same for V.  With USP_ATTN_DOUBLE_BUFFER or USP_ATTN_FUSED_PREFETCH the chunks
+ *              after the first (and their scales) are only read by the transfers, so they may
+ *              also sit in pinned host memory that the device can address (hipHostMalloc): the
+ *              transfers then cross the host link, which stands in for a slow ring link.
  *   k_scales / v_scales   NULL unless kv_dtype is FP8: HOST arrays of device pointers,
  *              chunk r -> float [B,H,chunk_len[r]] dense, one scale per (b,h,token)
  *              (value = code * scale, as produced by usp_fp8_quant on the

@@ -440,12 +440,12 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
     char* buf = ws + p.off_buf[(r - 1) & 1];
     if (len > 0) {
       const size_t bytes = (size_t)desc->B * desc->H * len * d * kv_es;
-      USP_CHECK_HIP(hipMemcpyAsync(buf + p.buf_k, k_chunks[r], bytes, hipMemcpyDeviceToDevice, xs));
-      USP_CHECK_HIP(hipMemcpyAsync(buf + p.buf_v, v_chunks[r], bytes, hipMemcpyDeviceToDevice, xs));
+      USP_CHECK_HIP(hipMemcpyAsync(buf + p.buf_k, k_chunks[r], bytes, hipMemcpyDefault, xs));
+      USP_CHECK_HIP(hipMemcpyAsync(buf + p.buf_v, v_chunks[r], bytes, hipMemcpyDefault, xs));
       if (p.fp8) {
         const size_t sb = (size_t)desc->B * desc->H * len * 4;
-        USP_CHECK_HIP(hipMemcpyAsync(buf + p.buf_ks, k_scales[r], sb, hipMemcpyDeviceToDevice, xs));
-        USP_CHECK_HIP(hipMemcpyAsync(buf + p.buf_vs, v_scales[r], sb, hipMemcpyDeviceToDevice, xs));
+        USP_CHECK_HIP(hipMemcpyAsync(buf + p.buf_ks, k_scales[r], sb, hipMemcpyDefault, xs));
+        USP_CHECK_HIP(hipMemcpyAsync(buf + p.buf_vs, v_scales[r], sb, hipMemcpyDefault, xs));
       }
     }
     USP_CHECK_HIP(g_events.get(&copied[r]));

@@ -161,3 +161,28 @@ def test_fp8_ring_call_replays_from_a_hip_graph(flags):
         call()
         torch.cuda.synchronize()
         assert torch.equal(out, ref_o) and torch.equal(lse, ref_l)
+
+
+@pytest.mark.parametrize("fp8", [False, True])
+def test_later_chunks_in_pinned_host_memory(fp8):
+    """With the double-buffered modes the chunks after the first are only read by the transfers: they may
+    sit in pinned host memory (a slow link).  Same result as with every chunk in device memory."""
+    P = _P()
+    wl = W.Workload("far_chunks", 95, 1, 3, 128, 200, (192, 64, 128, 128), "bf16")
+    inp, q, kq, ksc, vq, vsc, kx, vx = _fp8_ring(wl)
+    scale = float(inp.softmax_scale)
+    host = lambda t: torch.empty(t.shape, dtype=t.dtype, pin_memory=True).copy_(t)
+    far = lambda ts: [ts[0]] + [host(t) for t in ts[1:]]
+    if fp8:
+        near = dict(k_chunks=kq, v_chunks=vq, k_scales=ksc, v_scales=vsc)
+        away = dict(k_chunks=far(kq), v_chunks=far(vq), k_scales=far(ksc), v_scales=far(vsc))
+    else:
+        ks = [dev_bf16(k) for k in inp.k]; vs = [dev_bf16(v) for v in inp.v]
+        near = dict(k_chunks=ks, v_chunks=vs)
+        away = dict(k_chunks=far(ks), v_chunks=far(vs))
+    torch.cuda.synchronize()
+    for flags, side in ((1, torch.cuda.Stream()), (FUSED, None), (FUSED | STEPWISE, None)):
+        ro, rl = P.usp_ring_attn_fwd(q, softmax_scale=scale, flags=flags, copy_stream=side, **near)
+        o, l = P.usp_ring_attn_fwd(q, softmax_scale=scale, flags=flags, copy_stream=side, **away)
+        torch.cuda.synchronize()
+        assert torch.equal(o, ro) and torch.equal(l, rl), flags
