@@ -51,8 +51,8 @@ typedef enum {
 #define USP_ATTN_FUSED_PREFETCH 16u /* Algorithm 2 without a second stream: the transfers are done by extra
                                       work-groups of the attention launches on compute_stream;
                                       copy_stream is ignored.  Excludes USP_ATTN_DOUBLE_BUFFER.  Two forms:
-                                      - one launch per chunk (always with USP_ATTN_STEPWISE, a key mask
-                                        or a chunk length that is not a multiple of 64): step
+                                      - one launch per chunk (always with USP_ATTN_STEPWISE, a chunk length
+                                        that is not a multiple of 64, or a key mask on bf16 chunks): step
                                         r's launch carries the transfer of chunk r+1 into the idle one
                                         of two internal buffers, in work-groups that occupy the CUs the
                                         attention grid leaves free.  Same buffers and results as
@@ -66,7 +66,9 @@ typedef enum {
                                         arrival): the same work-groups decode each chunk while they
                                         copy it, into bf16 K (the codes as they are), bf16 V (codes
                                         times scales) and K's scales as per-key factors of the exponent;
-                                        the first chunk is decoded by a launch of its own in front. */
+                                        the first chunk is decoded by a launch of its own in front;
+                                        key masks go into the records (every tile of a chunk that came
+                                        with a mask is treated as one that may hold dead keys). */
 /* Work decomposition of the bf16 d=128 matrix-core kernel on unmasked chunks whose length is a
  * multiple of 64.  Default (neither bit): chosen from the number of work-groups the Q shard gives.
  * All variants meet the same accuracy bar; the bits exist for tuning and for tests. */
@@ -77,7 +79,9 @@ typedef enum {
                                      whole ring: without USP_ATTN_DOUBLE_BUFFER and USP_ATTN_UNFUSED_MERGE,
                                      bf16 or FP8 chunks (bf16 Q, d = 128) that need no mask and whose
                                      lengths are multiples of 64 (2 to 16 of them non-empty) are otherwise
-                                     taken as one stream of key tiles by a single launch, the running
+                                     taken as one stream of key tiles by a single launch (when the Q
+                                     shard's 256-query blocks fit one round of work-groups on the chip,
+                                     or the transfers are asked to ride inside the launch), the running
                                      softmax state staying in registers from the first chunk to the last
                                      (no carried state in the workspace); FP8 chunks are decoded by
                                      work-groups of that launch as described under

@@ -730,6 +730,16 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
     const float* p = s.ext + ((int64_t)bh_ * nt_all + min(tile, nt_all - 1)) * (kExtTileB / 4) + 128;
     return *(const_fptr)(uintptr_t)p;
   };
+  // several chunks per launch: the records are written while the launch runs, so instead of a flag
+  // per tile every tile of a chunk that came with a key mask is treated as one that may hold dead keys
+  int sm_c = 0, sm_first = 0;   // chunk of sm_tile and the index of its first tile
+  auto chunk_masked = [&](int tile) -> bool {
+    while (sm_c + 1 < s.n_multi && tile >= sm_first + s.chunk[sm_c].Sc / kTile) {
+      sm_first += s.chunk[sm_c].Sc / kTile;
+      ++sm_c;
+    }
+    return s.chunk[sm_c].mask_src != nullptr;
+  };
   int sm_tile = (kSplit && !grpA) ? 1 : 0;   // tile of this wave's next softmax phase
   float flag_next = 0.0f;
   // SM of the tile whose record sits in stage xs; loads K tile kpre_idx into stage sk (if do_k, with
@@ -740,9 +750,14 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
     if (kExt) x_load(0, xs, 0, 0);
     if (kExt && !kNoDead) {
       // this tile's flag was fetched during the wave's previous softmax phase; fetch the next one
-      dead_keys = flag_next != 0.0f;
-      sm_tile += kPreStep;
-      flag_next = tile_flag(sm_tile);
+      if (kMulti) {
+        dead_keys = chunk_masked(sm_tile);
+        sm_tile += kPreStep;
+      } else {
+        dead_keys = flag_next != 0.0f;
+        sm_tile += kPreStep;
+        flag_next = tile_flag(sm_tile);
+      }
     }
     if (max_first > 0) {
       --max_first;
@@ -833,7 +848,7 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
     asm volatile("" : "+v"(lsum));
   };
   auto nxt = [](int x) { return x == 2 ? 0 : x + 1; };
-  if (kExt && !kNoDead) flag_next = tile_flag(sm_tile);
+  if (kExt && !kNoDead && !kMulti) flag_next = tile_flag(sm_tile);
   auto first_scores = [&](int stage) {
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
@@ -1140,14 +1155,20 @@ usp_status launch_attn_mfma(const AttnStep& step, hipStream_t st) {
         return USP_ERR_INVALID_ARG;
       }
     const unsigned w256 = wg_grid_size((s.Sq + kQPerWG - 1) / kQPerWG, s.B * s.H);
-    const bool split = s.variant == 2 || (s.variant != 1 && (int)w256 <= kSplitBelowWGs);
-    const unsigned wgs = split ? wg_grid_size((s.Sq + kQPerWGSplit - 1) / kQPerWGSplit, s.B * s.H) : w256;
+    const unsigned w128 = wg_grid_size((s.Sq + kQPerWGSplit - 1) / kQPerWGSplit, s.B * s.H);
+    // There is no mixed form of this launch: between the two decompositions, take the one whose
+    // rounds of work-groups over the 256 CUs cost less (a key-split work-group takes about 0.55 of a
+    // 256-query one)
+    const double cost256 = (double)((w256 + 255) / 256), cost128 = 0.55 * (double)((w128 + 255) / 256);
+    const bool split = s.variant == 2 || (s.variant != 1 && ((int)w256 <= kSplitBelowWGs || cost128 < cost256));
+    const unsigned wgs = split ? w128 : w256;
     s.copy_wgs = 0;
     if (s.arrive != nullptr) {
       for (int c = s.multi_fp8 ? 0 : 1; c < s.n_multi; ++c)
         if (!s.chunk[c].k_src || !s.chunk[c].v_src || s.chunk[c].bytes <= 0 || s.chunk[c].bytes % 16 != 0 ||
             !aligned16(s.chunk[c].k_src) || !aligned16(s.chunk[c].v_src) || !aligned16(s.chunk[c].k) || !aligned16(s.chunk[c].v) ||
-            (s.multi_fp8 && (!s.chunk[c].k_scale_src || !s.chunk[c].v_scale_src || !aligned16(s.chunk[c].k_scale_src)))) {
+            (s.multi_fp8 && (!s.chunk[c].k_scale_src || !s.chunk[c].v_scale_src || !aligned16(s.chunk[c].k_scale_src) ||
+                             ((uintptr_t)s.chunk[c].mask_src & 3u) != 0))) {
           set_error("transfers inside a launch over several chunks need 16-byte aligned sources and buffers");
           return USP_ERR_INVALID_ARG;
         }
@@ -1155,6 +1176,8 @@ usp_status launch_attn_mfma(const AttnStep& step, hipStream_t st) {
       s.copy_wgs = prefetch_wg_count(s, (int)wgs, 1);
       s.n_copy = 0;
     }
+    if (s.multi_fp8 && s.multi_masked)
+      return split ? launch_pp<true, true, true, false>(s, wgs, st) : launch_pp<false, true, true, false>(s, wgs, st);
     if (s.multi_fp8) return split ? launch_pp<true, true, true, true>(s, wgs, st) : launch_pp<false, true, true, true>(s, wgs, st);
     if (split) return launch_pp<true, false, true>(s, wgs, st);
     return launch_pp<false, false, true>(s, wgs, st);

@@ -103,10 +103,27 @@ __device__ __forceinline__ void fp8_chunk_prepare(const AttnStep& s, int c, int6
     const int key = (int)(row - bh * ch.Sc);
     const float4 ks = ((const float4*)ch.k_scale_src)[u];
     float* rec = s.ext + ((bh * nt_total + tile0 + (key >> 6)) << 8) + (key & 63);
-    put16<kDeviceScope>((uint4*)rec, make_uint4(__float_as_uint(ks.x * scale2), __float_as_uint(ks.y * scale2),
-                                               __float_as_uint(ks.z * scale2), __float_as_uint(ks.w * scale2)));
-    put16<kDeviceScope>((uint4*)(rec + 64), zero);      // no dead keys: bias 0, flag 0
-    put16<kDeviceScope>((uint4*)(rec + 128), zero);
+    if (ch.mask_src == nullptr) {                       // no dead keys: bias 0, flag 0
+      put16<kDeviceScope>((uint4*)rec, make_uint4(__float_as_uint(ks.x * scale2), __float_as_uint(ks.y * scale2),
+                                                 __float_as_uint(ks.z * scale2), __float_as_uint(ks.w * scale2)));
+      put16<kDeviceScope>((uint4*)(rec + 64), zero);
+      put16<kDeviceScope>((uint4*)(rec + 128), zero);
+      put16<kDeviceScope>((uint4*)(rec + 192), zero);
+      continue;
+    }
+    // masked chunk: a dead key gets factor 0 and bias -inf; the tile's flag says whether it has any.
+    // The 16 lanes that share a tile are consecutive (units are handed out in lane order and a tile
+    // is 16 units), so the wave's ballot holds the tile's 16 answers side by side.
+    const uint32_t mk = *(const uint32_t*)(ch.mask_src + (bh / s.H) * ch.Sc + key);
+    const bool k0 = (mk & 0xffu) != 0, k1 = (mk & 0xff00u) != 0, k2 = (mk & 0xff0000u) != 0, k3 = (mk & 0xff000000u) != 0;
+    const unsigned long long dead = __builtin_amdgcn_ballot_w64(!(k0 && k1 && k2 && k3));
+    const int lane16 = (int)(__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u))) & ~15;
+    const uint32_t fl = ((dead >> lane16) & 0xffffull) != 0 ? 0x3f800000u : 0u;
+    const uint32_t ninf = 0xff800000u;
+    put16<kDeviceScope>((uint4*)rec, make_uint4(k0 ? __float_as_uint(ks.x * scale2) : 0u, k1 ? __float_as_uint(ks.y * scale2) : 0u,
+                                               k2 ? __float_as_uint(ks.z * scale2) : 0u, k3 ? __float_as_uint(ks.w * scale2) : 0u));
+    put16<kDeviceScope>((uint4*)(rec + 64), make_uint4(k0 ? 0u : ninf, k1 ? 0u : ninf, k2 ? 0u : ninf, k3 ? 0u : ninf));
+    put16<kDeviceScope>((uint4*)(rec + 128), make_uint4(fl, fl, fl, fl));
     put16<kDeviceScope>((uint4*)(rec + 192), zero);
   }
 }

@@ -229,8 +229,8 @@ usp_status make_plan(const usp_attn_desc* d, Plan* p) {
   }
   // FP8 chunks, all of them at hand or with the transfers inside the launches: the decoding of
   // Algorithm 1 line 4 rides in the one launch over the ring (copy work-groups decode chunk r+1
-  // while chunk r is computed on), each live chunk into bf16 buffers of its own.  A key mask, known
-  // only at the call, sends the call back to one launch per chunk.
+  // while chunk r is computed on), each live chunk into bf16 buffers of its own; key masks go into the
+  // records the same work-groups write.
   p->ring8 = p->fp8 && p->mfma && !p->unfused && !(d->flags & (USP_ATTN_STEPWISE | USP_ATTN_DOUBLE_BUFFER));
   if (p->ring8) {
     int live = 0;
@@ -475,9 +475,17 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
     if ((st = stage_chunk(1)) != USP_OK) return st;
   }
 
+  // One launch over the ring pays when a ring step is short (launch, pipeline fill and the carried
+  // state's round trip weigh on it).  Where the Q shard's 256-query blocks need more than one round of
+  // work-groups on the 256 CUs, a step is long, its per-chunk launch can mix the two work
+  // decompositions to fill its last round, and the plain call keeps one launch per chunk; a call
+  // that asks for the transfers inside the launches takes the one launch at any size.
+  const int64_t q_blocks = (int64_t)desc->B * desc->H * ((desc->Sq + 255) / 256);
+  const bool short_steps = q_blocks <= 256 || p.fused_pf;
   // Every chunk resident and plain, merge fused: one launch over the whole ring.
   {
-    bool one_launch = p.mfma && !p.fp8 && (!p.dbuf || p.ring1) && !p.unfused && p.W > 1 && !(desc->flags & USP_ATTN_STEPWISE);
+    bool one_launch = p.mfma && !p.fp8 && (!p.dbuf || p.ring1) && !p.unfused && p.W > 1 && !(desc->flags & USP_ATTN_STEPWISE) &&
+                      short_steps;
     int n_live = 0;
     for (int r = 0; one_launch && r < p.W; ++r) {
       const int len = desc->chunk_len[r];
@@ -520,11 +528,11 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
     }
   }
 
-  // FP8 chunks without key masks: one launch over the ring that decodes them as it goes
-  if (p.ring8) {
+  // FP8 chunks: one launch over the ring that decodes them as it goes
+  if (p.ring8 && short_steps) {
     bool ok = true;
     for (int r = 0; r < p.W; ++r)
-      if (desc->chunk_len[r] > 0 && ((key_mask && key_mask[r]) || ((uintptr_t)k_scales[r] & 15) != 0)) ok = false;
+      if (desc->chunk_len[r] > 0 && (((uintptr_t)k_scales[r] & 15) != 0 || (key_mask && ((uintptr_t)key_mask[r] & 3) != 0))) ok = false;
     if (ok) {
       AttnStep a;
       memset(&a, 0, sizeof(a));
@@ -548,6 +556,8 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
           c.k = ws + stage; c.v = ws + stage + align_up(bytes);
           c.k_src = k_chunks[r]; c.v_src = v_chunks[r]; c.bytes = (int64_t)(bytes / 2);
           c.k_scale_src = k_scales[r]; c.v_scale_src = v_scales[r];
+          c.mask_src = key_mask ? key_mask[r] : nullptr;
+          if (c.mask_src) a.multi_masked = 1;
         }
         stage += 2 * align_up(bytes);
       }

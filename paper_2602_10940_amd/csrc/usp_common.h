@@ -123,10 +123,12 @@ struct AttnStep {
     const void* k; const void* v; int64_t ks0, ks1; int Sc;
     const void* k_src; const void* v_src; int64_t bytes;
     const float* k_scale_src; const float* v_scale_src;
+    const uint8_t* mask_src;   // multi_fp8: key mask [B,Sc] of the chunk (nonzero = key takes part), or null
   };
   static constexpr int kMaxMulti = 16;
   int n_multi;
   int multi_fp8;
+  int multi_masked;          // multi_fp8: some chunk has a key mask (the records may then flag dead keys)
   int* arrive;               // [kMaxMulti] counters, zero when the launch starts; or null
   Chunk chunk[kMaxMulti];
   // Prefetch carried by this launch (Algorithm 2, the transfer of the next chunk): the last

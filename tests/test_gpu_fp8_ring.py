@@ -95,19 +95,43 @@ def test_fp8_ring_one_launch_poisoned_workspace_and_alternating_inputs():
         assert torch.equal(o, runs[it & 1][6][0]) and torch.equal(l, runs[it & 1][6][1]), it
 
 
-def test_fp8_ring_with_a_key_mask_takes_the_per_chunk_form():
-    """A key mask is known only at the call: the same descriptor (and workspace size) then runs one
-    launch per chunk, and the result still matches the oracle."""
+def test_fp8_ring_one_launch_with_key_masks():
+    """Key masks in the one-launch form: the copy work-groups write them into the per-tile records
+    (factor 0, bias -inf, a flag per tile).  A tail of masked keys; then a batch of three with a mask
+    of its own per entry: nothing masked, a hole in the first chunk with the second chunk dead, and
+    only the first tile plus one key of the second chunk alive."""
     P = _P()
     wl = W.Workload("fp8_masked", 73, 1, 2, 128, 150, (128, 192), "bf16", masked_keys=(250, 320))
     inp, q, kq, ksc, vq, vsc, kx, vx = _fp8_ring(wl)
     km = [torch.from_numpy(m).to(DEV) for m in inp.key_mask]
     ro, rl = orc.ring_attention(inp.q, kx, vx, float(inp.softmax_scale), inp.key_mask)
-    for flags in (0, FUSED):
+    for flags in (0, FUSED, STEPWISE, WIDE, SPLIT):
         o, l = P.usp_ring_attn_fwd(q, kq, vq, k_scales=ksc, v_scales=vsc, key_mask=km,
                                    softmax_scale=float(inp.softmax_scale), flags=flags)
         torch.cuda.synchronize()
         _assert_parity(host_f64(o), host_f64(l), ro, rl)
+
+    wl = W.Workload("fp8_masked_b3", 74, 3, 2, 128, 300, (192, 128, 64), "bf16", masked_keys=(100, 384))
+    inp, q, kq, ksc, vq, vsc, kx, vx = _fp8_ring(wl)
+    for m in inp.key_mask:
+        m[0, :] = 1
+    inp.key_mask[0][1, :] = 1; inp.key_mask[0][1, 3:70] = 0; inp.key_mask[1][1, :] = 0; inp.key_mask[2][1, :] = 1
+    inp.key_mask[0][2, :] = 0; inp.key_mask[0][2, :64] = 1; inp.key_mask[1][2, :] = 0; inp.key_mask[1][2, 5] = 1
+    inp.key_mask[2][2, :] = 0
+    km = [torch.from_numpy(m).to(DEV) for m in inp.key_mask]
+    ro, rl = orc.ring_attention(inp.q, kx, vx, float(inp.softmax_scale), inp.key_mask)
+    for flags in (0, STEPWISE, WIDE, SPLIT):
+        o, l = P.usp_ring_attn_fwd(q, kq, vq, k_scales=ksc, v_scales=vsc, key_mask=km,
+                                   softmax_scale=float(inp.softmax_scale), flags=flags)
+        torch.cuda.synchronize()
+        _assert_parity(host_f64(o), host_f64(l), ro, rl)
+    # a mask for some chunks only
+    km2 = [km[0], None, km[2]]
+    masks2 = [inp.key_mask[0], np.ones_like(inp.key_mask[1]), inp.key_mask[2]]
+    ro2, rl2 = orc.ring_attention(inp.q, kx, vx, float(inp.softmax_scale), masks2)
+    o, l = P.usp_ring_attn_fwd(q, kq, vq, k_scales=ksc, v_scales=vsc, key_mask=km2, softmax_scale=float(inp.softmax_scale))
+    torch.cuda.synchronize()
+    _assert_parity(host_f64(o), host_f64(l), ro2, rl2)
 
 
 def test_fp8_ring_flux1024_r4_full_size_sampled_rows():
