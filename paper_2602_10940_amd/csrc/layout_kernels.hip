@@ -1,26 +1,28 @@
 // Head-dimension padding for the bf16 d = 64 case: the matrix-core attention kernels are written
 // for d = 128, and softmax(Q K^T) V is unchanged when Q and K get 64 extra zero columns (the scores
 // of section 2.2 gain only zero terms) and V gets 64 extra zero columns (they come out as zero columns
-// of O, which are dropped).  pad: strided [B,H,S,64] bf16 -> dense [B,H,S,128]; unpad: the reverse
-// for O.  One thread moves 16 bytes; both kernels are bandwidth-bound and tiny next to the attention.
+// of O, which are dropped).  pad: strided [B,H,S,64] bf16 (or E4M3 codes, whose zero code is 0.0) ->
+// dense [B,H,S,128]; unpad: the reverse for a bf16 O.  One thread moves 16 bytes; both kernels are bandwidth-bound and tiny next to the attention.
 #include <hip/hip_runtime.h>
 #include "usp_common.h"
 
 namespace usp {
 namespace {
 
-__global__ __launch_bounds__(256) void pad64_kernel(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst, int H, int S,
-                                                    int64_t s0, int64_t s1, int64_t s2, int64_t rows) {
-  const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;   // 16 units of 16 bytes per padded row
-  const int64_t row = g >> 4;
+// kUnits: 16-byte units of a source row (8 for bf16, 4 for one-byte codes); the padded row has twice as many
+template <int kUnits>
+__global__ __launch_bounds__(256) void pad64_kernel(const unsigned char* __restrict__ src, unsigned char* __restrict__ dst,
+                                                    int H, int S, int64_t s0, int64_t s1, int64_t s2, int64_t rows) {
+  const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t row = g / (2 * kUnits);
   if (row >= rows) return;
-  const int part = (int)(g & 15);
+  const int part = (int)(g - row * (2 * kUnits));
   uint4 v = make_uint4(0u, 0u, 0u, 0u);
-  if (part < 8) {
+  if (part < kUnits) {
     const int64_t t = row % S, bh = row / S, h = bh % H, b = bh / H;
-    v = *reinterpret_cast<const uint4*>(src + b * s0 + h * s1 + t * s2 + part * 8);
+    v = *reinterpret_cast<const uint4*>(src + (b * s0 + h * s1 + t * s2) * (kUnits * 16 / 64) + part * 16);
   }
-  *reinterpret_cast<uint4*>(dst + row * 128 + part * 8) = v;
+  *reinterpret_cast<uint4*>(dst + (row * 2 * kUnits + part) * 16) = v;
 }
 
 __global__ __launch_bounds__(256) void unpad64_kernel(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst, int H, int S,
@@ -36,11 +38,16 @@ __global__ __launch_bounds__(256) void unpad64_kernel(const bf16_t* __restrict__
 
 }  // namespace
 
-usp_status launch_pad64(const void* src, void* dst, int B, int H, int S, const int64_t stride[3], hipStream_t st) {
+usp_status launch_pad64(const void* src, void* dst, int B, int H, int S, const int64_t stride[3], int elt_bytes,
+                        hipStream_t st) {
   const int64_t rows = (int64_t)B * H * S;
   if (rows == 0) return USP_OK;
-  hipLaunchKernelGGL(pad64_kernel, dim3((unsigned)((rows * 16 + 255) / 256)), dim3(256), 0, st, (const bf16_t*)src,
-                     (bf16_t*)dst, H, S, stride[0], stride[1], stride[2], rows);
+  if (elt_bytes == 2)
+    hipLaunchKernelGGL(pad64_kernel<8>, dim3((unsigned)((rows * 16 + 255) / 256)), dim3(256), 0, st, (const unsigned char*)src,
+                       (unsigned char*)dst, H, S, stride[0], stride[1], stride[2], rows);
+  else
+    hipLaunchKernelGGL(pad64_kernel<4>, dim3((unsigned)((rows * 8 + 255) / 256)), dim3(256), 0, st, (const unsigned char*)src,
+                       (unsigned char*)dst, H, S, stride[0], stride[1], stride[2], rows);
   USP_CHECK_HIP(hipGetLastError());
   return USP_OK;
 }

@@ -142,7 +142,7 @@ usp_status make_plan(const usp_attn_desc* d, Plan* p) {
   p->fp8 = d->kv_dtype == USP_FP8_E4M3FN;
   USP_CHECK_ARG(!((d->flags & USP_ATTN_DOUBLE_BUFFER) && (d->flags & USP_ATTN_FUSED_PREFETCH)),
                 "USP_ATTN_DOUBLE_BUFFER and USP_ATTN_FUSED_PREFETCH exclude each other");
-  p->pad64 = d->qo_dtype == USP_BF16 && d->kv_dtype == USP_BF16 && d->d == 64;
+  p->pad64 = d->qo_dtype == USP_BF16 && (d->kv_dtype == USP_BF16 || d->kv_dtype == USP_FP8_E4M3FN) && d->d == 64;
   if (p->pad64) {
     const usp_attn_desc in = padded_desc(d);
     Plan ip;
@@ -155,7 +155,7 @@ usp_status make_plan(const usp_attn_desc* d, Plan* p) {
     size_t off = 0;
     if (padded_o(d)) { p->off_pad_o = off; off += align_up(p->rows_q * 128 * 2); }
     p->off_pad_kv = off;
-    for (int r = 0; r < p->W; ++r) off += 2 * align_up((size_t)d->B * d->H * d->chunk_len[r] * 128 * 2);
+    for (int r = 0; r < p->W; ++r) off += 2 * align_up((size_t)d->B * d->H * d->chunk_len[r] * 128 * elt_size(d->kv_dtype));
     p->off_pad_inner = off; off += ip.total;
     p->inner_total = ip.total;
     p->total = off;
@@ -413,18 +413,19 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
     size_t off = p.off_pad_kv;
     for (int r = 0; r < p.W; ++r) {
       const int len = desc->chunk_len[r];
-      const size_t bytes = align_up((size_t)desc->B * desc->H * len * 128 * 2);
+      const int kv_es = (int)elt_size(desc->kv_dtype);
+      const size_t bytes = align_up((size_t)desc->B * desc->H * len * 128 * kv_es);
       kp[r] = ws + off; vp[r] = ws + off + bytes;
       if (len > 0) {
         const int64_t dense[3] = {(int64_t)desc->H * len * 64, (int64_t)len * 64, 64};
         const int64_t* ks = kv_auto(desc) ? dense : desc->kv_stride;
-        if ((st = launch_pad64(k_chunks[r], ws + off, desc->B, desc->H, len, ks, cs)) != USP_OK) return st;
-        if ((st = launch_pad64(v_chunks[r], ws + off + bytes, desc->B, desc->H, len, ks, cs)) != USP_OK) return st;
+        if ((st = launch_pad64(k_chunks[r], ws + off, desc->B, desc->H, len, ks, kv_es, cs)) != USP_OK) return st;
+        if ((st = launch_pad64(v_chunks[r], ws + off + bytes, desc->B, desc->H, len, ks, kv_es, cs)) != USP_OK) return st;
       }
       off += 2 * bytes;
     }
     g_half_d = true;
-    st = usp_ring_attn_fwd(&in, q, kp.data(), vp.data(), nullptr, nullptr, key_mask, pad_o ? (void*)(ws + p.off_pad_o) : out, lse,
+    st = usp_ring_attn_fwd(&in, q, kp.data(), vp.data(), k_scales, v_scales, key_mask, pad_o ? (void*)(ws + p.off_pad_o) : out, lse,
                            p.inner_total ? ws + p.off_pad_inner : nullptr, p.inner_total, compute_stream, copy_stream);
     g_half_d = false;
     if (st != USP_OK || !pad_o) return st;

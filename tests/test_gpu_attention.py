@@ -307,7 +307,9 @@ def test_fp8_kv_ring_against_oracle_on_dequantised_values():
         _assert_parity(host_f64(o), host_f64(l), ro, rl)
 
 
-def test_fp8_kv_generic_kernel_d64():
+def test_fp8_kv_d64():
+    """FP8 K/V with head dimension 64 and bf16 Q: codes zero-padded to d = 128 (the zero code is 0.0),
+    then the d = 128 path."""
     P = _P()
     rng = np.random.Generator(np.random.PCG64(9))
     B, H, Sq, L, d = 1, 2, 50, 70, 64

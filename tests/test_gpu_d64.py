@@ -65,3 +65,29 @@ def test_bf16_d64_default_scale_is_that_of_the_original_head_dimension():
     assert torch.equal(o0, o1) and torch.equal(l0, l1)
     ro, rl = orc.ring_attention(inp.q, inp.k, inp.v, 0.125)
     _assert_parity(host_f64(o0), host_f64(l0), ro, rl)
+
+
+@pytest.mark.parametrize("lens,flags", [((192, 100), 0), ((128, 256, 64), 0), ((128, 256, 64), 64), ((128, 192), 16)])
+def test_fp8_kv_d64_ring_against_oracle(lens, flags):
+    """FP8 K/V chunks with d = 64 (ragged chunks: one launch per chunk; whole tiles: the one-launch
+    form with the decode inside), a key mask over the tail."""
+    import paper_2602_10940_amd as P
+    S = sum(lens)
+    wl = W.Workload("d64_fp8", 94, 2, 3, 64, 150, tuple(lens), "bf16", masked_keys=(S - 40, S))
+    inp = W.make_attention_inputs(wl)
+    q = dev_bf16(inp.q)
+    kq, ksc, vq, vsc, kx, vx = [], [], [], [], [], []
+    for k, v in zip(inp.k, inp.v):
+        B, H, L, d = k.shape
+        a, sa = P.usp_fp8_quant(dev_bf16(k).reshape(B * H * L, d))
+        b, sb = P.usp_fp8_quant(dev_bf16(v).reshape(B * H * L, d))
+        kq.append(a.reshape(B, H, L, d)); ksc.append(sa.reshape(B, H, L))
+        vq.append(b.reshape(B, H, L, d)); vsc.append(sb.reshape(B, H, L))
+        kx.append(orc.dequant_exact_f64(a.cpu().numpy().reshape(B, H, L, d), sa.cpu().numpy().reshape(B, H, L)))
+        vx.append(orc.dequant_exact_f64(b.cpu().numpy().reshape(B, H, L, d), sb.cpu().numpy().reshape(B, H, L)))
+    km = [torch.from_numpy(m).to(DEV) for m in inp.key_mask]
+    o, l = P.usp_ring_attn_fwd(q, kq, vq, k_scales=ksc, v_scales=vsc, key_mask=km, softmax_scale=float(inp.softmax_scale),
+                               flags=flags)
+    torch.cuda.synchronize()
+    ro, rl = orc.ring_attention(inp.q, kx, vx, float(inp.softmax_scale), inp.key_mask)
+    _assert_parity(host_f64(o), host_f64(l), ro, rl)
