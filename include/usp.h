@@ -99,8 +99,9 @@ typedef enum {
  * [B,H,chunk_len[r],d] array" (the only way to describe dense chunks of unequal length).
  */
 typedef struct usp_attn_desc {
-  int32_t B, H, d;          /* d: a multiple of 8 up to 256.  bf16 with d = 128 runs on the matrix-core
-                               kernels; every other combination on a slower general kernel */
+  int32_t B, H, d;          /* d: a multiple of 8 up to 256.  bf16 Q with d = 128 runs on the matrix-core
+                               kernels, and so does bf16 Q with d = 64 (on copies of K and V padded to
+                               d = 128 in the workspace); every other combination on a slower general kernel */
   int32_t Sq;               /* tokens of the local Q shard */
   int32_t n_chunks;         /* ring degree W >= 1 */
   const int32_t* chunk_len; /* HOST array [n_chunks] */
@@ -116,7 +117,7 @@ typedef struct usp_attn_desc {
 /*
  * Bytes of device workspace usp_ring_attn_fwd needs for this descriptor
  * (0 is possible, e.g. one f32 chunk; bf16 with d = 128 always asks for a little, about
- * 1/16 of a K chunk).  Returns (size_t)-1 if the descriptor is invalid.
+ * 1/16 of a K chunk; bf16 with d = 64 for twice its K and V on top).  Returns (size_t)-1 if the descriptor is invalid.
  */
 size_t usp_ring_attn_workspace_bytes(const usp_attn_desc* desc);
 
