@@ -642,7 +642,7 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
   // Fast path: exponentials are taken against the current reference m without first looking for
   // the tile's maximum; the row sum then certifies the result: if this lane's sum of P is at most
   // 2^60, no P exceeded 2^60, and neither l (at most 2^60 per key) nor O~ (at most 2^60 |v| per key)
-  // can leave the fp32 range over any sequence that fits the device; a reference that lags the
+  // leaves the fp32 range (2^127) over 2^20 keys with |v| up to 2^40; a reference that lags the
   // maximum by D only scales P, l and O~ by 2^D, which floating point carries without loss.  Only
   // when some lane fails that test (always on the first tile, where m = -inf makes every P inf)
   // does the wave find the true maximum, move m, rescale O and l, and redo the exponentials.
