@@ -238,13 +238,20 @@ __device__ __forceinline__ void finish_and_store(const AttnStep& s, f32x16 (&oac
 // its exact codes: its scale costs nothing inside the exponent's FMA, and rounding K would move
 // the scores themselves.
 //
-// Template parameter kMulti (plain kernels only) lets one launch cover a whole ring (Algorithm 2):
-// the 64-key tiles of up to 16 chunks form one stream in ring order, a cursor maps a tile index to
+// Template parameter kMulti lets one launch cover a whole ring (Algorithm 2): the 64-key tiles of up
+// to 16 chunks (whole tiles only) form one stream in ring order, a cursor maps a tile index to
 // its chunk's pointer, and the running (O~, m, l) stays in registers from the first tile to the
 // last, which is the merge of section 3.4 applied tile by tile.  With AttnStep::arrive set the
 // launch also plays the ring's transfers: its first work-groups copy the chunks into staging
 // buffers and count themselves on a per-chunk arrival counter (prefetch_copy.h), and an attention
 // work-group waits for a chunk's count before it loads the chunk's first tile (wait_arrival).
+// FP8 chunks (AttnStep::multi_fp8) are decoded by those work-groups on the way (Algorithm 1 line 4:
+// K widened, V dequantised, the records above written, masks included) and attended by the
+// record-reading form; there a chunk that came with a mask marks all of its tiles as possibly
+// holding dead keys, since a per-tile flag would have to be read while the launch still writes it.
+//
+// kNoDead: records that carry only per-key factors (no mask, whole tiles): flag and bias are never
+// read.  kHalfD: head dimension 64 held in the d = 128 layout (see attn_pp_body).
 // =============================================================================================
 __device__ __forceinline__ void lds_dma16(const void* gbase, uint32_t lane_off, uint32_t lds_base) {
   // 64 lanes x 16 bytes from gbase (wave-uniform) + lane_off (per lane): lane i's 16 bytes land at

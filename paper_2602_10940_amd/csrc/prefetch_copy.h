@@ -1,7 +1,12 @@
-// Device-side copy of the next KV chunk into the idle staging buffer, run by the leading
-// work-groups of an attention launch (Algorithm 2: the transfer of chunk r+1 overlaps the compute
-// on chunk r).  Stream order gives the two hazards for free: the launch that reads the buffer
-// starts after this one has ended, and the buffer's previous reader ended before this one began.
+// Device-side transfers that ride in an attention launch (Algorithm 2: the transfer of chunk r+1
+// overlaps the compute on chunk r).
+//  * prefetch_copy: the next chunk into the idle one of two staging buffers, run by extra work-groups
+//    of a per-chunk launch.  Stream order gives the two hazards for free: the launch that reads the
+//    buffer starts after this one has ended, and the buffer's previous reader ended before this one
+//    began.
+//  * stream_chunks / stream_chunks_fp8: every later chunk of a ring into a buffer of its own, run by
+//    the first work-groups of the one launch over the ring, each chunk published through an arrival
+//    counter; the FP8 form decodes the chunk on the way (Algorithm 1 line 4).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
