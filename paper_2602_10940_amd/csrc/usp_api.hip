@@ -231,7 +231,8 @@ usp_status make_plan(const usp_attn_desc* d, Plan* p) {
   // Algorithm 1 line 4 rides in the one launch over the ring (copy work-groups decode chunk r+1
   // while chunk r is computed on), each live chunk into bf16 buffers of its own; key masks go into the
   // records the same work-groups write.
-  p->ring8 = p->fp8 && p->mfma && !p->unfused && !(d->flags & (USP_ATTN_STEPWISE | USP_ATTN_DOUBLE_BUFFER));
+  p->ring8 = p->fp8 && p->mfma && !p->unfused && !(d->flags & (USP_ATTN_STEPWISE | USP_ATTN_DOUBLE_BUFFER)) &&
+             (p->fused_pf || (int64_t)d->B * d->H * ((d->Sq + 255) / 256) <= 256);   // short ring steps (see usp_ring_attn_fwd)
   if (p->ring8) {
     int live = 0;
     size_t tiles = 0;
