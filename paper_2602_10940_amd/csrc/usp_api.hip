@@ -628,6 +628,11 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
       a.k = ws + p.off_deq_k; a.v = ws + p.off_deq_v;
       a.v_scale = nullptr;
       a.kv_dtype = USP_BF16;
+    } else if (p.dequant_stage) {
+      // an empty chunk still merges and stores (its epilogue mode): keep it on the matrix-core kernel,
+      // which reads no key of it
+      a.k_scale = nullptr; a.v_scale = nullptr;
+      a.kv_dtype = USP_BF16;
     }
     if (attn_mfma_supported(a) && attn_mfma_needs_ext(a)) {
       a.ext = (float*)(ws + p.off_ext);

@@ -67,7 +67,8 @@ def test_bf16_d64_default_scale_is_that_of_the_original_head_dimension():
     _assert_parity(host_f64(o0), host_f64(l0), ro, rl)
 
 
-@pytest.mark.parametrize("lens,flags", [((192, 100), 0), ((128, 256, 64), 0), ((128, 256, 64), 64), ((128, 192), 16)])
+@pytest.mark.parametrize("lens,flags", [((192, 100), 0), ((128, 256, 64), 0), ((128, 256, 64), 64), ((128, 192), 16),
+                                        ((256, 0), 0), ((256, 64, 0), 1), ((0, 128, 0, 64), 16)])   # empty chunks, also last
 def test_fp8_kv_d64_ring_against_oracle(lens, flags):
     """FP8 K/V chunks with d = 64 (ragged chunks: one launch per chunk; whole tiles: the one-launch
     form with the decode inside), a key mask over the tail."""
@@ -79,6 +80,11 @@ def test_fp8_kv_d64_ring_against_oracle(lens, flags):
     kq, ksc, vq, vsc, kx, vx = [], [], [], [], [], []
     for k, v in zip(inp.k, inp.v):
         B, H, L, d = k.shape
+        if L == 0:
+            kq.append(torch.empty((B, H, 0, d), dtype=torch.uint8, device=DEV)); vq.append(kq[-1])
+            ksc.append(torch.empty((B, H, 0), dtype=torch.float32, device=DEV)); vsc.append(ksc[-1])
+            kx.append(k.astype(np.float64)); vx.append(v.astype(np.float64))
+            continue
         a, sa = P.usp_fp8_quant(dev_bf16(k).reshape(B * H * L, d))
         b, sb = P.usp_fp8_quant(dev_bf16(v).reshape(B * H * L, d))
         kq.append(a.reshape(B, H, L, d)); ksc.append(sa.reshape(B, H, L))
@@ -87,7 +93,7 @@ def test_fp8_kv_d64_ring_against_oracle(lens, flags):
         vx.append(orc.dequant_exact_f64(b.cpu().numpy().reshape(B, H, L, d), sb.cpu().numpy().reshape(B, H, L)))
     km = [torch.from_numpy(m).to(DEV) for m in inp.key_mask]
     o, l = P.usp_ring_attn_fwd(q, kq, vq, k_scales=ksc, v_scales=vsc, key_mask=km, softmax_scale=float(inp.softmax_scale),
-                               flags=flags)
+                               flags=flags, copy_stream=torch.cuda.Stream() if flags & 1 else None)
     torch.cuda.synchronize()
     ro, rl = orc.ring_attention(inp.q, kx, vx, float(inp.softmax_scale), inp.key_mask)
     _assert_parity(host_f64(o), host_f64(l), ro, rl)
