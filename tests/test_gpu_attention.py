@@ -569,3 +569,15 @@ def test_invalid_arguments_are_rejected():
     assert e.value.status == -1
     with pytest.raises(P.UspError):
         P.usp_fp8_quant(torch.zeros((4, 12), dtype=torch.bfloat16, device=DEV))
+
+
+@pytest.mark.parametrize("flags", [0, 64, 16])
+def test_long_sequence_65536_keys_sampled_rows(flags):
+    """A 64K-key ring (4 chunks of 16384) against the oracle on sampled query rows: tile counts, byte
+    offsets and the running sums far beyond the benchmark shapes."""
+    wl = W.Workload("long", 77, 1, 2, 128, 512, (16384,) * 4, "bf16")
+    inp = W.make_attention_inputs(wl)
+    o, l = _run(inp, flags=flags)
+    rows = np.array([0, 1, 31, 32, 127, 128, 255, 256, 300, 511])
+    ro, rl = _oracle(inp, rows)
+    _assert_parity(o[:, :, rows, :], l[:, :, rows], ro, rl)
