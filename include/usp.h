@@ -67,8 +67,7 @@ typedef enum {
                                         copy it, into bf16 K (the codes as they are), bf16 V (codes
                                         times scales) and K's scales as per-key factors of the exponent;
                                         the first chunk is decoded by a launch of its own in front;
-                                        key masks go into the records (every tile of a chunk that came
-                                        with a mask is treated as one that may hold dead keys). */
+                                        key masks go into the records as well. */
 /* Work decomposition of the bf16 d=128 matrix-core kernel on unmasked chunks whose length is a
  * multiple of 64.  Default (neither bit): chosen from the number of work-groups the Q shard gives.
  * All variants meet the same accuracy bar; the bits exist for tuning and for tests. */

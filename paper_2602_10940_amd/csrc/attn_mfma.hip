@@ -247,8 +247,8 @@ __device__ __forceinline__ void finish_and_store(const AttnStep& s, f32x16 (&oac
 // work-group waits for a chunk's count before it loads the chunk's first tile (wait_arrival).
 // FP8 chunks (AttnStep::multi_fp8) are decoded by those work-groups on the way (Algorithm 1 line 4:
 // K widened, V dequantised, the records above written, masks included) and attended by the
-// record-reading form; there a chunk that came with a mask marks all of its tiles as possibly
-// holding dead keys, since a per-tile flag would have to be read while the launch still writes it.
+// record-reading form; there the tiles of a chunk that came with a mask read their dead-key flag
+// from the record in LDS (it cannot be fetched ahead from memory the launch is still writing).
 //
 // kNoDead: records that carry only per-key factors (no mask, whole tiles): flag and bias are never
 // read.  kHalfD: head dimension 64 held in the d = 128 layout (see attn_pp_body).
@@ -737,8 +737,9 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
     const float* p = s.ext + ((int64_t)bh_ * nt_all + min(tile, nt_all - 1)) * (kExtTileB / 4) + 128;
     return *(const_fptr)(uintptr_t)p;
   };
-  // several chunks per launch: the records are written while the launch runs, so instead of a flag
-  // per tile every tile of a chunk that came with a key mask is treated as one that may hold dead keys
+  // several chunks per launch: the records are written while the launch runs, so a tile's flag cannot
+  // be fetched ahead from global memory; tiles of chunks that came with a key mask read it from their
+  // record in LDS when the softmax phase starts (a short wait), tiles of other chunks skip it
   int sm_c = 0, sm_first = 0;   // chunk of sm_tile and the index of its first tile
   auto chunk_masked = [&](int tile) -> bool {
     while (sm_c + 1 < s.n_multi && tile >= sm_first + s.chunk[sm_c].Sc / kTile) {
@@ -758,7 +759,12 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
     if (kExt && !kNoDead) {
       // this tile's flag was fetched during the wave's previous softmax phase; fetch the next one
       if (kMulti) {
-        dead_keys = chunk_masked(sm_tile);
+        // a tile of a chunk that came with a mask: its flag, from the record in LDS
+        if (chunk_masked(sm_tile)) {
+          const float f = *reinterpret_cast<const __attribute__((address_space(3))) float*>(
+              (lds_cptr)(uintptr_t)(lds_ext + xs * kExtTileB + 512));
+          dead_keys = __builtin_amdgcn_readfirstlane(__float_as_uint(f)) != 0u;
+        }
         sm_tile += kPreStep;
       } else {
         dead_keys = flag_next != 0.0f;
