@@ -142,6 +142,16 @@ def main() -> int:
     yb = torch.empty((8 * R, C), dtype=torch.bfloat16, device=dev)
     t_quant8 = per_launch(lambda i: P.usp_fp8_quant(xb, qb, sb), reps=100, rounds=3)
     t_deq8 = per_launch(lambda i: P.usp_fp8_dequant(qb, sb, y=yb), reps=100, rounds=3)
+    # ... and on 3 payloads (the Q, K and V of one attention layer entering the All-to-All) in one call
+    R3 = 3 * R
+    x3 = torch.cat(xs[:24], 0)                      # 8 disjoint sets of three payloads: 1.7 GB with codes and outputs
+    q3 = torch.empty((24 * R, C), dtype=torch.uint8, device=dev)
+    s3 = torch.empty((24 * R,), dtype=torch.float32, device=dev)
+    y3 = torch.empty((24 * R, C), dtype=torch.bfloat16, device=dev)
+    sl = lambda t, i: t[(i % 8) * R3:(i % 8) * R3 + R3]
+    t_quant3 = per_launch(lambda i: P.usp_fp8_quant(sl(x3, i), sl(q3, i), sl(s3, i)), reps=200, rounds=3)
+    t_deq3 = per_launch(lambda i: P.usp_fp8_dequant(sl(q3, i), sl(s3, i), y=sl(y3, i)), reps=200, rounds=3)
+    del x3, q3, s3, y3
     # pack / unpack in the layouts around the All-to-All (section 2.2.1), 8 peers: the same 28.3 MB as
     # [1, 24, 4608, 128] on the sequence-sharded side -> send blocks [8][1][3][4608] rows of 128 ->
     # (exchange) -> [1, 3, 36864, 128] on the head-sharded side
@@ -219,6 +229,12 @@ def main() -> int:
                            "quant_gbs": round(8 * fp8_bytes / (t_quant8 * 1e-3) * 1e-9, 1),
                            "dequant_gbs": round(8 * fp8_bytes / (t_deq8 * 1e-3) * 1e-9, 1),
                            "note": "[36864,3072] in one call: the dispatch gap that bounds a single 28 MB launch is amortised"},
+        "fp8_x3_payload": {"quant_us": round(t_quant3 * 1e3, 2), "dequant_us": round(t_deq3 * 1e3, 2),
+                           "quant_gbs": round(3 * fp8_bytes / (t_quant3 * 1e-3) * 1e-9, 1),
+                           "dequant_gbs": round(3 * fp8_bytes / (t_deq3 * 1e-3) * 1e-9, 1),
+                           "quant_frac_of_hbm_peak": round(3 * fp8_bytes / (t_quant3 * 1e-3) * 1e-9 / PEAK_HBM_GBS, 4),
+                           "dequant_frac_of_hbm_peak": round(3 * fp8_bytes / (t_deq3 * 1e-3) * 1e-9 / PEAK_HBM_GBS, 4),
+                           "note": "[13824,3072] in one call: the Q, K and V payloads of one attention layer"},
         "fp8_a2a_layouts": {"pack_us": round(t_quant_map * 1e3, 2), "unpack_us": round(t_deq_map * 1e3, 2),
                             "pack_gbs": round(map_bytes / (t_quant_map * 1e-3) * 1e-9, 1),
                             "unpack_gbs": round(map_bytes / (t_deq_map * 1e-3) * 1e-9, 1),
