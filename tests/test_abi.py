@@ -113,3 +113,15 @@ def test_workspace_sizes_and_descriptor_checks():
     d.d = 100
     with pytest.raises(b.UspError):
         b.usp_ring_attn_workspace_bytes(d)
+
+
+def test_header_is_plain_c():
+    """include/usp.h is the boundary: it must compile as C99 and as C++ with nothing but the standard headers."""
+    import shutil
+    import subprocess
+    hdr = os.path.join(ROOT, "include", "usp.h")
+    for cc, std, lang in (("gcc", "-std=c99", "c"), ("g++", "-std=c++11", "c++")):
+        if shutil.which(cc) is None:
+            pytest.skip(cc + " not available")
+        r = subprocess.run([cc, std, "-Wall", "-Werror", "-fsyntax-only", "-x", lang, hdr], capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
