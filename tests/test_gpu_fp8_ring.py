@@ -210,3 +210,29 @@ def test_later_chunks_in_pinned_host_memory(fp8):
         o, l = P.usp_ring_attn_fwd(q, softmax_scale=scale, flags=flags, copy_stream=side, **away)
         torch.cuda.synchronize()
         assert torch.equal(o, ro) and torch.equal(l, rl), flags
+
+
+def test_two_rings_on_two_streams_at_once():
+    """An FP8 ring and a bf16 ring, each as one launch with its transfers inside, issued on two streams
+    without synchronising: every launch has its own counters and buffers in its own workspace, and its
+    copy work-groups are dispatched ahead of its own attention work-groups whatever else is running."""
+    P = _P()
+    wl = W.Workload("two_streams", 97, 1, 6, 128, 700, (512, 256, 320), "bf16")
+    inp, q, kq, ksc, vq, vsc, kx, vx = _fp8_ring(wl)
+    ks = [dev_bf16(k) for k in inp.k]; vs = [dev_bf16(v) for v in inp.v]
+    scale = float(inp.softmax_scale)
+    ref8 = _call(q, kq, ksc, vq, vsc, scale, FUSED)
+    refb = P.usp_ring_attn_fwd(q, ks, vs, softmax_scale=scale, flags=FUSED)
+    torch.cuda.synchronize()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    outs = []
+    for it in range(6):
+        with torch.cuda.stream(s1):
+            a = P.usp_ring_attn_fwd(q, kq, vq, k_scales=ksc, v_scales=vsc, softmax_scale=scale, flags=FUSED, compute_stream=s1)
+        with torch.cuda.stream(s2):
+            b = P.usp_ring_attn_fwd(q, ks, vs, softmax_scale=scale, flags=FUSED, compute_stream=s2)
+        outs.append((a, b))
+    torch.cuda.synchronize()
+    for it, (a, b) in enumerate(outs):
+        assert torch.equal(a[0], ref8[0]) and torch.equal(a[1], ref8[1]), it
+        assert torch.equal(b[0], refb[0]) and torch.equal(b[1], refb[1]), it
