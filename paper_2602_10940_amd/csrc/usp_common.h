@@ -139,6 +139,7 @@ struct AttnStep {
   int copy_wgs;
   CopySeg copy[4];
 };
+static_assert(sizeof(AttnStep) <= 4096, "AttnStep is passed by value as the kernels' only argument");
 // Copy work-groups appended to a launch of attn_wgs attention work-groups, slots_per_cu of which
 // fit on a CU: the CU slots the attention grid leaves free, as a multiple of 8 in [16, 64]
 // (one work-group moves about 50 GB/s).
