@@ -236,3 +236,26 @@ def test_two_rings_on_two_streams_at_once():
     for it, (a, b) in enumerate(outs):
         assert torch.equal(a[0], ref8[0]) and torch.equal(a[1], ref8[1]), it
         assert torch.equal(b[0], refb[0]) and torch.equal(b[1], refb[1]), it
+
+
+def test_fp8_ring_with_scales_and_masks_that_are_not_16_byte_aligned():
+    """The one-launch form reads scales 16 bytes and mask bytes 4 at a time; tensors that start at an odd
+    offset send the call to the per-chunk form, with the same result."""
+    P = _P()
+    wl = W.Workload("fp8_unaligned", 98, 2, 2, 128, 150, (128, 192), "bf16", masked_keys=(250, 320))
+    inp, q, kq, ksc, vq, vsc, kx, vx = _fp8_ring(wl)
+    km = [torch.from_numpy(m).to(DEV) for m in inp.key_mask]
+    scale = float(inp.softmax_scale)
+    ref = P.usp_ring_attn_fwd(q, kq, vq, k_scales=ksc, v_scales=vsc, key_mask=km, softmax_scale=scale, flags=STEPWISE)
+    def shifted(t, n):                     # the same values, n elements into a larger allocation
+        flat = torch.empty((t.numel() + n,), dtype=t.dtype, device=DEV)
+        flat[n:].copy_(t.reshape(-1))
+        return flat[n:].reshape(t.shape)
+    ksc1 = [shifted(t, 1) for t in ksc]
+    km1 = [shifted(t, 1) for t in km]
+    torch.cuda.synchronize()
+    assert ksc1[0].data_ptr() % 16 != 0 and km1[0].data_ptr() % 4 != 0
+    for kw in (dict(k_scales=ksc1, key_mask=km), dict(k_scales=ksc, key_mask=km1), dict(k_scales=ksc1, key_mask=km1)):
+        o, l = P.usp_ring_attn_fwd(q, kq, vq, v_scales=vsc, softmax_scale=scale, **kw)
+        torch.cuda.synchronize()
+        assert torch.equal(o, ref[0]) and torch.equal(l, ref[1])
