@@ -15,6 +15,8 @@
 //     operand (8 keys of one head-dim column per lane) comes from the LDS transposing read.
 //   * O and l are rescaled lazily: only when a row max has outgrown the exponent reference.
 //   * exp is taken in base 2 with scale * log2(e) folded into one FMA.
+#include <atomic>
+
 #include "usp_common.h"
 #include "prefetch_copy.h"
 
@@ -1132,13 +1134,25 @@ usp_status launch_attn_arrive_reset(int* arrive, hipStream_t st) {
 }
 
 namespace {
+// More than 64 KB of dynamic LDS has to be allowed per kernel, and the setting belongs to the device
+// that is current when it is made: once per (kernel, device ordinal below 64), every launch beyond.
+template <void (*kKernel)(AttnStep)>
+hipError_t allow_large_lds(int bytes) {
+  static std::atomic<uint64_t> done{0};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const bool tracked = dev >= 0 && dev < 64;
+  if (tracked && ((done.load(std::memory_order_acquire) >> dev) & 1u) != 0) return hipSuccess;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(kKernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess && tracked) done.fetch_or((uint64_t)1 << dev, std::memory_order_release);
+  return e;
+}
 template <bool kSplit, bool kExt, bool kMulti = false, bool kNoDead = false, bool kHalfD = false>
 usp_status launch_pp_d(const AttnStep& s, unsigned wgs, hipStream_t st) {
   static_assert(kLdsBytes >= (int)sizeof(SmemPPExt) && kLdsBytes <= 160 * 1024, "LDS plan");
   constexpr int lds = kLdsBytes;
-  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_pp_kernel<kSplit, kExt, kMulti, kNoDead, kHalfD>),
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-  USP_CHECK_HIP(attr);
+  USP_CHECK_HIP((allow_large_lds<attn_pp_kernel<kSplit, kExt, kMulti, kNoDead, kHalfD>>(lds)));
   hipLaunchKernelGGL((attn_pp_kernel<kSplit, kExt, kMulti, kNoDead, kHalfD>), dim3(wgs + s.copy_wgs), dim3(kThreads), lds, st, s);
   USP_CHECK_HIP(hipGetLastError());
   return USP_OK;
@@ -1220,17 +1234,13 @@ usp_status launch_attn_mfma(const AttnStep& step, hipStream_t st) {
     const int per = (items + kXcds - 1) / kXcds;
     const unsigned wgs_mixed = (unsigned)(kXcds * (per + s.mix_halves));
     s.copy_wgs = prefetch_wg_count(s, (int)wgs_mixed, 1);
-    constexpr int lds_e = kLdsBytes, lds_p = kLdsBytes;
+    constexpr int lds = kLdsBytes;
     if (ext) {
-      static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_pp_mixed_kernel<true>),
-                                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds_e);
-      USP_CHECK_HIP(attr);
-      hipLaunchKernelGGL((attn_pp_mixed_kernel<true>), dim3(wgs_mixed + s.copy_wgs), dim3(kThreads), lds_e, st, s);
+      USP_CHECK_HIP(allow_large_lds<attn_pp_mixed_kernel<true>>(lds));
+      hipLaunchKernelGGL((attn_pp_mixed_kernel<true>), dim3(wgs_mixed + s.copy_wgs), dim3(kThreads), lds, st, s);
     } else {
-      static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_pp_mixed_kernel<false>),
-                                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds_p);
-      USP_CHECK_HIP(attr);
-      hipLaunchKernelGGL((attn_pp_mixed_kernel<false>), dim3(wgs_mixed + s.copy_wgs), dim3(kThreads), lds_p, st, s);
+      USP_CHECK_HIP(allow_large_lds<attn_pp_mixed_kernel<false>>(lds));
+      hipLaunchKernelGGL((attn_pp_mixed_kernel<false>), dim3(wgs_mixed + s.copy_wgs), dim3(kThreads), lds, st, s);
     }
     USP_CHECK_HIP(hipGetLastError());
     return USP_OK;
