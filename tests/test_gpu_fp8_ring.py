@@ -259,3 +259,64 @@ def test_fp8_ring_with_scales_and_masks_that_are_not_16_byte_aligned():
         o, l = P.usp_ring_attn_fwd(q, kq, vq, v_scales=vsc, softmax_scale=scale, **kw)
         torch.cuda.synchronize()
         assert torch.equal(o, ref[0]) and torch.equal(l, ref[1])
+
+
+def test_two_host_threads_call_at_once():
+    """Two host threads issue rings on streams of their own at the same time (ctypes drops the GIL
+    around a call): the library's per-call state (error text, event pool, the d = 64 marker) is
+    per thread, and a refused call in one thread leaves the other's results and error text alone."""
+    import threading
+    P = _P()
+    wl = W.Workload("two_threads", 99, 1, 4, 128, 520, (256, 192, 128), "bf16")
+    inp, q, kq, ksc, vq, vsc, kx, vx = _fp8_ring(wl)
+    wl64 = W.Workload("two_threads_d64", 100, 1, 4, 64, 300, (128, 200), "bf16")
+    inp64 = W.make_attention_inputs(wl64)
+    q64 = dev_bf16(inp64.q); k64 = [dev_bf16(k) for k in inp64.k]; v64 = [dev_bf16(v) for v in inp64.v]
+    scale, scale64 = float(inp.softmax_scale), float(inp64.softmax_scale)
+    ref8 = _call(q, kq, ksc, vq, vsc, scale, 0)
+    ref64 = P.usp_ring_attn_fwd(q64, k64, v64, softmax_scale=scale64)
+    torch.cuda.synchronize()
+    results, errors = {}, []
+
+    def fp8_rings():
+        try:
+            st = torch.cuda.Stream()
+            outs = []
+            with torch.cuda.stream(st):
+                for it in range(20):
+                    outs.append(P.usp_ring_attn_fwd(q, kq, vq, k_scales=ksc, v_scales=vsc, softmax_scale=scale,
+                                                    flags=(0, STEPWISE, 1)[it % 3], compute_stream=st,
+                                                    copy_stream=torch.cuda.Stream() if it % 3 == 2 else None))
+            st.synchronize()
+            results["fp8"] = outs
+        except Exception as e:   # noqa: BLE001 (reported by the main thread)
+            errors.append(e)
+
+    def d64_rings_and_refusals():
+        try:
+            st = torch.cuda.Stream()
+            outs = []
+            with torch.cuda.stream(st):
+                for it in range(20):
+                    outs.append(P.usp_ring_attn_fwd(q64, k64, v64, softmax_scale=scale64, compute_stream=st))
+                    with pytest.raises(P.UspError, match="exclude"):
+                        P.usp_ring_attn_fwd(q64, k64, v64, softmax_scale=scale64, flags=WIDE | SPLIT, compute_stream=st)
+            st.synchronize()
+            results["d64"] = outs
+        except Exception as e:   # noqa: BLE001
+            errors.append(e)
+
+    threads = [threading.Thread(target=fp8_rings), threading.Thread(target=d64_rings_and_refusals)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=100)
+    assert not errors, errors
+    assert all(not t.is_alive() for t in threads)
+    torch.cuda.synchronize()
+    ref_step = _call(q, kq, ksc, vq, vsc, scale, STEPWISE)
+    for it, (o, l) in enumerate(results["fp8"]):
+        want = ref8 if it % 3 == 0 else ref_step        # (the side-stream form shares the per-chunk kernels)
+        assert torch.equal(o, want[0]) and torch.equal(l, want[1]), it
+    for it, (o, l) in enumerate(results["d64"]):
+        assert torch.equal(o, ref64[0]) and torch.equal(l, ref64[1]), it
