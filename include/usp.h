@@ -98,7 +98,7 @@ typedef enum {
  * [B,H,chunk_len[r],d] array" (the only way to describe dense chunks of unequal length).
  */
 typedef struct usp_attn_desc {
-  int32_t B, H, d;          /* d: a multiple of 8 up to 256.  bf16 Q with d = 128 runs on the matrix-core
+  int32_t B, H, d;          /* B*H at most 65535.  d: a multiple of 8 up to 256.  bf16 Q with d = 128 runs on the matrix-core
                                kernels, and so does bf16 Q with d = 64 (on copies of K and V padded to
                                d = 128 in the workspace); every other combination on a slower general kernel */
   int32_t Sq;               /* tokens of the local Q shard */

@@ -112,6 +112,9 @@ usp_status make_plan(const usp_attn_desc* d, Plan* p) {
   USP_CHECK_ARG(d != nullptr, "desc is NULL");
   USP_CHECK_ARG(d->B > 0 && d->H > 0 && d->Sq > 0, "B, H, Sq must be positive (B=%d H=%d Sq=%d)", d->B, d->H, d->Sq);
   USP_CHECK_ARG(d->d > 0 && d->d % 8 == 0 && d->d <= 256, "d must be a multiple of 8 in [8, 256] (got %d)", d->d);
+  // launch grids: (batch, head) pairs ride in a 16-bit grid dimension, query blocks times pairs in a 32-bit one
+  USP_CHECK_ARG((int64_t)d->B * d->H <= 65535, "B*H=%lld exceeds 65535", (long long)d->B * d->H);
+  USP_CHECK_ARG((int64_t)d->B * d->H * d->Sq < ((int64_t)1 << 37), "B*H*Sq=%lld is too large", (long long)d->B * d->H * d->Sq);
   USP_CHECK_ARG(d->n_chunks >= 1 && d->chunk_len != nullptr, "n_chunks must be >= 1 with chunk_len set");
   USP_CHECK_ARG(d->qo_dtype == USP_F32 || d->qo_dtype == USP_BF16, "qo_dtype must be USP_F32 or USP_BF16");
   USP_CHECK_ARG(d->kv_dtype == d->qo_dtype || d->kv_dtype == USP_FP8_E4M3FN,

@@ -125,3 +125,20 @@ def test_header_is_plain_c():
             pytest.skip(cc + " not available")
         r = subprocess.run([cc, std, "-Wall", "-Werror", "-fsyntax-only", "-x", lang, hdr], capture_output=True, text=True)
         assert r.returncode == 0, r.stderr
+
+
+def test_batch_times_heads_beyond_the_launch_grid_is_refused():
+    """(batch, head) pairs index a 16-bit grid dimension in some kernels: more than 65535 of them are
+    refused when the call is planned, not at launch."""
+    from paper_2602_10940_amd import binding as b
+    lens = (ctypes.c_int32 * 1)(64)
+    d = b.AttnDesc()
+    d.B, d.H, d.d, d.Sq, d.n_chunks = 4, 16384, 128, 64, 1
+    d.chunk_len = ctypes.cast(lens, ctypes.POINTER(ctypes.c_int32))
+    d.qo_dtype = d.kv_dtype = b.USP_BF16
+    for i, s in enumerate((16384 * 64 * 128, 64 * 128, 128)):
+        d.q_stride[i] = d.o_stride[i] = s
+    with pytest.raises(b.UspError, match="65535"):
+        b.usp_ring_attn_workspace_bytes(d)
+    d.H = 16383                                   # 65532 pairs: planned
+    assert b.usp_ring_attn_workspace_bytes(d) > 0

@@ -581,3 +581,37 @@ def test_long_sequence_65536_keys_sampled_rows(flags):
     rows = np.array([0, 1, 31, 32, 127, 128, 255, 256, 300, 511])
     ro, rl = _oracle(inp, rows)
     _assert_parity(o[:, :, rows, :], l[:, :, rows], ro, rl)
+
+
+@pytest.mark.parametrize("masked", [False, True])
+def test_largest_batch_times_heads_sampled_pairs(masked):
+    """65532 (batch, head) pairs, next to the most the launch grids take (65535): short shards, two
+    chunks, inputs drawn on the device from a seeded generator; sampled pairs against the oracle.  With
+    key masks the per-tile records are prepared by a launch whose second grid dimension is the pairs."""
+    P = _P()
+    B, H, Sq, lens, d = 3, 21844, 40, (128, 64), 128
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(4242)
+
+    def draw(*shape):
+        return torch.randn(shape, generator=gen, device=DEV, dtype=torch.float32).to(torch.bfloat16)
+
+    q = draw(B, H, Sq, d)
+    ks = [draw(B, H, L, d) for L in lens]
+    vs = [draw(B, H, L, d) for L in lens]
+    km = None
+    if masked:
+        km = [torch.ones((B, L), dtype=torch.uint8, device=DEV) for L in lens]
+        km[0][1, 100:] = 0; km[1][1, :22] = 0        # entry 1: keys 100..149 of the ring are dead
+        km[1][2, :] = 0                              # entry 2: the whole second chunk
+    scale = 1.0 / np.sqrt(d)
+    o, l = P.usp_ring_attn_fwd(q, ks, vs, key_mask=km, softmax_scale=float(np.float32(scale)))
+    torch.cuda.synchronize()
+    rng = np.random.Generator(np.random.PCG64(4243))
+    pairs = [(0, 0), (0, 1), (1, 7), (1, H - 1), (2, 0), (2, H - 1)] + \
+            [(int(rng.integers(0, B)), int(rng.integers(0, H))) for _ in range(10)]
+    for b, h in pairs:
+        sl = lambda t: host_f64(t[b:b + 1, h:h + 1])
+        mk = None if km is None else [m[b:b + 1].cpu().numpy() for m in km]
+        ro, rl = orc.ring_attention(sl(q), [sl(k) for k in ks], [sl(v) for v in vs], float(np.float32(scale)), mk)
+        _assert_parity(sl(o), host_f64(l[b:b + 1, h:h + 1]), ro, rl)
