@@ -1,7 +1,7 @@
 """Seeded random sweep of usp_ring_attn_fwd against the fp64 oracle: head dimension 64 / 128, batch,
 heads, Q shard length, 1-5 chunks (whole tiles or ragged, empty chunks included), bf16 or FP8 K/V,
-key masks (shared or per batch entry), x20 outliers, and every schedule / kernel flag.  Small shapes;
-each case is printed before it runs."""
+key masks (shared or per batch entry), x20 outliers, every schedule / kernel flag, and (one seed) the
+softmax scale at 0.25 to 6 times 1/sqrt(d).  Small shapes; each case is printed before it runs."""
 import numpy as np
 import pytest
 import torch
@@ -16,7 +16,7 @@ pytestmark = pytest.mark.gpu
 FLAGS = [0, 64, 16, 16 | 64, 1, 2, 4, 8, 32, 16 | 8, 16 | 4, 2 | 16, 64 | 8, 64 | 4]
 
 
-def _case(rng, case):
+def _case(rng, case, vary_scale=False):
     d = int(rng.choice([128, 128, 64]))
     B = int(rng.choice([1, 1, 2, 3])); H = int(rng.integers(1, 5))
     Sq = int(rng.choice([1, 31, 64, 100, 128, 130, 200, 256, 300, 520, 700]))
@@ -35,17 +35,18 @@ def _case(rng, case):
     own_masks = bool(rng.random() < 0.5)
     wl = W.Workload("sweep", 1000 + case, B, H, d, Sq, lens, "bf16", masked_keys=(lo, hi) if masked else (0, 0),
                     outlier_frac=0.01 if outliers else 0.0, outlier_mul=20.0)
-    return wl, fp8, flags, own_masks
+    scale_mul = float(rng.choice([0.25, 1.0, 2.5, 6.0])) if vary_scale else 1.0
+    return wl, fp8, flags, own_masks, scale_mul
 
 
-@pytest.mark.parametrize("seed", [7, 10, 13])
-def test_random_sweep(seed):
+@pytest.mark.parametrize("seed,vary_scale", [(7, False), (10, False), (13, False), (17, True)])
+def test_random_sweep(seed, vary_scale):
     import paper_2602_10940_amd as P
     rng = np.random.Generator(np.random.PCG64(seed))
     for case in range(40):
-        wl, fp8, flags, own_masks = _case(rng, case)
+        wl, fp8, flags, own_masks, scale_mul = _case(rng, case, vary_scale)
         print("case", seed, case, dict(d=wl.d, B=wl.B, H=wl.H, Sq=wl.Sq, lens=wl.chunk_len, fp8=fp8, masked=wl.masked_keys,
-                                       flags=flags), flush=True)
+                                       flags=flags, scale_mul=scale_mul), flush=True)
         inp = W.make_attention_inputs(wl)
         if inp.key_mask is not None and own_masks and wl.B > 1:     # entry 0 keeps every key
             for m in inp.key_mask:
@@ -53,7 +54,7 @@ def test_random_sweep(seed):
         q = dev_bf16(inp.q)
         km = None if inp.key_mask is None else [torch.from_numpy(m).to(DEV) for m in inp.key_mask]
         side = torch.cuda.Stream() if flags & 1 else None
-        scale = float(inp.softmax_scale)
+        scale = float(np.float32(float(inp.softmax_scale) * scale_mul))
         if fp8:
             kq, ksc, vq, vsc, kx, vx = [], [], [], [], [], []
             for k, v in zip(inp.k, inp.v):
