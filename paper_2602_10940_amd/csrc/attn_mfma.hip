@@ -729,6 +729,12 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
   // such move re-arms the counter.  Scores with heavy tails then cost one maximum pass per tile
   // instead of a second round of exponentials on most tiles; ordinary scores never arm it.
   constexpr float kCertifiedSum = 1152921504606846976.0f;   // 2^60
+  // A reference that moves is set this far ABOVE the maximum that moved it: the largest P is then 2^-32
+  // instead of 1, which fp32 sums and bf16 P carry as well (every P, l and O~ is scaled by the same
+  // power of two), and a later score has to exceed the maximum seen so far by 2^92, not 2^60, before
+  // the reference has to move again.  With heavy-tailed scores (x20 outliers in Q and K) that is the
+  // difference between a second round of exponentials on many tiles and on few.
+  constexpr float kRefMargin = 32.0f;
   constexpr int kMaxFirstTiles = 8;
   int max_first = 0;
   // "some key of the tile is dead", read from the tile's record in global memory through the scalar
@@ -779,8 +785,9 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
       const float tmax = tile_max(xs);
       const bool jump = tmax > m + 8.0f;
       if (__builtin_amdgcn_ballot_w64(jump) != 0ull) {
-        const float alpha = jump ? __builtin_amdgcn_exp2f(m - tmax) : 1.0f;   // m = -inf gives 0
-        m = jump ? tmax : m;
+        const float m_new = tmax + kRefMargin;
+        const float alpha = jump ? __builtin_amdgcn_exp2f(m - m_new) : 1.0f;   // m = -inf gives 0
+        m = jump ? m_new : m;
         lsum *= alpha;
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
@@ -834,7 +841,7 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
       // maximum first on the next tiles instead of paying for the exponentials twice
       if (__builtin_amdgcn_ballot_w64(m != -INFINITY) != 0ull) max_first = kMaxFirstTiles;
       const float tmax = tile_max(xs);
-      const float m_new = fmaxf(m, tmax);
+      const float m_new = tmax > m ? tmax + kRefMargin : m;
       // m = -inf (first live tile) gives alpha 0; no live key so far: nothing to rescale, P = 0
       const float alpha = m_new == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(m - m_new);
       m = m_new;
