@@ -46,10 +46,24 @@ __device__ __forceinline__ void prefetch_copy(const AttnStep& s, int wg, int tid
 }
 
 // The transfers of a whole ring inside one launch: work-group wg of s.copy_wgs copies its share of
-// chunk c = 1, 2, .. and then counts itself on s.arrive[c].  The stores carry device scope (they are
-// written through to where every CU's loads find them; a fence would write back and invalidate the
-// whole L2 under the attention work-groups), each thread waits for its own stores, the
-// work-group barrier collects the threads, and one thread publishes the count.
+// chunk c = 1, 2, .. and then counts itself on s.arrive[c].  The stores carry device scope (written
+// through towards memory, where the loads of every XCD find them), each thread waits for its own
+// stores, the work-group barrier collects the threads, and the first wave then makes a device-scope
+// release (on a chip with one L2 per XCD: the write-back of that L2, awaited) before one of its threads
+// publishes the count: an acknowledged write-through store alone proved not to be enough when the
+// reader sits waiting for the count and loads at once (rare stale lines on short chunks).  One release
+// per work-group and chunk, not one per wave.  The readers make no acquire of their own (it would
+// invalidate the L2 under every other attention work-group): nothing reads a staging buffer or its
+// records before their chunk's count is complete, and the launch starts with invalid caches, so no
+// cache on the reading side can hold an older copy of those lines.
+__device__ __forceinline__ void publish_chunk(int* counter, int tid) {
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this thread's stores have been acknowledged
+  __syncthreads();
+  if (tid < 64) {                       // (the first wave)
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    if (tid == 0) __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
 __device__ __forceinline__ void store16_device_scope(uint4* p, const uint4& v) {
   typedef unsigned int vec4u __attribute__((ext_vector_type(4)));
   const vec4u x = {v.x, v.y, v.z, v.w};
@@ -136,9 +150,7 @@ __device__ __forceinline__ void fp8_chunk_prepare(const AttnStep& s, int c, int6
 __device__ __forceinline__ void stream_chunks_fp8(const AttnStep& s, int wg, int tid, int nthr) {
   for (int c = 1; c < s.n_multi; ++c) {
     fp8_chunk_prepare<true>(s, c, (int64_t)wg * nthr + tid, (int64_t)s.copy_wgs * nthr);
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this thread's stores have been acknowledged
-    __syncthreads();
-    if (tid == 0) __hip_atomic_fetch_add(s.arrive + c, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    publish_chunk(s.arrive + c, tid);
   }
 }
 __device__ __forceinline__ void stream_chunks(const AttnStep& s, int wg, int tid, int nthr) {
@@ -157,9 +169,7 @@ __device__ __forceinline__ void stream_chunks(const AttnStep& s, int wg, int tid
       }
       for (; i < n; i += stride) store16_device_scope(d4 + i, s4[i]);
     }
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this thread's stores have been acknowledged
-    __syncthreads();
-    if (tid == 0) __hip_atomic_fetch_add(s.arrive + c, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    publish_chunk(s.arrive + c, tid);
   }
 }
 
