@@ -326,6 +326,27 @@ __global__ __launch_bounds__(64) void attn_ext_prepare_kernel(AttnStep s, float*
   }
 }
 
+// Records of a launch over several bf16 chunks of which some have a key mask: one work-group of 64
+// threads per (tile of the ring's tile stream, batch*head), laid out [B*H][tiles in ring order] like
+// the records the FP8 form writes while it decodes.  Masks are inputs of the call, not part of what
+// the ring transfers, so the records of every chunk can be written before the attention launch.
+__global__ __launch_bounds__(64) void attn_multi_records_kernel(AttnStep s) {
+  int tile = blockIdx.x;
+  const int bh = blockIdx.y, t = threadIdx.x;
+  int nt_total = 0;
+  for (int c = 0; c < s.n_multi; ++c) nt_total += s.chunk[c].Sc / kTile;
+  int c = 0;
+  while (tile >= s.chunk[c].Sc / kTile) { tile -= s.chunk[c].Sc / kTile; ++c; }   // (the grid has nt_total tiles)
+  const AttnStep::Chunk& ch = s.chunk[c];
+  const int key = tile * kTile + t;
+  const bool keep = ch.mask_src == nullptr || ch.mask_src[(int64_t)(bh / s.H) * ch.Sc + key] != 0;
+  float* rec = s.ext + ((int64_t)bh * nt_total + blockIdx.x) * (kExtTileB / 4);
+  rec[t] = keep ? s.scale * 1.44269504088896340736f : 0.0f;
+  rec[64 + t] = keep ? 0.0f : -INFINITY;
+  rec[128 + t] = __builtin_amdgcn_ballot_w64(!keep) != 0ull ? 1.0f : 0.0f;
+  rec[192 + t] = 0.0f;
+}
+
 // Wait of an attention work-group for a chunk that the copy work-groups of the same launch are still
 // writing: polls the chunk's counter with device-scope loads until it reaches `need`.  The copy
 // work-groups are dispatched before every attention work-group and wait for nothing, so the count
@@ -1050,11 +1071,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_pp_kernel(AttnStep s) {
   int lead = 0;
   if (kMulti && s.arrive != nullptr) {   // the whole ring's transfers ride in this launch, in its first work-groups
     if ((int)blockIdx.x < s.copy_wgs) {
-      if (kExt) {
-        if (s.multi_fp8) stream_chunks_fp8(s, blockIdx.x, threadIdx.x, kThreads);
-      } else {
-        stream_chunks(s, blockIdx.x, threadIdx.x, kThreads);
-      }
+      if (kExt && s.multi_fp8) stream_chunks_fp8(s, blockIdx.x, threadIdx.x, kThreads);
+      else stream_chunks(s, blockIdx.x, threadIdx.x, kThreads);   // bf16 chunks (their records, if any, were written before the launch)
       return;
     }
     lead = s.copy_wgs;
@@ -1134,6 +1152,24 @@ usp_status launch_attn_fp8_chunk_prepare(const AttnStep& s, int c, bool reset_ar
   return USP_OK;
 }
 
+usp_status launch_attn_multi_records(const AttnStep& s, hipStream_t st) {
+  int nt_total = 0;
+  for (int c = 0; c < s.n_multi; ++c) {
+    if (s.chunk[c].Sc <= 0 || s.chunk[c].Sc % kTile != 0) {
+      set_error("records of a launch over several chunks need chunk lengths that are positive multiples of %d", kTile);
+      return USP_ERR_INVALID_ARG;
+    }
+    nt_total += s.chunk[c].Sc / kTile;
+  }
+  if (s.n_multi <= 0 || s.n_multi > AttnStep::kMaxMulti || !s.ext || s.multi_fp8) {
+    set_error("records of a launch over several bf16 chunks need the chunks and room for the records");
+    return USP_ERR_INVALID_ARG;
+  }
+  hipLaunchKernelGGL(attn_multi_records_kernel, dim3((unsigned)nt_total, (unsigned)(s.B * s.H)), dim3(64), 0, st, s);
+  USP_CHECK_HIP(hipGetLastError());
+  return USP_OK;
+}
+
 usp_status launch_attn_arrive_reset(int* arrive, hipStream_t st) {
   hipLaunchKernelGGL(attn_arrive_reset_kernel, dim3(1), dim3(64), 0, st, arrive);
   USP_CHECK_HIP(hipGetLastError());
@@ -1183,6 +1219,10 @@ usp_status launch_attn_mfma(const AttnStep& step, hipStream_t st) {
       set_error("a launch over several FP8 chunks needs arrival counters and per-tile records");
       return USP_ERR_INVALID_ARG;
     }
+    if (!s.multi_fp8 && s.multi_masked && !s.ext) {
+      set_error("a launch over several chunks with key masks needs their per-tile records");
+      return USP_ERR_INVALID_ARG;
+    }
     for (int c = 0; c < s.n_multi; ++c)
       if (s.chunk[c].Sc <= 0 || s.chunk[c].Sc % kTile != 0 || !s.chunk[c].k || !s.chunk[c].v) {
         set_error("a launch over several chunks needs chunk lengths that are positive multiples of %d", kTile);
@@ -1213,6 +1253,8 @@ usp_status launch_attn_mfma(const AttnStep& step, hipStream_t st) {
     if (s.multi_fp8 && s.multi_masked)
       return split ? launch_pp<true, true, true, false>(s, wgs, st) : launch_pp<false, true, true, false>(s, wgs, st);
     if (s.multi_fp8) return split ? launch_pp<true, true, true, true>(s, wgs, st) : launch_pp<false, true, true, true>(s, wgs, st);
+    if (s.multi_masked)   // bf16 chunks, records written by launch_attn_multi_records
+      return split ? launch_pp<true, true, true, false>(s, wgs, st) : launch_pp<false, true, true, false>(s, wgs, st);
     if (split) return launch_pp<true, false, true>(s, wgs, st);
     return launch_pp<false, false, true>(s, wgs, st);
   }

@@ -71,6 +71,8 @@ struct Plan {
   bool ring8 = false;                   // FP8 chunks decoded inside one launch over the whole ring
   size_t off_ring8 = 0, off_ext8 = 0;   // bf16 K | V of every live chunk; records of all their tiles
   bool ext = false;
+  bool multi_rec = false;               // room for the records of a one-launch ring over bf16 chunks with key masks
+  size_t off_multi_rec = 0;
   // bf16 with d = 64: zero-padded to d = 128 copies in the workspace (Q, O, K | V of every chunk),
   // then the d = 128 path on those with a workspace of its own behind them
   bool pad64 = false;
@@ -252,6 +254,21 @@ usp_status make_plan(const usp_attn_desc* d, Plan* p) {
       p->off_ext8 = off; off += align_up((size_t)d->B * d->H * tiles * 1024);
       p->off_arrive = off; off += align_up(AttnStep::kMaxMulti * sizeof(int));
     }
+  }
+  // bf16 chunks that one launch could take (see usp_ring_attn_fwd): should some of them come with a key
+  // mask (not known here), that launch reads per-tile records, 1 KB per 64 keys of a head
+  p->multi_rec = p->mfma && !p->fp8 && (!p->dbuf || p->ring1) && !p->unfused && p->W > 1 && !(d->flags & USP_ATTN_STEPWISE);
+  if (p->multi_rec) {
+    int live = 0;
+    size_t tiles = 0;
+    for (int r = 0; r < p->W; ++r) {
+      if (d->chunk_len[r] == 0) continue;
+      if (d->chunk_len[r] % 64 != 0) p->multi_rec = false;
+      tiles += (size_t)d->chunk_len[r] / 64;
+      ++live;
+    }
+    if (live < 2 || live > AttnStep::kMaxMulti) p->multi_rec = false;
+    if (p->multi_rec) { p->off_multi_rec = off; off += align_up((size_t)d->B * d->H * tiles * 1024); }
   }
   p->total = off;
   p->valid = true;
@@ -487,7 +504,8 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
   // that asks for the transfers inside the launches takes the one launch at any size.
   const int64_t q_blocks = (int64_t)desc->B * desc->H * ((desc->Sq + 255) / 256);
   const bool short_steps = q_blocks <= 256 || p.fused_pf;
-  // Every chunk resident and plain, merge fused: one launch over the whole ring.
+  // Every chunk resident, whole tiles, merge fused: one launch over the whole ring (chunks with a key
+  // mask through per-tile records written just before it).
   {
     bool one_launch = p.mfma && !p.fp8 && (!p.dbuf || p.ring1) && !p.unfused && p.W > 1 && !(desc->flags & USP_ATTN_STEPWISE) &&
                       short_steps;
@@ -495,10 +513,10 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
     for (int r = 0; one_launch && r < p.W; ++r) {
       const int len = desc->chunk_len[r];
       if (len == 0) continue;
-      if (len % 64 != 0 || (key_mask && key_mask[r])) one_launch = false;
+      if (len % 64 != 0) one_launch = false;
       ++n_live;
     }
-    if (one_launch && n_live >= 2 && n_live <= AttnStep::kMaxMulti) {
+    if (one_launch && n_live >= 2 && n_live <= AttnStep::kMaxMulti && p.multi_rec) {
       AttnStep a;
       memset(&a, 0, sizeof(a));
       a.B = desc->B; a.H = desc->H; a.d = d; a.Sq = desc->Sq;
@@ -522,12 +540,17 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
             c.k_src = k_chunks[r]; c.v_src = v_chunks[r]; c.bytes = (int64_t)bytes;
             c.k = ws + stage; c.v = ws + stage + align_up(bytes);
           }
+          if (key_mask && key_mask[r]) { c.mask_src = key_mask[r]; a.multi_masked = 1; }
         }
         if (r >= 1) stage += 2 * align_up(bytes);
       }
       if (transfers) {
         a.arrive = (int*)(ws + p.off_arrive);
         if ((st = launch_attn_arrive_reset(a.arrive, cs)) != USP_OK) return st;
+      }
+      if (a.multi_masked) {   // some chunk has a key mask: the launch reads per-tile records
+        a.ext = (float*)(ws + p.off_multi_rec);
+        if ((st = launch_attn_multi_records(a, cs)) != USP_OK) return st;
       }
       return launch_attn_mfma(a, cs);
     }

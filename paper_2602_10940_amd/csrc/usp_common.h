@@ -123,12 +123,13 @@ struct AttnStep {
     const void* k; const void* v; int64_t ks0, ks1; int Sc;
     const void* k_src; const void* v_src; int64_t bytes;
     const float* k_scale_src; const float* v_scale_src;
-    const uint8_t* mask_src;   // multi_fp8: key mask [B,Sc] of the chunk (nonzero = key takes part), or null
+    const uint8_t* mask_src;   // key mask [B,Sc] of the chunk (nonzero = key takes part), or null
   };
   static constexpr int kMaxMulti = 16;
   int n_multi;
   int multi_fp8;
-  int multi_masked;          // multi_fp8: some chunk has a key mask (the records may then flag dead keys)
+  int multi_masked;          // some chunk has a key mask (Chunk::mask_src): the records may flag dead keys.  With bf16
+                             // chunks (no multi_fp8) the records are those of launch_attn_multi_records
   int* arrive;               // [kMaxMulti] counters, zero when the launch starts; or null
   Chunk chunk[kMaxMulti];
   // Prefetch carried by this launch (Algorithm 2, the transfer of the next chunk): the last
@@ -158,6 +159,9 @@ bool attn_mfma_needs_ext(const AttnStep& s);
 size_t attn_mfma_ext_bytes(int B, int H, int Sc);
 usp_status launch_attn_ext_prepare(const AttnStep& s, hipStream_t st);
 usp_status launch_attn_arrive_reset(int* arrive, hipStream_t st);
+// per-tile records (AttnStep::ext, [B*H][tiles in ring order]) of a step over several bf16 chunks some of
+// which have a key mask (Chunk::mask_src, multi_masked); precedes the attention launch on the stream
+usp_status launch_attn_multi_records(const AttnStep& s, hipStream_t st);
 // [B,H,S,64] (bf16: elt_bytes 2, E4M3 codes: 1) by (B,H,token) strides in elements <-> dense [B,H,S,128]
 // with zero columns 64..127
 usp_status launch_pad64(const void* src, void* dst, int B, int H, int S, const int64_t stride[3], int elt_bytes,

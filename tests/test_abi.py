@@ -70,7 +70,11 @@ def test_workspace_sizes_and_descriptor_checks():
     # bf16 d=128: per-(head, 64-key tile) records of 1 KB for masks / scales / ragged chunks, plus
     # one live-tile count per batch entry (256-byte granularity)
     recs = 24 * (1152 // 64) * 1024 + 256
-    assert b.usp_ring_attn_workspace_bytes(d) == rows * 128 * 4 + recs     # fp32 carried O
+    # one launch over the four chunks: records of all 4 * 18 tiles per head, should a chunk come with a mask
+    ring_recs = 24 * 72 * 1024
+    assert b.usp_ring_attn_workspace_bytes(d) == rows * 128 * 4 + recs + ring_recs     # fp32 carried O
+    d.flags = b.USP_ATTN_STEPWISE
+    assert b.usp_ring_attn_workspace_bytes(d) == rows * 128 * 4 + recs
     d.flags = b.USP_ATTN_DOUBLE_BUFFER
     assert b.usp_ring_attn_workspace_bytes(d) == rows * 128 * 4 + 4 * rows * 128 * 2 + recs
     d.flags = b.USP_ATTN_FUSED_PREFETCH | b.USP_ATTN_STEPWISE             # same two staging buffers
@@ -78,7 +82,7 @@ def test_workspace_sizes_and_descriptor_checks():
     # transfers inside one launch over the whole ring: a buffer (K | V) for each of the 3 later chunks
     # on top, and the arrival counters
     d.flags = b.USP_ATTN_FUSED_PREFETCH
-    assert b.usp_ring_attn_workspace_bytes(d) == rows * 128 * 4 + 4 * rows * 128 * 2 + recs + 3 * 2 * rows * 128 * 2 + 256
+    assert b.usp_ring_attn_workspace_bytes(d) == rows * 128 * 4 + 4 * rows * 128 * 2 + recs + 3 * 2 * rows * 128 * 2 + 256 + ring_recs
     for both in (b.USP_ATTN_FUSED_PREFETCH | b.USP_ATTN_DOUBLE_BUFFER,
                  b.USP_ATTN_KERNEL_WIDE | b.USP_ATTN_KERNEL_SPLIT, b.USP_ATTN_KERNEL_SPLIT | b.USP_ATTN_KERNEL_MIXED):
         d.flags = both

@@ -615,3 +615,54 @@ def test_largest_batch_times_heads_sampled_pairs(masked):
         mk = None if km is None else [m[b:b + 1].cpu().numpy() for m in km]
         ro, rl = orc.ring_attention(sl(q), [sl(k) for k in ks], [sl(v) for v in vs], float(np.float32(scale)), mk)
         _assert_parity(sl(o), host_f64(l[b:b + 1, h:h + 1]), ro, rl)
+
+
+@pytest.mark.parametrize("kernel", ["auto", "wide", "split"])
+@pytest.mark.parametrize("B,Sq,lens,masked", [
+    (1, 200, (128, 64, 192), (100, 250)),          # dead keys across a chunk boundary
+    (2, 300, (64, 128, 64, 64), (64, 192)),        # one chunk entirely dead
+    (3, 130, (256, 128), (0, 70)),                 # the ring starts with dead keys
+    (1, 257, (128, 0, 192, 64), (383, 384)),       # a single dead key, the last one; an empty chunk
+])
+def test_one_launch_over_bf16_chunks_with_key_masks(B, Sq, lens, masked, kernel):
+    """bf16 chunks of whole tiles with key masks are covered by one launch too, through per-tile records
+    written just before it: parity, agreement with the launch-per-chunk form, and the same with the
+    transfers inside the launch (poisoned workspace)."""
+    P = _P()
+    wl = W.Workload("multi_masked", 47, B, 3, 128, Sq, tuple(lens), "bf16", masked_keys=masked)
+    inp = W.make_attention_inputs(wl)
+    if B == 3:                                     # a different mask per batch entry
+        for m in inp.key_mask:
+            m[0, :] = 1
+        inp.key_mask[0][2, ::3] = 0
+    ro, rl = _oracle(inp)
+    flags = _KERNEL_FLAG[kernel]
+    o, l = _run(inp, flags=flags)
+    _assert_parity(o, l, ro, rl)
+    os_, ls_ = _run(inp, flags=flags | 64)
+    _assert_parity(os_, ls_, ro, rl)
+    assert np.abs(o - os_).max() <= 2.0 ** -6 and np.abs(l - ls_).max() <= 1e-5
+    q = dev_bf16(inp.q); ks = [dev_bf16(k) for k in inp.k]; vs = [dev_bf16(v) for v in inp.v]
+    km = [torch.from_numpy(m).to(DEV) for m in inp.key_mask]
+    out = torch.empty_like(q)
+    desc = P.make_attn_desc(q, ks, out, float(inp.softmax_scale), flags | 16)
+    ws = torch.full((P.usp_ring_attn_workspace_bytes(desc),), 0xFF, dtype=torch.uint8, device=DEV)
+    for _ in range(2):
+        of, lf = P.usp_ring_attn_fwd(q, ks, vs, key_mask=km, softmax_scale=float(inp.softmax_scale), flags=flags | 16,
+                                     out=out, workspace=ws)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host_f64(of), o)
+    np.testing.assert_array_equal(host_f64(lf), l)
+
+
+def test_one_launch_masked_ring_with_every_key_of_an_entry_dead():
+    """A batch entry whose keys are all dead: lse = -inf and O = 0 for its rows, the other entry unaffected."""
+    wl = W.Workload("multi_masked_all", 48, 2, 2, 128, 140, (128, 64), "bf16", masked_keys=(0, 0))
+    inp = W.make_attention_inputs(wl)
+    inp.key_mask = [np.ones((2, L), dtype=np.uint8) for L in wl.chunk_len]
+    for m in inp.key_mask:
+        m[1, :] = 0
+    ro, rl = _oracle(inp)
+    o, l = _run(inp)
+    _assert_parity(o, l, ro, rl)
+    assert np.all(np.isneginf(l[1])) and np.all(o[1] == 0.0) and np.all(np.isfinite(l[0]))
