@@ -46,28 +46,28 @@ __device__ __forceinline__ void prefetch_copy(const AttnStep& s, int wg, int tid
 }
 
 // The transfers of a whole ring inside one launch: work-group wg of s.copy_wgs copies its share of
-// chunk c = 1, 2, .. and then counts itself on s.arrive[c].  The stores carry device scope (written
-// through towards memory, where the loads of every XCD find them), each thread waits for its own
-// stores, the work-group barrier collects the threads, and the first wave then makes a device-scope
-// release (on a chip with one L2 per XCD: the write-back of that L2, awaited) before one of its threads
-// publishes the count: an acknowledged write-through store alone proved not to be enough when the
-// reader sits waiting for the count and loads at once (rare stale lines on short chunks).  One release
-// per work-group and chunk, not one per wave.  The readers make no acquire of their own (it would
-// invalidate the L2 under every other attention work-group): nothing reads a staging buffer or its
-// records before their chunk's count is complete, and the launch starts with invalid caches, so no
-// cache on the reading side can hold an older copy of those lines.
+// chunk c = 1, 2, .. and then counts itself on s.arrive[c].  The stores carry device scope (they are
+// written through to where every XCD's loads find them; a fence would write back and invalidate the
+// whole L2 under the attention work-groups), each thread waits until its own stores have been
+// acknowledged, the work-group barrier collects the threads, and one thread publishes the count.
+// The readers make no acquire of their own either: nothing reads a staging buffer or its records
+// before their chunk's count is complete, and the launch starts with invalid caches, so no cache on
+// the reading side can hold an older copy of those lines.
 __device__ __forceinline__ void publish_chunk(int* counter, int tid) {
   __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this thread's stores have been acknowledged
   __syncthreads();
-  if (tid < 64) {                       // (the first wave)
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-    if (tid == 0) __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  }
+  if (tid == 0) __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// A 16-byte store with device scope.  The instruction sits in inline asm (no builtin sets the scope
+// bits of a plain store), where the compiler's hazard recogniser cannot see that it is a store: on
+// gfx9 a store of more than 8 bytes reads its data registers late, and a VALU instruction that
+// overwrites them within the next two wait states can change what is stored (seen as rare wrong
+// words in some lanes when the next store's data was computed into the same registers).  The two
+// wait states therefore ride inside the asm statement.
 __device__ __forceinline__ void store16_device_scope(uint4* p, const uint4& v) {
   typedef unsigned int vec4u __attribute__((ext_vector_type(4)));
   const vec4u x = {v.x, v.y, v.z, v.w};
-  asm volatile("global_store_dwordx4 %0, %1, off sc1" :: "v"(p), "v"(x) : "memory");
+  asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" :: "v"(p), "v"(x) : "memory");
 }
 // Algorithm 1 line 4 for chunk c of a launch over several FP8 chunks: unit `first`, first + stride, ..
 // of the chunk (16 codes of K and of V each; then 4 keys of the records).  The arithmetic is the

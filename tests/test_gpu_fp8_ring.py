@@ -320,3 +320,38 @@ def test_two_host_threads_call_at_once():
         assert torch.equal(o, want[0]) and torch.equal(l, want[1]), it
     for it, (o, l) in enumerate(results["d64"]):
         assert torch.equal(o, ref64[0]) and torch.equal(l, ref64[1]), it
+
+
+def test_masked_fp8_ring_many_calls_through_one_workspace():
+    """Three rings of one shape (short chunks, three batch entries, key masks) take turns through one
+    workspace, 3000 calls back to back: every result must equal its ring's own reference bit for bit.
+    (The copy work-groups' 16-byte device-scope stores are inline asm; without wait states behind them
+    the instruction that computed the next store's data could change the one in flight, which showed
+    as wrong per-key factors in one call out of a few hundred.)"""
+    P = _P()
+    rings = []
+    for seed in (200, 201, 202):
+        wl = W.Workload("fp8_many", seed, 3, 2, 128, 130, (128, 256, 128, 128), "bf16", masked_keys=(441, 583))
+        inp, q, kq, ksc, vq, vsc, kx, vx = _fp8_ring(wl)
+        km = [torch.from_numpy(m).to(DEV) for m in inp.key_mask]
+        rings.append(dict(q=q, k_chunks=kq, v_chunks=vq, k_scales=ksc, v_scales=vsc, key_mask=km,
+                          softmax_scale=float(inp.softmax_scale)))
+    refs = []
+    for r in rings:
+        a = P.usp_ring_attn_fwd(**r)
+        b = P.usp_ring_attn_fwd(flags=STEPWISE, **r)
+        torch.cuda.synchronize()
+        assert (a[0].float() - b[0].float()).abs().max().item() <= 2.0 ** -5 and (a[1] - b[1]).abs().max().item() <= 1e-4
+        refs.append(a)
+    desc = P.make_attn_desc(rings[0]["q"], rings[0]["k_chunks"], torch.empty_like(rings[0]["q"]), rings[0]["softmax_scale"], 0)
+    ws = torch.full((P.usp_ring_attn_workspace_bytes(desc),), 0xFF, dtype=torch.uint8, device=DEV)
+    rng = np.random.Generator(np.random.PCG64(9))
+    bad = 0
+    for batch in range(60):
+        outs = []
+        for _ in range(50):
+            i = int(rng.integers(0, 3))
+            outs.append((i, P.usp_ring_attn_fwd(workspace=ws, **rings[i])))
+        torch.cuda.synchronize()
+        bad += sum(1 for i, (o, l) in outs if not (torch.equal(o, refs[i][0]) and torch.equal(l, refs[i][1])))
+    assert bad == 0, bad
