@@ -52,7 +52,7 @@ typedef enum {
                                       work-groups of the attention launches on compute_stream;
                                       copy_stream is ignored.  Excludes USP_ATTN_DOUBLE_BUFFER.  Two forms:
                                       - one launch per chunk (always with USP_ATTN_STEPWISE, a chunk length
-                                        that is not a multiple of 64, or a key mask on bf16 chunks): step
+                                        that is not a multiple of 64): step
                                         r's launch carries the transfer of chunk r+1 into the idle one
                                         of two internal buffers, in work-groups that occupy the CUs the
                                         attention grid leaves free.  Same buffers and results as
@@ -76,7 +76,7 @@ typedef enum {
                                      64-key tiles and combine their partial results at the end */
 #define USP_ATTN_STEPWISE 64u     /* one attention launch per chunk even where one launch could cover the
                                      whole ring: without USP_ATTN_DOUBLE_BUFFER and USP_ATTN_UNFUSED_MERGE,
-                                     bf16 or FP8 chunks (bf16 Q, d = 128) that need no mask and whose
+                                     bf16 or FP8 chunks (bf16 Q, d = 128), with or without key masks, whose
                                      lengths are multiples of 64 (2 to 16 of them non-empty) are otherwise
                                      taken as one stream of key tiles by a single launch (when the Q
                                      shard's 256-query blocks fit one round of work-groups on the chip,
