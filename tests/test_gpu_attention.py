@@ -218,21 +218,24 @@ def test_ring4_fused_unfused_and_double_buffered_agree():
     np.testing.assert_array_equal(lf2, lu)
 
 
-@pytest.mark.parametrize("flags,lens", [(0, (192, 64, 100, 128)), (16, (192, 64, 100, 128)), (2, (192, 64, 100, 128)),
-                                        (0, (192, 64, 128, 128)), (16, (192, 64, 128, 128))])
-def test_ring_call_replays_from_a_hip_graph(flags, lens):
+@pytest.mark.parametrize("flags,lens,masked", [(0, (192, 64, 100, 128), None), (16, (192, 64, 100, 128), None),
+                                               (2, (192, 64, 100, 128), None), (0, (192, 64, 128, 128), None),
+                                               (16, (192, 64, 128, 128), None),
+                                               (0, (192, 64, 128, 128), (200, 300)), (16, (192, 64, 128, 128), (200, 300))])
+def test_ring_call_replays_from_a_hip_graph(flags, lens, masked):
     """The library allocates nothing and clears nothing with memset nodes, so a ring call can be
     captured into a HIP graph.  Every replay (with eager calls and synchronisations of the program
     in between, outputs scrubbed first) must reproduce the eager result bit for bit."""
     P = _P()
-    wl = W.Workload("r4_graph", 12, 1, 3, 128, 200, tuple(lens), "bf16")
+    wl = W.Workload("r4_graph", 12, 1, 3, 128, 200, tuple(lens), "bf16", masked_keys=masked or (0, 0))
     inp = W.make_attention_inputs(wl)
     q = dev_bf16(inp.q); ks = [dev_bf16(k) for k in inp.k]; vs = [dev_bf16(v) for v in inp.v]
+    km = None if inp.key_mask is None else [torch.from_numpy(m).to(DEV) for m in inp.key_mask]
     out = torch.empty_like(q)
     lse = torch.empty((1, 3, 200), dtype=torch.float32, device=DEV)
     desc = P.make_attn_desc(q, ks, out, float(inp.softmax_scale), flags)
     ws = torch.empty((P.usp_ring_attn_workspace_bytes(desc),), dtype=torch.uint8, device=DEV)
-    call = lambda: P.usp_ring_attn_fwd(q, ks, vs, softmax_scale=float(inp.softmax_scale), flags=flags,
+    call = lambda: P.usp_ring_attn_fwd(q, ks, vs, key_mask=km, softmax_scale=float(inp.softmax_scale), flags=flags,
                                        out=out, lse=lse, workspace=ws)
     call()
     torch.cuda.synchronize()
