@@ -10,9 +10,13 @@ namespace usp {
 namespace {
 
 // kUnits: 16-byte units of a source row (8 for bf16, 4 for one-byte codes); the padded row has twice as many
+// blockIdx.y picks the tensor: K (0) or V (1) of a chunk, padded by one launch
 template <int kUnits>
-__global__ __launch_bounds__(256) void pad64_kernel(const unsigned char* __restrict__ src, unsigned char* __restrict__ dst,
+__global__ __launch_bounds__(256) void pad64_kernel(const unsigned char* __restrict__ src0, unsigned char* __restrict__ dst0,
+                                                    const unsigned char* __restrict__ src1, unsigned char* __restrict__ dst1,
                                                     int H, int S, int64_t s0, int64_t s1, int64_t s2, int64_t rows) {
+  const unsigned char* src = blockIdx.y ? src1 : src0;
+  unsigned char* dst = blockIdx.y ? dst1 : dst0;
   const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t row = g / (2 * kUnits);
   if (row >= rows) return;
@@ -38,16 +42,16 @@ __global__ __launch_bounds__(256) void unpad64_kernel(const bf16_t* __restrict__
 
 }  // namespace
 
-usp_status launch_pad64(const void* src, void* dst, int B, int H, int S, const int64_t stride[3], int elt_bytes,
-                        hipStream_t st) {
+usp_status launch_pad64(const void* k_src, void* k_dst, const void* v_src, void* v_dst, int B, int H, int S,
+                        const int64_t stride[3], int elt_bytes, hipStream_t st) {
   const int64_t rows = (int64_t)B * H * S;
   if (rows == 0) return USP_OK;
   if (elt_bytes == 2)
-    hipLaunchKernelGGL(pad64_kernel<8>, dim3((unsigned)((rows * 16 + 255) / 256)), dim3(256), 0, st, (const unsigned char*)src,
-                       (unsigned char*)dst, H, S, stride[0], stride[1], stride[2], rows);
+    hipLaunchKernelGGL(pad64_kernel<8>, dim3((unsigned)((rows * 16 + 255) / 256), 2), dim3(256), 0, st, (const unsigned char*)k_src,
+                       (unsigned char*)k_dst, (const unsigned char*)v_src, (unsigned char*)v_dst, H, S, stride[0], stride[1], stride[2], rows);
   else
-    hipLaunchKernelGGL(pad64_kernel<4>, dim3((unsigned)((rows * 8 + 255) / 256)), dim3(256), 0, st, (const unsigned char*)src,
-                       (unsigned char*)dst, H, S, stride[0], stride[1], stride[2], rows);
+    hipLaunchKernelGGL(pad64_kernel<4>, dim3((unsigned)((rows * 8 + 255) / 256), 2), dim3(256), 0, st, (const unsigned char*)k_src,
+                       (unsigned char*)k_dst, (const unsigned char*)v_src, (unsigned char*)v_dst, H, S, stride[0], stride[1], stride[2], rows);
   USP_CHECK_HIP(hipGetLastError());
   return USP_OK;
 }

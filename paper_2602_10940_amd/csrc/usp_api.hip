@@ -440,8 +440,7 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
       if (len > 0) {
         const int64_t dense[3] = {(int64_t)desc->H * len * 64, (int64_t)len * 64, 64};
         const int64_t* ks = kv_auto(desc) ? dense : desc->kv_stride;
-        if ((st = launch_pad64(k_chunks[r], ws + off, desc->B, desc->H, len, ks, kv_es, cs)) != USP_OK) return st;
-        if ((st = launch_pad64(v_chunks[r], ws + off + bytes, desc->B, desc->H, len, ks, kv_es, cs)) != USP_OK) return st;
+        if ((st = launch_pad64(k_chunks[r], ws + off, v_chunks[r], ws + off + bytes, desc->B, desc->H, len, ks, kv_es, cs)) != USP_OK) return st;
       }
       off += 2 * bytes;
     }

@@ -164,8 +164,8 @@ usp_status launch_attn_arrive_reset(int* arrive, hipStream_t st);
 usp_status launch_attn_multi_records(const AttnStep& s, hipStream_t st);
 // [B,H,S,64] (bf16: elt_bytes 2, E4M3 codes: 1) by (B,H,token) strides in elements <-> dense [B,H,S,128]
 // with zero columns 64..127
-usp_status launch_pad64(const void* src, void* dst, int B, int H, int S, const int64_t stride[3], int elt_bytes,
-                        hipStream_t st);
+usp_status launch_pad64(const void* k_src, void* k_dst, const void* v_src, void* v_dst, int B, int H, int S,
+                        const int64_t stride[3], int elt_bytes, hipStream_t st);   // K and V of one chunk in one launch
 usp_status launch_unpad64(const void* src, void* dst, int B, int H, int S, const int64_t stride[3], hipStream_t st);
 // chunk c of a step over several FP8 chunks decoded by a launch of its own; reset_arrive: the same
 // launch zeroes the arrival counters (it precedes the attention launch on the stream)
