@@ -146,3 +146,27 @@ def test_batch_times_heads_beyond_the_launch_grid_is_refused():
         b.usp_ring_attn_workspace_bytes(d)
     d.H = 16383                                   # 65532 pairs: planned
     assert b.usp_ring_attn_workspace_bytes(d) > 0
+
+
+def test_missing_library_is_an_error_not_a_fallback(monkeypatch, tmp_path):
+    """Without the built library the binding raises; no Python or CPU path stands in for the kernels."""
+    from paper_2602_10940_amd import binding as b
+    monkeypatch.setattr(b, "_lib", None)
+    monkeypatch.setattr(b, "LIB_PATH", str(tmp_path / "libusp.so"))
+    with pytest.raises(b.UspError, match="no fallback"):
+        b.load_library()
+    with pytest.raises(b.UspError):
+        b.usp_version()
+
+
+def test_product_code_does_not_import_the_oracle():
+    """oracle/ is test infrastructure: nothing under the package (Python or HIP sources) names it."""
+    import glob
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    pkg = os.path.join(root, "paper_2602_10940_amd")
+    files = glob.glob(os.path.join(pkg, "*.py")) + glob.glob(os.path.join(pkg, "csrc", "*")) + \
+        glob.glob(os.path.join(root, "include", "*.h"))
+    assert files
+    for f in files:
+        text = open(f, encoding="utf-8", errors="replace").read()
+        assert "import oracle" not in text and "from oracle" not in text and "usp_oracle" not in text, f
