@@ -51,7 +51,7 @@ typedef enum {
 #define USP_ATTN_FUSED_PREFETCH 16u /* Algorithm 2 without a second stream: the transfers are done by extra
                                       work-groups of the attention launches on compute_stream;
                                       copy_stream is ignored.  Excludes USP_ATTN_DOUBLE_BUFFER.  Two forms:
-                                      - one launch per chunk (always with USP_ATTN_STEPWISE, a chunk length
+                                      - one launch per chunk (always with USP_ATTN_STEPWISE or a chunk length
                                         that is not a multiple of 64): step
                                         r's launch carries the transfer of chunk r+1 into the idle one
                                         of two internal buffers, in work-groups that occupy the CUs the
