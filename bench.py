@@ -401,6 +401,17 @@ def ring_leg(P, W, torch, dev, up_bf16, name="flux1024_r4", reps=600):
                    "by launches of their own before its attention launch; one launch: copy work-groups of the "
                    "attention launch decode chunk r+1 while chunk r is computed on (the plain call and "
                    "USP_ATTN_FUSED_PREFETCH give this same launch)"}
+    # the same bf16 ring with a key mask on its last chunk (its last tenth of the keys dead, as padded
+    # text tokens would be): one launch per chunk against the one launch over the ring
+    km = [None] * (wl.W - 1) + [torch.ones((wl.B, wl.chunk_len[-1]), dtype=torch.uint8, device=dev)]
+    km[-1][:, -(sum(wl.chunk_len) // 10):] = 0
+    t_mk_c = timed(lambda: P.usp_ring_attn_fwd(q, ks, vs, key_mask=km, softmax_scale=scale, flags=P.USP_ATTN_STEPWISE,
+                                               out=out, lse=lse, workspace=ws1))
+    t_mk_1 = timed(lambda: P.usp_ring_attn_fwd(q, ks, vs, key_mask=km, softmax_scale=scale, out=out, lse=lse, workspace=ws1))
+    masked = {"dead_keys": int(sum(wl.chunk_len) // 10), "t_per_chunk_ms": round(t_mk_c, 4), "t_plain_call_ms": round(t_mk_1, 4),
+              "plain_call_over_unmasked_one_launch": round(t_mk_1 / t_1, 3),
+              "note": "the plain call takes one launch over the ring (per-tile records for every chunk) where the ring "
+                      "steps are short or every chunk is masked, else one launch per chunk"}
     hid = lambda t: round(max(0.0, min(1.0, 1.0 - (t - t_c) / t_m)), 3) if t_m > 0 else None
     return {"workload": "%s: Sq=%d, %d chunks of %d, H=%d d=%d bf16" % (name, wl.Sq, wl.W, wl.chunk_len[0], wl.H, wl.d),
             "t_compute_ms": round(t_c, 4), "t_copies_ms": round(t_m, 4),
@@ -413,7 +424,7 @@ def ring_leg(P, W, torch, dev, up_bf16, name="flux1024_r4", reps=600):
             "t_pipelined_one_launch_ms": round(t_r1, 4), "tflops_pipelined_one_launch": tf(t_r1),
             "hidden_fraction_one_launch": round(max(0.0, min(1.0, 1.0 - (t_r1 - t_1) / t_m)), 3) if t_m > 0 else None,
             "serial_over_pipelined_one_launch": round(t_s / t_r1, 3),
-            "fp8_kv": fp8,
+            "fp8_kv": fp8, "masked_last_chunk": masked,
             "note": "on-device copies stand in for ring recv; an xGMI link is ~50x slower"}
 
 

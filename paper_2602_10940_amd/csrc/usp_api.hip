@@ -508,13 +508,23 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
   {
     bool one_launch = p.mfma && !p.fp8 && (!p.dbuf || p.ring1) && !p.unfused && p.W > 1 && !(desc->flags & USP_ATTN_STEPWISE) &&
                       short_steps;
-    int n_live = 0;
+    int n_live = 0, n_masked = 0;
+    int64_t keys = 0;
     for (int r = 0; one_launch && r < p.W; ++r) {
       const int len = desc->chunk_len[r];
       if (len == 0) continue;
       if (len % 64 != 0) one_launch = false;
+      if (key_mask && key_mask[r]) ++n_masked;
+      keys += len;
       ++n_live;
     }
+    // Key masks: the one launch then reads per-tile records for every chunk, which costs it about a
+    // third (96 against 73 us on a FLUX-1024 ring of four with one masked chunk), while the per-chunk
+    // form pays for records only in the masked chunks' launches.  The one launch still wins where the
+    // ring steps are short (below about 40 million query-key pairs per step) or every chunk is masked.
+    if (one_launch && n_masked > 0 && n_masked < n_live &&
+        (double)desc->B * desc->H * desc->Sq * ((double)keys / n_live) > 40e6)
+      one_launch = false;
     if (one_launch && n_live >= 2 && n_live <= AttnStep::kMaxMulti && p.multi_rec) {
       AttnStep a;
       memset(&a, 0, sizeof(a));
