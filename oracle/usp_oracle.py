@@ -42,7 +42,10 @@ logsumexp, chunk-order invariance over every permutation, merge-tree
 associativity, raw-form == difference-form merge, the OCP E4M3 value table facts
 (448, 2^-9, 2^-6, NaN codes, monotonicity), torch.float8_e4m3fn casts inside
 +-448, encode(decode(b)) == b, tie and saturation cases, per-row invariants of
-the quantiser and its provable round-trip bound; for the mapped variants the
+the quantiser and its provable round-trip bound; dequant_exact_f64 (what an FP8
+K/V chunk means as numbers) against exact rationals, against the fp32
+dequantiser it must round to in one step, and on a [B,H,L,d] case with a
+different scale per (b, h, token); for the mapped variants the
 identity with numpy transposes of the plain result, and a four-rank emulation
 of the exchange of section 2.2.1 (8 heads, 1024 tokens: [B,8,256,D] ->
 [B,2,1024,D] and back).

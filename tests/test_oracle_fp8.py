@@ -237,8 +237,54 @@ def test_dequant_values():
     codes = np.array([[0x38, 0xB8, 0x7E, 0x01]], np.uint8)     # 1, -1, 448, 2^-9
     y = orc.fp8_dequant(codes, np.array([0.5], np.float32))
     np.testing.assert_array_equal(y, [[0.5, -0.5, 224.0, 2.0 ** -10]])
-    ex = orc.dequant_exact_f64(codes, np.array([0.1], np.float32))
-    np.testing.assert_array_equal(ex, orc.e4m3fn_decode(codes) * np.float64(np.float32(0.1)))
+
+
+def test_dequant_exact_f64_rounds_once_to_the_pinned_dequantiser():
+    """Algorithm 1 line 4 in exact arithmetic: an E4M3 value has 4 significant bits and an fp32
+    scale 24, so the fp64 product is exact, and ONE rounding of it to fp32 must reproduce the
+    pinned fp32 dequantiser bit for bit: every finite code against scales over the whole normal
+    fp32 range (a dropped scale, a squared scale or a wrong table entry fails)."""
+    codes = np.array([c for c in range(256) if (c & 0x7F) != 0x7F], np.uint8)     # the 254 finite codes
+    rng = np.random.Generator(np.random.PCG64(77))
+    n_scales = 512
+    scales = (rng.uniform(1.0, 2.0, n_scales) * np.exp2(rng.integers(-100, 100, n_scales))).astype(np.float32)
+    cm = np.broadcast_to(codes[None, :], (n_scales, codes.size)).copy()
+    ex = orc.dequant_exact_f64(cm, scales)
+    assert ex.dtype == np.float64 and ex.shape == cm.shape
+    # exactness: the product as a ratio of integers equals the double, on a sample of entries
+    for i in rng.integers(0, n_scales, 40):
+        for j in rng.integers(0, codes.size, 6):
+            want = Fraction(float(orc.e4m3fn_decode_table()[codes[j]])) * Fraction(float(scales[i]))
+            assert Fraction(float(ex[i, j])) == want
+    with np.errstate(over="ignore", under="ignore"):
+        once = ex.astype(np.float32)
+    np.testing.assert_array_equal(once.view(np.uint32), orc.fp8_dequant(cm, scales).view(np.uint32))
+
+
+def test_dequant_exact_f64_scale_axes_explicit_values():
+    """[B,H,L,d] codes with one scale per (b, h, token): every scale a different power of two or
+    small integer, so each expected value can be written down; a scale taken along the wrong axis
+    (head for token, token for element) gives a different number somewhere."""
+    B, H, L, d = 2, 3, 4, 5
+    one, m_one, c448, tiny, c1p5 = 0x38, 0xB8, 0x7E, 0x01, 0x3C        # 1, -1, 448, 2^-9, 1.5
+    row = np.array([one, m_one, c448, tiny, c1p5], np.uint8)
+    codes = np.broadcast_to(row, (B, H, L, d)).copy()
+    scales = np.empty((B, H, L), np.float32)
+    for b in range(B):
+        for h in range(H):
+            for t in range(L):
+                scales[b, h, t] = np.float32((1 + 10 * b) * 2.0 ** h * (3 + 2 * t))  # all 24 distinct
+    assert len(set(scales.reshape(-1).tolist())) == B * H * L
+    ex = orc.dequant_exact_f64(codes, scales)
+    assert ex.shape == (B, H, L, d)
+    for b in range(B):
+        for h in range(H):
+            for t in range(L):
+                s = (1 + 10 * b) * 2.0 ** h * (3 + 2 * t)
+                np.testing.assert_array_equal(ex[b, h, t], [s, -s, 448.0 * s, s * 2.0 ** -9, 1.5 * s])
+    # 2-D view [rows, cols] with [rows] scales is the same function
+    ex2 = orc.dequant_exact_f64(codes.reshape(-1, d), scales.reshape(-1))
+    np.testing.assert_array_equal(ex2.reshape(ex.shape), ex)
 
 
 # ---------------------------------------------------------------------------
