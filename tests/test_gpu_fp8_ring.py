@@ -134,9 +134,9 @@ def test_fp8_ring_one_launch_with_key_masks():
     _assert_parity(host_f64(o), host_f64(l), ro2, rl2)
 
 
-def test_fp8_ring_flux1024_r4_full_size_sampled_rows():
+def test_fp8_ring_flux1024_r4_full_size_every_row():
     """The configuration bench.py times for the FP8 ring (flags 0 and FUSED_PREFETCH give the same
-    launch): sampled query rows against the oracle, the whole output against the per-chunk form."""
+    launch): every query row of every head against the oracle, for it and for the per-chunk form."""
     wl = W.WORKLOADS["flux1024_r4"]
     inp, q, kq, ksc, vq, vsc, kx, vx = _fp8_ring(wl)
     scale = float(inp.softmax_scale)
@@ -146,9 +146,13 @@ def test_fp8_ring_flux1024_r4_full_size_sampled_rows():
     so, sl = _call(q, kq, ksc, vq, vsc, scale, STEPWISE)
     assert float((o.float() - so.float()).abs().max()) <= 2.0 ** -6
     assert float((l - sl).abs().max()) <= 1e-4
-    rows = np.array([0, 1, 63, 64, 255, 256, 511, 777, 1000, 1151])
-    ro, rl = orc.ring_attention(inp.q[:, :, rows, :], kx, vx, scale)
-    _assert_parity(host_f64(o)[:, :, rows, :], host_f64(l)[:, :, rows], ro, rl)
+    ro, rl = orc.ring_attention(inp.q, kx, vx, scale)
+    for oo, ll in ((o, l), (so, sl)):
+        ho, hl = host_f64(oo), host_f64(ll)
+        assert ho.shape == ro.shape == (1, 24, 1152, 128)
+        _assert_parity(ho, hl, ro, rl)
+        for h in range(wl.H):
+            _assert_parity(ho[:, h:h + 1], hl[:, h:h + 1], ro[:, h:h + 1], rl[:, h:h + 1])
 
 
 @pytest.mark.parametrize("flags", [0, STEPWISE])

@@ -61,12 +61,11 @@ def test_many_calls_through_one_workspace(kind, shape, masked, flag_list):
         need = P.usp_ring_attn_workspace_bytes(desc)
         ws = torch.full((max(need, 256),), 0xFF, dtype=torch.uint8, device=DEV)
         rng = np.random.Generator(np.random.PCG64(11))
-        bad = 0
-        for _ in range(12):
+        for batch in range(12):
             outs = []
             for _ in range(50):
                 i = int(rng.integers(0, 3))
                 outs.append((i, P.usp_ring_attn_fwd(flags=flags, workspace=ws if need else None, **kw, **rings[i])))
             torch.cuda.synchronize()
-            bad += sum(1 for i, (o, l) in outs if not (torch.equal(o, refs[i][0]) and torch.equal(l, refs[i][1])))
-        assert bad == 0, (flags, bad)
+            bad = sum(1 for i, (o, l) in outs if not (torch.equal(o, refs[i][0]) and torch.equal(l, refs[i][1])))
+            assert bad == 0, (flags, batch, bad)        # stop at the first batch with a mismatch
