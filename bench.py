@@ -28,9 +28,23 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2516.6   # 256 CU x 4096 flop/clk x 2.4 GHz (dense, no sparsity)
 PEAK_HBM_GBS = 8000.0
-# HBM bytes of one flux1024_u attention launch (104.1 MB read + 28.8 MB written), from the rocprofv3
-# FETCH_SIZE / WRITE_SIZE runs summarised in profiles/attn_pp_kernel_flux1024_u.md
-ATTN_TRAFFIC_BYTES = 132.9e6
+PREHEAT_S = 1.5             # untimed run of the same step before the warm-up and the timed region
+
+
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch (fetch + write) from the rocprofv3 --pmc summary kept under profiles/,
+    or None if there is no entry for this workload and kernel."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_per_launch.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) == 4 and not line.startswith("#") and parts[0] == workload and parts[1] == kernel:
+                    return {"bytes": float(parts[2]) + float(parts[3]), "fetch_bytes": float(parts[2]),
+                            "write_bytes": float(parts[3]), "source": "profiles/hbm_traffic_per_launch.txt"}
+    except OSError:
+        pass
+    return None
 
 
 def _events(n):
@@ -41,10 +55,10 @@ def _events(n):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    # the GPU needs a few hundred ms of sustained load before its clocks settle; the defaults
-    # warm up for ~1 s and time ~1.5 s
+    # the GPU needs a few hundred ms of sustained load before its clocks settle: a fixed pre-heat
+    # (PREHEAT_S of the same step, untimed, whatever --warmup says) precedes the W warm-up steps
     ap.add_argument("--steps", type=int, default=2500)
-    ap.add_argument("--warmup", type=int, default=1500)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-ring", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -59,6 +73,7 @@ def main() -> int:
 
     import torch
     import paper_2602_10940_amd as P
+    from paper_2602_10940_amd import diag as D
     from paper_2602_10940_amd import workloads as W
 
     P.load_library()                      # fails loudly if the HIP library is not built
@@ -98,6 +113,15 @@ def main() -> int:
         P.usp_ring_attn_fwd(q, [k], [v], softmax_scale=scale, out=out, lse=lse, workspace=ws)
         if ev: ev[1].record()
 
+    # pre-heat: the same step, untimed, until PREHEAT_S of wall time have passed (clocks settled)
+    t_pre = time.perf_counter()
+    n_pre = 0
+    while time.perf_counter() - t_pre < PREHEAT_S:
+        for i in range(50):
+            step(n_pre + i)
+        n_pre += 50
+        torch.cuda.synchronize()
+    preheat_s = time.perf_counter() - t_pre
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -195,13 +219,14 @@ def main() -> int:
         iters = 1000
         pout = torch.empty((n_cu * 512,), dtype=torch.float32, device=dev)
         pclk = torch.zeros((2,), dtype=torch.int64, device=dev)
-        t = per_launch(lambda i: P.usp_probe_mfma_rate(n_cu, iters, random_data, pout, pclk), reps=20, rounds=3)
+        t = per_launch(lambda i: D.usp_diag_mfma_rate(n_cu, iters, random_data, pout, pclk), reps=20, rounds=3)
         cyc, ticks = [int(v) for v in pclk.cpu()]
         fl = n_cu * 8 * iters * 32 * 32768.0
         return {"tflops": round(fl / (t * 1e-3) * 1e-12, 1), "shader_mhz": round(cyc / max(ticks, 1) * 100.0),
                 "frac_of_bf16_peak": round(fl / (t * 1e-3) * 1e-12 / PEAK_BF16_TFLOPS, 4)}
     probe_rand, probe_const = mfma_probe(True), mfma_probe(False)
 
+    traffic = measured_traffic("flux1024_u", "attn_pp_kernel<wide,plain>")
     flops = wl.attn_flops()
     value = flops / (ms_per_step * 1e-3) * 1e-12
     attn_tflops = flops / (t_attn * 1e-3) * 1e-12
@@ -212,7 +237,8 @@ def main() -> int:
     result = {
         "metric": "ring-attn TFLOP/s + FP8 quant GB/s, % of MI355X peak, FLUX-1024 shard",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "warmup": args.warmup, "preheat_s": round(preheat_s, 2), "preheat_steps": n_pre,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "flux1024_u: B=1 H=24 d=128 S=4608 bf16, one KV chunk; FP8 payload [4608,3072] bf16",
                    "step": "fp8_quant + fp8_dequant + ring_attn_fwd"},
@@ -245,10 +271,11 @@ def main() -> int:
         "lse_merge": {"us": round(t_merge * 1e3, 2), "gbs": round(merge_bytes / (t_merge * 1e-3) * 1e-9, 1),
                       "bytes": merge_bytes, "note": "flux1024_r4 state [27648,128] bf16, cache-warm (21 MB per launch)"},
         "roofline": {"bound": "mfma", "achieved": round(attn_tflops, 1), "peak": PEAK_BF16_TFLOPS,
-                     "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4), "traffic": ATTN_TRAFFIC_BYTES,
+                     "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4),
+                     "traffic": traffic["bytes"] if traffic else None, "traffic_detail": traffic,
                      "kernel": "attn_pp_kernel<wide, plain>", "flops_per_launch": flops},
         "mfma_sustained": {"random_operands": probe_rand, "constant_operands": probe_const,
-                           "note": "MFMA-only probe on every CU (usp_probe_mfma_rate): the rate and clock the chip "
+                           "note": "MFMA-only probe on every CU (libusp_diag.so, usp_diag_mfma_rate): the rate and clock the chip "
                                    "holds under a full matrix-core load; the published peak assumes 2400 MHz"},
     }
     result["roofline"]["frac_of_sustained_mfma"] = round(attn_tflops / probe_rand["tflops"], 4)

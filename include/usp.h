@@ -133,7 +133,9 @@ size_t usp_ring_attn_workspace_bytes(const usp_attn_desc* desc);
  *   v_chunks   same for V.  With USP_ATTN_DOUBLE_BUFFER or USP_ATTN_FUSED_PREFETCH the chunks
  *              after the first (and their scales) are only read by the transfers, so they may
  *              also sit in pinned host memory that the device can address (hipHostMalloc): the
- *              transfers then cross the host link, which stands in for a slow ring link.
+ *              transfers then cross the host link, which stands in for a slow ring link.  (Not with
+ *              bf16 Q and d = 64: every chunk is first padded to d = 128 by a kernel on
+ *              compute_stream, which reads it where it is.)
  *   k_scales / v_scales   NULL unless kv_dtype is FP8: HOST arrays of device pointers,
  *              chunk r -> float [B,H,chunk_len[r]] dense, one scale per (b,h,token)
  *              (value = code * scale, as produced by usp_fp8_quant on the
@@ -218,20 +220,6 @@ usp_status usp_fp8_quant_mapped(const usp_row_map* map, int64_t cols, int32_t in
                                 uint8_t* q, float* scales, void* stream);
 usp_status usp_fp8_dequant_mapped(const usp_row_map* map, int64_t cols, int32_t out_dt, const uint8_t* q,
                                   const float* scales, void* y, void* stream);
-
-/* Diagnostic, not a step of the paper's method: the dense bf16 MFMA rate the device sustains when
- * nothing else is issued, the measured ceiling that the attention kernels' rate can be read
- * against.  wgs work-groups of 8 waves each execute iters * 32 MFMAs (32x32x16, fp32 accumulate,
- * 32768 flop each) per wave on operands held in registers: pseudo-random values in [-1, 1] if
- * random_data != 0, constants otherwise (the clock the chip holds under load depends on the data).
- *   out    : device, wgs * 512 floats, receives per-thread sums (so the work cannot be dropped)
- *   clocks : device, 2 x uint64: shader cycles and 100 MHz ticks that work-group 0 spent in its
- *            loop (their ratio x 100 = shader clock in MHz)
- * Asynchronous on stream; time it with events around the call.
- * Limits: 1 <= wgs <= 65536, 1 <= iters <= 1000000.
- */
-usp_status usp_probe_mfma_rate(int32_t wgs, int32_t iters, int32_t random_data, float* out,
-                               uint64_t* clocks, void* stream);
 
 /* Thread-local, statically stored description of the last failure ("" if none). */
 const char* usp_last_error(void);

@@ -24,7 +24,7 @@ USP_ATTN_KERNEL_MIXED = 32
 USP_ATTN_STEPWISE = 64
 
 EXPORTS = ("usp_ring_attn_workspace_bytes", "usp_ring_attn_fwd", "usp_lse_merge", "usp_fp8_quant",
-           "usp_fp8_dequant", "usp_fp8_quant_mapped", "usp_fp8_dequant_mapped", "usp_probe_mfma_rate",
+           "usp_fp8_dequant", "usp_fp8_quant_mapped", "usp_fp8_dequant_mapped",
            "usp_last_error", "usp_version")
 
 
@@ -89,8 +89,6 @@ def load_library() -> ctypes.CDLL:
     lib.usp_fp8_quant_mapped.argtypes = [ctypes.POINTER(RowMap), i64, i32, vp, vp, vp, vp]
     lib.usp_fp8_dequant_mapped.restype = i32
     lib.usp_fp8_dequant_mapped.argtypes = [ctypes.POINTER(RowMap), i64, i32, vp, vp, vp, vp]
-    lib.usp_probe_mfma_rate.restype = i32
-    lib.usp_probe_mfma_rate.argtypes = [i32, i32, i32, vp, vp, vp]
     _lib = lib
     return lib
 
@@ -187,16 +185,6 @@ def usp_fp8_dequant_mapped(q: torch.Tensor, scales: torch.Tensor, n, src_stride,
     _check(lib.usp_fp8_dequant_mapped(ctypes.byref(m), q.shape[1], _dt(y.dtype), _ptr(q), _ptr(scales), _ptr(y),
                                       _stream_handle(stream)))
     return y
-
-
-def usp_probe_mfma_rate(wgs: int, iters: int, random_data: bool, out: torch.Tensor, clocks: torch.Tensor,
-                        stream=None) -> None:
-    """out: f32 device tensor of wgs*512 elements; clocks: int64 device tensor of 2 (shader cycles, 100 MHz ticks)."""
-    lib = load_library()
-    assert out.dtype == torch.float32 and out.numel() >= wgs * 512 and out.is_contiguous()
-    assert clocks.dtype == torch.int64 and clocks.numel() >= 2 and clocks.is_contiguous()
-    _check(lib.usp_probe_mfma_rate(int(wgs), int(iters), 1 if random_data else 0, _ptr(out), _ptr(clocks),
-                                   _stream_handle(stream)))
 
 
 def usp_lse_merge(o1: torch.Tensor, lse1: torch.Tensor, o2: torch.Tensor, lse2: torch.Tensor,

@@ -16,7 +16,10 @@ OBJ_DIR = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libusp.so")
 
 SOURCES = ["usp_api.hip", "fp8_kernels.hip", "merge_kernel.hip", "attn_generic.hip", "attn_mfma.hip",
-           "probe_kernels.hip", "layout_kernels.hip"]
+           "layout_kernels.hip"]
+# libusp_diag.so: the MFMA-rate probe of the benchmark and a test hook, outside the library's ABI
+DIAG_LIB = os.path.join(PKG, "libusp_diag.so")
+DIAG_SOURCES = [os.path.join("diag", "usp_diag.hip")]
 
 # -packed-fp32-ops off: keep the compiler from forming packed fp32 VALU ops.
 # IEEE fp32 division / denormals are required by the FP8 scale arithmetic (no fast-math).
@@ -38,7 +41,7 @@ def hipcc() -> str:
 
 
 def _compile(src: str, extra) -> str:
-    obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
+    obj = os.path.join(OBJ_DIR, os.path.splitext(os.path.basename(src))[0] + ".o")
     cmd = [hipcc(), *HIPCC_FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
@@ -48,14 +51,18 @@ def _compile(src: str, extra) -> str:
 
 def build(verbose: bool = False, extra_flags=()) -> str:
     os.makedirs(OBJ_DIR, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
-        objs = list(ex.map(lambda s: _compile(s, list(extra_flags)), SOURCES))
-    cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("link failed:\n%s" % r.stderr[-8000:])
-    if verbose:
-        print("built", LIB)
+    srcs = SOURCES + DIAG_SOURCES
+    with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
+        objs = list(ex.map(lambda s: _compile(s, list(extra_flags)), srcs))
+    n = len(SOURCES)
+    for lib, lib_objs, extra in ((LIB, objs[:n], []),
+                                 (DIAG_LIB, objs[n:], ["-L", PKG, "-lusp", "-Wl,-rpath,$ORIGIN"])):
+        cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *lib_objs, *extra]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("link failed:\n%s" % r.stderr[-8000:])
+        if verbose:
+            print("built", lib)
     return LIB
 
 

@@ -20,19 +20,6 @@
 #include "usp_common.h"
 #include "prefetch_copy.h"
 
-// Instrumentation points of the tile loop (phase boundaries, slow-path count, work-group begin and
-// end): empty in the library; a timing harness that includes this file defines them before it does.
-#ifndef LAB_STAMP
-#define LAB_STAMP(slot)
-#endif
-#ifndef LAB_COUNT_SLOW
-#define LAB_COUNT_SLOW()
-#endif
-#ifndef LAB_WG_START
-#define LAB_WG_START()
-#define LAB_WG_END()
-#endif
-
 namespace usp {
 namespace {
 
@@ -88,8 +75,10 @@ __device__ __forceinline__ float xlane32_sum(float x) {
 // Chunk result, merge and store straight from the accumulator layout (32 bytes per query row and
 // instruction): what the key-split work-groups use, whose epilogue is too short for the detour
 // through LDS to pay.
+// `invalid`: the rows are not to be trusted (a chunk of the ring never arrived): O and lse become NaN,
+// which no valid result is (a query whose keys are all masked gets O = 0, lse = -inf).
 __device__ __forceinline__ void finish_and_store_direct(const AttnStep& s, f32x16 (&oacc)[4], float m, float lsum,
-                                                 int b, int h, int q0, int n, int g) {
+                                                 int b, int h, int q0, int n, int g, bool invalid) {
   // ---- chunk result, merge with carried state, store ------------------------------------
   const float l = xlane32_sum(lsum);
   const int qi = q0 + n;
@@ -108,6 +97,7 @@ __device__ __forceinline__ void finish_and_store_direct(const AttnStep& s, f32x1
       c_cur *= expf(lse_r - lse_new);
     }
   }
+  if (invalid) { c_cur = __builtin_nanf(""); lse_new = c_cur; }
   if (!valid) return;
   float* accp = s.acc ? s.acc + row * kD : nullptr;
   bf16_t* outp = (bf16_t*)s.out + b * s.os[0] + h * s.os[1] + (int64_t)qi * s.os[2];
@@ -143,7 +133,7 @@ __device__ __forceinline__ void finish_and_store_direct(const AttnStep& s, f32x1
 constexpr int kEpiPitch = kD * 4 + 16;                    // bytes per staged row
 constexpr int kEpiWaveB = kQPerWave * kEpiPitch + 512;    // + per-row (scale of O~, weight of the carry, lse, unused)
 __device__ __forceinline__ void finish_and_store(const AttnStep& s, f32x16 (&oacc)[4], float m, float lsum,
-                                                 int b, int h, int q0, int n, int g, unsigned char* epi) {
+                                                 int b, int h, int q0, int n, int g, unsigned char* epi, bool invalid) {
   typedef float f32x4 __attribute__((ext_vector_type(4)));
   const int lane = n + 32 * g;
   const float l = xlane32_sum(lsum);
@@ -162,6 +152,7 @@ __device__ __forceinline__ void finish_and_store(const AttnStep& s, f32x16 (&oac
       c_cur *= expf(lse_r - lse_new);
     }
   }
+  if (invalid) { c_cur = __builtin_nanf(""); lse_new = c_cur; }
   if (g == 0 && qi < s.Sq) s.lse[row0 + qi] = lse_new;
   // stage: row n, head dims 32*dt + 8*i4 + 4*g .. +3
   float* info = reinterpret_cast<float*>(epi + kQPerWave * kEpiPitch);
@@ -350,11 +341,12 @@ __global__ __launch_bounds__(64) void attn_multi_records_kernel(AttnStep s) {
 // Wait of an attention work-group for a chunk that the copy work-groups of the same launch are still
 // writing: polls the chunk's counter with device-scope loads until it reaches `need`.  The copy
 // work-groups are dispatched before every attention work-group and wait for nothing, so the count
-// is reached; the poll limit (of the order of a second) only keeps a launch from spinning forever
-// should that ever not hold, at the price of a result the caller can recognise as invalid (NaN).
+// is reached; the poll limit (of the order of a second by default) only keeps a launch from spinning
+// forever should that ever not hold, at the price of a result the caller can recognise as invalid:
+// every row of a work-group one of whose waves gave up is returned as NaN in out and lse.
 constexpr int kArrivePolls = 1 << 21;
-__device__ __forceinline__ bool wait_arrival(const int* counter, int need) {
-  for (int i = 0; i < kArrivePolls; ++i) {
+__device__ __forceinline__ bool wait_arrival(const int* counter, int need, int polls) {
+  for (int i = 0; i < polls; ++i) {
     if (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= need) {
       asm volatile("" ::: "memory");
       return true;
@@ -389,7 +381,6 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
   // split: waves w and w+4 share their 32 queries
   const int q0 = q_base + (kSplit ? (wave & 3) : wave) * kQPerWave;
   const bool grpA = wave < 4;
-  LAB_WG_START();
 
   const bf16_t* qb = (const bf16_t*)s.q + b * s.qs[0] + h * s.qs[1];
   const unsigned char* kb = (const unsigned char*)((const bf16_t*)s.k + b * s.ks[0] + h * s.ks[1]);
@@ -463,7 +454,7 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
       xcur_first += s.chunk[xcur_c].Sc / kTile;
       ++xcur_c;
       if (s.arrive != nullptr && xcur_c > arrived_upto) {
-        if (!wait_arrival(s.arrive + xcur_c, s.copy_wgs)) late = true;
+        if (!wait_arrival(s.arrive + xcur_c, s.arrive_need, s.arrive_polls)) late = true;
         arrived_upto = xcur_c;
       }
     }
@@ -492,8 +483,8 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
       ++cur.c;
       if (s.arrive != nullptr && cur.c > arrived_upto) {
         // the count read a few tiles ago usually settles it; otherwise poll
-        const bool seen = probe_c == cur.c && __builtin_amdgcn_readfirstlane(probe_val) >= s.copy_wgs;
-        if (!seen && !wait_arrival(s.arrive + cur.c, s.copy_wgs)) late = true;
+        const bool seen = probe_c == cur.c && __builtin_amdgcn_readfirstlane(probe_val) >= s.arrive_need;
+        if (!seen && !wait_arrival(s.arrive + cur.c, s.arrive_need, s.arrive_polls)) late = true;
         arrived_upto = cur.c;
       }
     }
@@ -857,7 +848,6 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
     kpre_idx += kPreStep;
     vpre_idx += kPreStep;
     if (__builtin_amdgcn_ballot_w64(!(psum <= kCertifiedSum)) != 0ull) {
-      LAB_COUNT_SLOW();
       // a reference that was already set and still failed: scores with heavy tails; look for the
       // maximum first on the next tiles instead of paying for the exponentials twice
       if (__builtin_amdgcn_ballot_w64(m != -INFINITY) != 0ull) max_first = kMaxFirstTiles;
@@ -938,13 +928,9 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
       //         phase 2j+1 = MM(j) with V(j) in stage st, K(j+1) in stage st+1
       for (int j = 0; j < nt - 1; ++j) {
         const int s1 = nxt(st), s2 = nxt(s1);
-        LAB_STAMP(6 * j);
         SM(j & 3, s2, s1, j + 2 < nt, true, j + 2 < nt, j + 2, (j + 2) & 3);
-        LAB_STAMP(6 * j + 1);
         phase_barrier(j + 2 < nt ? 1 : 2);
-        LAB_STAMP(6 * j + 3);
         MM_full(st, s1);
-        LAB_STAMP(6 * j + 5);
         phase_barrier(0, false);
         st = s1;
       }
@@ -963,13 +949,9 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
       for (int j = 1; j < nt; ++j) {
         const int sp = st;                              // stage of tile j-1
         st = nxt(st);
-        LAB_STAMP(6 * j);
         MM_full(sp, st);
-        LAB_STAMP(6 * j + 1);
         phase_barrier(0);
-        LAB_STAMP(6 * j + 3);
         SM(j & 3, st, sp, j + 3 < nt, j + 2 < nt, false, 0, 0);   // st+2 == sp (mod 3)
-        LAB_STAMP(6 * j + 5);
         phase_barrier(j + 3 < nt ? 1 : 2, false);
       }
       MM_last(st);
@@ -997,17 +979,11 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
     int st = t;                            // t % 3
     if (!grpA) end_phase(false);           // phase 0: group B has no scores yet
     while (t + 2 < nt) {
-      LAB_STAMP(6 * t);
       const int s1 = nxt(st), s2 = nxt(s1);                // (t + 1) % 3, (t + 2) % 3
       SM(st, st, s1, t + 3 < nt, true, true, t + 2, s2);   // phase t (t + 1 < nt holds here)
-      LAB_STAMP(6 * t + 1);
       end_phase(false);
-      LAB_STAMP(6 * t + 2);
       MM_full(st, s2);                                     // phase t + 1
-      LAB_STAMP(6 * t + 3);
-      LAB_STAMP(6 * t + 4);
       end_phase(true);
-      LAB_STAMP(6 * t + 5);
       t += 2;
       st = s2;
     }
@@ -1022,6 +998,11 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
     if ((grpA && (nt % 2 == 0)) || (!grpA && (nt % 2 == 1))) end_phase(false);
   }
   }  // nt > 0
+  // A wave that gave up waiting for a chunk loaded its rows of the tiles too early, and every wave of
+  // the work-group has read those rows: the flag belongs to the work-group.
+  if (kMulti) {
+    if (s.arrive != nullptr) late = __syncthreads_or(late ? 1 : 0) != 0;
+  }
 
   if (kSplit) {
     // ---- fold group B's partial state into group A's (same queries, disjoint keys) --------------
@@ -1051,12 +1032,10 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
     lsum = wa * lsum + wb * lB;
     m = mm;
   }
-  LAB_WG_END();
-  if (kMulti && late) lsum = __builtin_nanf("");
 
   // every tile read of the work-group is behind a barrier here (the one after the last matrix phase)
-  if (kSplit) finish_and_store_direct(s, oacc, m, lsum, b, h, q0, n, g);
-  else finish_and_store(s, oacc, m, lsum, b, h, q0, n, g, smem_raw + wave * kEpiWaveB);
+  if (kSplit) finish_and_store_direct(s, oacc, m, lsum, b, h, q0, n, g, kMulti && late);
+  else finish_and_store(s, oacc, m, lsum, b, h, q0, n, g, smem_raw + wave * kEpiWaveB, kMulti && late);
 }
 
 template <bool kSplit, bool kExt, bool kMulti = false, bool kNoDead = false, bool kHalfD = false>
@@ -1249,6 +1228,8 @@ usp_status launch_attn_mfma(const AttnStep& step, hipStream_t st) {
       s.n_copy = 1;                                    // (only asks prefetch_wg_count for a count)
       s.copy_wgs = prefetch_wg_count(s, (int)wgs, 1);
       s.n_copy = 0;
+      s.arrive_need = s.copy_wgs + (s.arrive_need_extra > 0 ? s.arrive_need_extra : 0);
+      if (s.arrive_polls <= 0 || s.arrive_polls > kArrivePolls) s.arrive_polls = kArrivePolls;
     }
     if (s.multi_fp8 && s.multi_masked)
       return split ? launch_pp<true, true, true, false>(s, wgs, st) : launch_pp<false, true, true, false>(s, wgs, st);

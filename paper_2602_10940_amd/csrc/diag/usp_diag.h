@@ -1,0 +1,44 @@
+/*
+ * usp_diag.h - entry points of libusp_diag.so: diagnostics for the benchmark and the tests.  Not part
+ * of the library's ABI (include/usp.h); conventions (device pointers, streams as void*, usp_status,
+ * usp_last_error() of libusp.so) are the same.
+ */
+#ifndef USP_DIAG_H
+#define USP_DIAG_H
+
+#include "usp.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* The dense bf16 MFMA rate the device sustains when nothing else is issued: the measured ceiling
+ * that the attention kernels' rate can be read against.  wgs work-groups of 8 waves each execute
+ * iters * 32 MFMAs (32x32x16, fp32 accumulate, 32768 flop each) per wave on operands held in
+ * registers: pseudo-random values in [-1, 1] if random_data != 0, constants otherwise (the clock the
+ * chip holds under load depends on the data).
+ *   out    : device, wgs * 512 floats, receives per-thread sums (so the work cannot be dropped)
+ *   clocks : device, 2 x uint64: shader cycles and 100 MHz ticks that work-group 0 spent in its
+ *            loop (their ratio x 100 = shader clock in MHz)
+ * Asynchronous on stream.  Limits: 1 <= wgs <= 65536, 1 <= iters <= 1000000. */
+usp_status usp_diag_mfma_rate(int32_t wgs, int32_t iters, int32_t random_data, float* out,
+                              uint64_t* clocks, void* stream);
+
+/* usp_ring_attn_fwd (same arguments, no copy stream) with the two knobs of the bounded wait that an
+ * attention work-group of the one-launch ring makes for a chunk's arrival counter:
+ *   arrive_need_extra : added to the count it waits for (> 0: a count that is never reached)
+ *   arrive_polls      : poll limit (0 = the library's default, about a second)
+ * With a count that is never reached every waiting work-group gives up after arrive_polls polls and
+ * returns its rows as NaN in out and lse; every kernel still runs to its end.  Calls that do not take
+ * the one-launch form with transfers inside ignore both. */
+usp_status usp_diag_ring_attn_fwd_wait(const usp_attn_desc* desc, const void* q,
+                                       const void* const* k_chunks, const void* const* v_chunks,
+                                       const float* const* k_scales, const float* const* v_scales,
+                                       const uint8_t* const* key_mask, void* out, float* lse,
+                                       void* workspace, size_t workspace_bytes, void* compute_stream,
+                                       int32_t arrive_need_extra, int32_t arrive_polls);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* USP_DIAG_H */

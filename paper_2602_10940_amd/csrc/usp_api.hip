@@ -48,9 +48,6 @@ struct EventPool {
   }
 };
 thread_local EventPool g_events;
-// set around the d = 128 call that stands in for a bf16 d = 64 call: columns 64..127 of its Q, K and V
-// are zero, and the matrix-core kernels may skip the MFMAs on them
-thread_local bool g_half_d = false;
 
 struct Plan {
   bool valid = false;
@@ -110,7 +107,8 @@ usp_attn_desc padded_desc(const usp_attn_desc* d) {
   return in;
 }
 
-usp_status make_plan(const usp_attn_desc* d, Plan* p) {
+// half_d: the descriptor is the d = 128 stand-in of a bf16 d = 64 call (CallOptions::half_d)
+usp_status make_plan(const usp_attn_desc* d, Plan* p, bool half_d = false) {
   USP_CHECK_ARG(d != nullptr, "desc is NULL");
   USP_CHECK_ARG(d->B > 0 && d->H > 0 && d->Sq > 0, "B, H, Sq must be positive (B=%d H=%d Sq=%d)", d->B, d->H, d->Sq);
   USP_CHECK_ARG(d->d > 0 && d->d % 8 == 0 && d->d <= 256, "d must be a multiple of 8 in [8, 256] (got %d)", d->d);
@@ -130,7 +128,7 @@ usp_status make_plan(const usp_attn_desc* d, Plan* p) {
     USP_CHECK_ARG(d->kv_stride[i] >= 0 && d->kv_stride[i] % kal == 0, "kv_stride[%d]=%lld must be a non-negative multiple of %lld", i, (long long)d->kv_stride[i], (long long)kal);
   }
   {
-    const int qo_cols = g_half_d ? 64 : d->d;   // inside the stand-in call for d = 64, Q and O rows are 64 wide
+    const int qo_cols = half_d ? 64 : d->d;   // inside the stand-in call for d = 64, Q and O rows are 64 wide
     USP_CHECK_ARG(d->q_stride[2] >= qo_cols && d->o_stride[2] >= qo_cols && (kv_auto(d) || d->kv_stride[2] >= d->d),
                   "token strides must be >= d");
   }
@@ -151,10 +149,7 @@ usp_status make_plan(const usp_attn_desc* d, Plan* p) {
   if (p->pad64) {
     const usp_attn_desc in = padded_desc(d);
     Plan ip;
-    const bool outer = g_half_d;
-    g_half_d = true;
-    const usp_status st = make_plan(&in, &ip);
-    g_half_d = outer;
+    const usp_status st = make_plan(&in, &ip, true);
     if (st != USP_OK) return st;
     p->rows_q = (size_t)d->B * d->H * d->Sq;
     size_t off = 0;
@@ -386,24 +381,25 @@ usp_status usp_lse_merge(int64_t rows, int32_t d, int32_t dt, const void* o1, co
   return launch_lse_merge(rows, d, dt, o1, lse1, o2, lse2, o_out, lse_out, (hipStream_t)stream);
 }
 
-usp_status usp_probe_mfma_rate(int32_t wgs, int32_t iters, int32_t random_data, float* out, uint64_t* clocks,
-                               void* stream) {
-  clear_error();
-  USP_CHECK_ARG(wgs >= 1 && wgs <= 65536, "wgs=%d out of range [1, 65536]", wgs);
-  USP_CHECK_ARG(iters >= 1 && iters <= 1000000, "iters=%d out of range [1, 1000000]", iters);
-  USP_CHECK_ARG(out != nullptr && clocks != nullptr, "out or clocks is NULL");
-  return launch_probe_mfma_rate(wgs, iters, random_data, out, reinterpret_cast<unsigned long long*>(clocks),
-                                (hipStream_t)stream);
-}
-
 usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const void* const* k_chunks,
                              const void* const* v_chunks, const float* const* k_scales,
                              const float* const* v_scales, const uint8_t* const* key_mask, void* out,
                              float* lse, void* workspace, size_t workspace_bytes, void* compute_stream,
                              void* copy_stream) {
   clear_error();
+  return ring_attn_fwd_impl(desc, q, k_chunks, v_chunks, k_scales, v_scales, key_mask, out, lse, workspace,
+                            workspace_bytes, compute_stream, copy_stream, CallOptions());
+}
+
+}  // extern "C"
+
+usp_status usp::ring_attn_fwd_impl(const usp_attn_desc* desc, const void* q, const void* const* k_chunks,
+                                   const void* const* v_chunks, const float* const* k_scales,
+                                   const float* const* v_scales, const uint8_t* const* key_mask, void* out,
+                                   float* lse, void* workspace, size_t workspace_bytes, void* compute_stream,
+                                   void* copy_stream, const CallOptions& opt) {
   Plan p;
-  usp_status st = make_plan(desc, &p);
+  usp_status st = make_plan(desc, &p, opt.half_d);
   if (st != USP_OK) return st;
   USP_CHECK_ARG(q && out && lse && k_chunks && v_chunks, "q, out, lse, k_chunks or v_chunks is NULL");
   USP_CHECK_ARG(aligned16(q) && aligned16(out), "q and out must be 16-byte aligned");
@@ -444,10 +440,10 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
       }
       off += 2 * bytes;
     }
-    g_half_d = true;
-    st = usp_ring_attn_fwd(&in, q, kp.data(), vp.data(), k_scales, v_scales, key_mask, pad_o ? (void*)(ws + p.off_pad_o) : out, lse,
-                           p.inner_total ? ws + p.off_pad_inner : nullptr, p.inner_total, compute_stream, copy_stream);
-    g_half_d = false;
+    CallOptions inner = opt;
+    inner.half_d = true;
+    st = ring_attn_fwd_impl(&in, q, kp.data(), vp.data(), k_scales, v_scales, key_mask, pad_o ? (void*)(ws + p.off_pad_o) : out, lse,
+                            p.inner_total ? ws + p.off_pad_inner : nullptr, p.inner_total, compute_stream, copy_stream, inner);
     if (st != USP_OK || !pad_o) return st;
     return launch_unpad64(ws + p.off_pad_o, out, desc->B, desc->H, desc->Sq, desc->o_stride, cs);
   }
@@ -529,7 +525,7 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
       AttnStep a;
       memset(&a, 0, sizeof(a));
       a.B = desc->B; a.H = desc->H; a.d = d; a.Sq = desc->Sq;
-      a.qo_dtype = desc->qo_dtype; a.half_d = g_half_d ? 1 : 0; a.kv_dtype = desc->kv_dtype;
+      a.qo_dtype = desc->qo_dtype; a.half_d = opt.half_d ? 1 : 0; a.kv_dtype = desc->kv_dtype;
       a.q = q; a.out = out; a.lse = lse; a.scale = scale; a.mode = 0;
       for (int i = 0; i < 3; ++i) { a.qs[i] = desc->q_stride[i]; a.ks[i] = desc->kv_stride[i]; a.os[i] = desc->o_stride[i]; }
       if (kv_auto(desc)) a.ks[2] = d;
@@ -555,6 +551,7 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
       }
       if (transfers) {
         a.arrive = (int*)(ws + p.off_arrive);
+        a.arrive_need_extra = opt.arrive_need_extra; a.arrive_polls = opt.arrive_polls;
         if ((st = launch_attn_arrive_reset(a.arrive, cs)) != USP_OK) return st;
       }
       if (a.multi_masked) {   // some chunk has a key mask: the launch reads per-tile records
@@ -574,7 +571,7 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
       AttnStep a;
       memset(&a, 0, sizeof(a));
       a.B = desc->B; a.H = desc->H; a.d = d; a.Sq = desc->Sq;
-      a.qo_dtype = desc->qo_dtype; a.half_d = g_half_d ? 1 : 0; a.kv_dtype = USP_BF16;   // what the attention work-groups read
+      a.qo_dtype = desc->qo_dtype; a.half_d = opt.half_d ? 1 : 0; a.kv_dtype = USP_BF16;   // what the attention work-groups read
       a.q = q; a.out = out; a.lse = lse; a.scale = scale; a.mode = 0;
       for (int i = 0; i < 3; ++i) { a.qs[i] = desc->q_stride[i]; a.os[i] = desc->o_stride[i]; }
       a.ks[2] = d;
@@ -582,6 +579,7 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
       a.multi_fp8 = 1;
       a.ext = (float*)(ws + p.off_ext8);
       a.arrive = (int*)(ws + p.off_arrive);
+      a.arrive_need_extra = opt.arrive_need_extra; a.arrive_polls = opt.arrive_polls;
       size_t stage = p.off_ring8;
       for (int r = 0; r < p.W; ++r) {
         const int len = desc->chunk_len[r];
@@ -629,7 +627,7 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
     AttnStep a;
     memset(&a, 0, sizeof(a));
     a.B = desc->B; a.H = desc->H; a.d = d; a.Sq = desc->Sq; a.Sc = len;
-    a.qo_dtype = desc->qo_dtype; a.half_d = g_half_d ? 1 : 0; a.kv_dtype = desc->kv_dtype;
+    a.qo_dtype = desc->qo_dtype; a.half_d = opt.half_d ? 1 : 0; a.kv_dtype = desc->kv_dtype;
     a.q = q; a.k = kp; a.v = vp; a.k_scale = ksp; a.v_scale = vsp;
     a.key_mask = key_mask ? key_mask[r] : nullptr;
     for (int i = 0; i < 3; ++i) { a.qs[i] = desc->q_stride[i]; a.ks[i] = desc->kv_stride[i]; a.os[i] = desc->o_stride[i]; }
@@ -688,5 +686,3 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q, const voi
   }
   return USP_OK;
 }
-
-}  // extern "C"

@@ -131,6 +131,13 @@ struct AttnStep {
   int multi_masked;          // some chunk has a key mask (Chunk::mask_src): the records may flag dead keys.  With bf16
                              // chunks (no multi_fp8) the records are those of launch_attn_multi_records
   int* arrive;               // [kMaxMulti] counters, zero when the launch starts; or null
+  // what an attention work-group waits for on arrive[c], and for how long: the launcher sets the
+  // count to copy_wgs plus arrive_need_extra and the poll limit to its default when arrive_polls is
+  // 0.  Both exist so that a host-side test can make the bounded wait give up (a count that is never
+  // reached, a short limit) with every kernel still running to its end.
+  int arrive_need_extra;
+  int arrive_need;
+  int arrive_polls;
   Chunk chunk[kMaxMulti];
   // Prefetch carried by this launch (Algorithm 2, the transfer of the next chunk): the last
   // copy_wgs work-groups of the grid copy the n_copy segments and exit; they are dispatched after
@@ -150,8 +157,6 @@ inline int prefetch_wg_count(const AttnStep& s, int attn_wgs, int slots_per_cu) 
   const int n = spare / 8 * 8;
   return n < 16 ? 16 : (n > 64 ? 64 : n);
 }
-usp_status launch_probe_mfma_rate(int wgs, int iters, int random_data, float* out, unsigned long long* clocks,
-                                  hipStream_t st);
 usp_status launch_attn_generic(const AttnStep& s, hipStream_t st);
 usp_status launch_attn_mfma(const AttnStep& s, hipStream_t st);
 bool attn_mfma_supported(const AttnStep& s);
@@ -170,5 +175,19 @@ usp_status launch_unpad64(const void* src, void* dst, int B, int H, int S, const
 // chunk c of a step over several FP8 chunks decoded by a launch of its own; reset_arrive: the same
 // launch zeroes the arrival counters (it precedes the attention launch on the stream)
 usp_status launch_attn_fp8_chunk_prepare(const AttnStep& s, int c, bool reset_arrive, hipStream_t st);
+
+
+// What usp_ring_attn_fwd does, with the knobs the ABI does not carry.
+struct CallOptions {
+  bool half_d = false;        // the d = 128 call stands in for a bf16 d = 64 call: columns 64..127 of K and V are
+                              // zero padding, Q and O rows are 64 wide (the matrix-core kernels skip the MFMAs on zeros)
+  int arrive_need_extra = 0;  // see AttnStep (tests of the give-up path only)
+  int arrive_polls = 0;
+};
+usp_status ring_attn_fwd_impl(const usp_attn_desc* desc, const void* q, const void* const* k_chunks,
+                              const void* const* v_chunks, const float* const* k_scales,
+                              const float* const* v_scales, const uint8_t* const* key_mask, void* out,
+                              float* lse, void* workspace, size_t workspace_bytes, void* compute_stream,
+                              void* copy_stream, const CallOptions& opt);
 
 }  // namespace usp

@@ -1,0 +1,69 @@
+"""ctypes binding of libusp_diag.so (csrc/diag/usp_diag.h): diagnostics for the benchmark and the
+tests, outside the library's ABI.  Marshalling only."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence, Tuple
+
+import torch
+
+from . import binding as B
+
+DIAG_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libusp_diag.so")
+_diag = None
+
+
+def load_diag_library() -> ctypes.CDLL:
+    global _diag
+    if _diag is not None:
+        return _diag
+    B.load_library()   # libusp_diag.so is linked against libusp.so
+    if not os.path.exists(DIAG_LIB_PATH):
+        raise B.UspError(B.USP_ERR_HIP, "%s not found: run `python -m paper_2602_10940_amd.build` first" % DIAG_LIB_PATH)
+    lib = ctypes.CDLL(DIAG_LIB_PATH)
+    vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+    lib.usp_diag_mfma_rate.restype = i32
+    lib.usp_diag_mfma_rate.argtypes = [i32, i32, i32, vp, vp, vp]
+    lib.usp_diag_ring_attn_fwd_wait.restype = i32
+    lib.usp_diag_ring_attn_fwd_wait.argtypes = [ctypes.POINTER(B.AttnDesc), vp, ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                                ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                                vp, vp, vp, sz, vp, i32, i32]
+    _diag = lib
+    return lib
+
+
+def usp_diag_mfma_rate(wgs: int, iters: int, random_data: bool, out: torch.Tensor, clocks: torch.Tensor,
+                       stream=None) -> None:
+    """out: f32 device tensor of wgs*512 elements; clocks: int64 device tensor of 2 (shader cycles, 100 MHz ticks)."""
+    lib = load_diag_library()
+    assert out.dtype == torch.float32 and out.numel() >= wgs * 512 and out.is_contiguous()
+    assert clocks.dtype == torch.int64 and clocks.numel() >= 2 and clocks.is_contiguous()
+    B._check(lib.usp_diag_mfma_rate(int(wgs), int(iters), 1 if random_data else 0, B._ptr(out), B._ptr(clocks),
+                                    B._stream_handle(stream)))
+
+
+def usp_diag_ring_attn_fwd_wait(q: torch.Tensor, k_chunks: Sequence[torch.Tensor], v_chunks: Sequence[torch.Tensor],
+                                arrive_need_extra: int, arrive_polls: int,
+                                k_scales: Optional[Sequence[torch.Tensor]] = None,
+                                v_scales: Optional[Sequence[torch.Tensor]] = None,
+                                key_mask: Optional[Sequence[Optional[torch.Tensor]]] = None,
+                                softmax_scale: float = 0.0, flags: int = 0,
+                                workspace: Optional[torch.Tensor] = None, compute_stream=None
+                                ) -> Tuple[torch.Tensor, torch.Tensor]:
+    """usp_ring_attn_fwd with the knobs of the one-launch ring's bounded arrival wait."""
+    lib = load_diag_library()
+    Bn, H, Sq, d = q.shape
+    out = torch.empty((Bn, H, Sq, d), dtype=q.dtype, device=q.device)
+    lse = torch.empty((Bn, H, Sq), dtype=torch.float32, device=q.device)
+    desc = B.make_attn_desc(q, k_chunks, out, softmax_scale, flags)
+    need = B.usp_ring_attn_workspace_bytes(desc)
+    if workspace is None and need > 0:
+        workspace = torch.empty((need,), dtype=torch.uint8, device=q.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    B._check(lib.usp_diag_ring_attn_fwd_wait(ctypes.byref(desc), B._ptr(q), B._ptr_array(k_chunks), B._ptr_array(v_chunks),
+                                             B._ptr_array(k_scales), B._ptr_array(v_scales), B._ptr_array(key_mask),
+                                             B._ptr(out), B._ptr(lse), B._ptr(workspace), ws_bytes,
+                                             B._stream_handle(compute_stream), int(arrive_need_extra), int(arrive_polls)))
+    out._usp_workspace = workspace
+    return out, lse

@@ -50,10 +50,24 @@ def test_validation_without_gpu():
     lib.usp_lse_merge.argtypes = [i64, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     assert lib.usp_lse_merge(8, 12, 1, None, None, None, None, None, None, None) == -1
     assert lib.usp_lse_merge(0, 128, 1, None, None, None, None, None, None, None) == 0
-    lib.usp_probe_mfma_rate.argtypes = [i32, i32, i32, vp, vp, vp]
-    assert lib.usp_probe_mfma_rate(0, 10, 1, None, None, None) == -1        # wgs out of range
-    assert lib.usp_probe_mfma_rate(4, 10, 1, None, None, None) == -1        # NULL buffers
+
+
+def test_diag_library_is_separate_from_the_abi():
+    """The MFMA-rate probe and the arrival-wait hook live in libusp_diag.so with a header of their own:
+    include/usp.h declares neither, libusp.so exports neither."""
+    lib = _lib()
+    assert not hasattr(lib, "usp_diag_mfma_rate") and not hasattr(lib, "usp_probe_mfma_rate")
+    assert all(not n.startswith("usp_diag") and "probe" not in n for n in _declared())
+    from paper_2602_10940_amd import diag
+    dl = diag.load_diag_library()
+    lib.usp_last_error.restype = ctypes.c_char_p
+    assert dl.usp_diag_mfma_rate(0, 10, 1, None, None, None) == -1         # wgs out of range
+    assert dl.usp_diag_mfma_rate(4, 10, 1, None, None, None) == -1         # NULL buffers
     assert b"NULL" in lib.usp_last_error()
+    src = open(os.path.join(ROOT, "paper_2602_10940_amd", "csrc", "diag", "usp_diag.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    for n in sorted(set(re.findall(r"\b(usp_diag_[a-z0-9_]+)\s*\(", src))):
+        assert hasattr(dl, n), n
 
 
 def test_workspace_sizes_and_descriptor_checks():
@@ -164,7 +178,8 @@ def test_product_code_does_not_import_the_oracle():
     import glob
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     pkg = os.path.join(root, "paper_2602_10940_amd")
-    files = glob.glob(os.path.join(pkg, "*.py")) + glob.glob(os.path.join(pkg, "csrc", "*")) + \
+    files = glob.glob(os.path.join(pkg, "*.py")) + glob.glob(os.path.join(pkg, "csrc", "*.*")) + \
+        glob.glob(os.path.join(pkg, "csrc", "diag", "*.*")) + \
         glob.glob(os.path.join(root, "include", "*.h"))
     assert files
     for f in files:
