@@ -163,6 +163,32 @@ usp_status usp_ring_attn_fwd(const usp_attn_desc* desc, const void* q,
                              void* compute_stream, void* copy_stream);
 
 /*
+ * usp_ring_attn_fwd for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
+ * and results as usp_ring_attn_fwd (same kernels, same order: bit-identical outputs), minus the
+ * workspace and the copy stream: the workspace is an array of USP_NOALLOC_SCRATCH_BYTES that the
+ * library holds in device memory on every GPU it runs on, from the first such call on that GPU until
+ * the process ends.  The call allocates and frees nothing (no hipMalloc, no events).
+ *   - A descriptor whose usp_ring_attn_workspace_bytes() exceeds USP_NOALLOC_SCRATCH_BYTES is refused
+ *     with USP_ERR_WORKSPACE and nothing is enqueued (e.g. the FLUX-1024 ring shard needs 17 MB, the
+ *     Qwen-Image-like FP8 shard 0.5 GB: the latter has to bring its own workspace).
+ *   - USP_ATTN_DOUBLE_BUFFER (side stream and events) is refused with USP_ERR_UNSUPPORTED; the
+ *     transfers inside the launches (USP_ATTN_FUSED_PREFETCH) are available.
+ *   - Every call on one GPU uses that GPU's one array: calls that overlap in time on one GPU (two
+ *     streams, two host threads) race and give undefined results; calls ordered on one stream are
+ *     safe.  Nothing is carried from call to call: whatever a call needs to start at zero it clears
+ *     itself, on compute_stream.
+ *   - The first call on a device looks up the array's address for that device (no allocation); make
+ *     that call outside graph capture.
+ */
+#define USP_NOALLOC_SCRATCH_BYTES (64u << 20)
+usp_status usp_ring_attn_fwd_noalloc(const usp_attn_desc* desc, const void* q,
+                                     const void* const* k_chunks, const void* const* v_chunks,
+                                     const float* const* k_scales, const float* const* v_scales,
+                                     const uint8_t* const* key_mask,
+                                     void* out, float* lse, void* compute_stream);
+
+/*
  * Merge two partial attention results (section 3.4, the two equations under
  * Algorithm 2; same as the pair in section 2.2.2):
  *   lse = log(exp(lse1) + exp(lse2))

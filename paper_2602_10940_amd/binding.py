@@ -22,8 +22,9 @@ USP_ATTN_KERNEL_WIDE, USP_ATTN_KERNEL_SPLIT = 4, 8
 USP_ATTN_FUSED_PREFETCH = 16
 USP_ATTN_KERNEL_MIXED = 32
 USP_ATTN_STEPWISE = 64
+USP_NOALLOC_SCRATCH_BYTES = 64 << 20
 
-EXPORTS = ("usp_ring_attn_workspace_bytes", "usp_ring_attn_fwd", "usp_lse_merge", "usp_fp8_quant",
+EXPORTS = ("usp_ring_attn_workspace_bytes", "usp_ring_attn_fwd", "usp_ring_attn_fwd_noalloc", "usp_lse_merge", "usp_fp8_quant",
            "usp_fp8_dequant", "usp_fp8_quant_mapped", "usp_fp8_dequant_mapped",
            "usp_last_error", "usp_version")
 
@@ -79,6 +80,9 @@ def load_library() -> ctypes.CDLL:
     lib.usp_ring_attn_fwd.argtypes = [ctypes.POINTER(AttnDesc), vp, ctypes.POINTER(vp), ctypes.POINTER(vp),
                                       ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp),
                                       vp, vp, vp, sz, vp, vp]
+    lib.usp_ring_attn_fwd_noalloc.restype = i32
+    lib.usp_ring_attn_fwd_noalloc.argtypes = [ctypes.POINTER(AttnDesc), vp, ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                              ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), vp, vp, vp]
     lib.usp_lse_merge.restype = i32
     lib.usp_lse_merge.argtypes = [i64, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.usp_fp8_quant.restype = i32
@@ -264,4 +268,21 @@ def usp_ring_attn_fwd(q: torch.Tensor, k_chunks: Sequence[torch.Tensor], v_chunk
                                  _ptr_array(k_scales), _ptr_array(v_scales), _ptr_array(key_mask),
                                  _ptr(out), _ptr(lse), _ptr(workspace), ws_bytes, cs, xs))
     out._usp_workspace = workspace  # keep the workspace alive as long as the result
+    return out, lse
+
+
+def usp_ring_attn_fwd_noalloc(q: torch.Tensor, k_chunks: Sequence[torch.Tensor], v_chunks: Sequence[torch.Tensor],
+                              out: torch.Tensor, lse: torch.Tensor,
+                              k_scales: Optional[Sequence[torch.Tensor]] = None,
+                              v_scales: Optional[Sequence[torch.Tensor]] = None,
+                              key_mask: Optional[Sequence[Optional[torch.Tensor]]] = None,
+                              softmax_scale: float = 0.0, flags: int = 0, compute_stream=None
+                              ) -> Tuple[torch.Tensor, torch.Tensor]:
+    """usp_ring_attn_fwd on the library's built-in scratch: the caller passes every input and output
+    (out [B,H,Sq,d], lse [B,H,Sq]); nothing is allocated, here or in the library."""
+    lib = load_library()
+    desc = make_attn_desc(q, k_chunks, out, softmax_scale, flags)
+    _check(lib.usp_ring_attn_fwd_noalloc(ctypes.byref(desc), _ptr(q), _ptr_array(k_chunks), _ptr_array(v_chunks),
+                                         _ptr_array(k_scales), _ptr_array(v_scales), _ptr_array(key_mask),
+                                         _ptr(out), _ptr(lse), _stream_handle(compute_stream)))
     return out, lse

@@ -275,7 +275,63 @@ usp_status make_plan(const usp_attn_desc* d, Plan* p, bool half_d = false) {
 
 using namespace usp;
 
+// ---- the workspace of usp_ring_attn_fwd_noalloc: one array per GPU, held until the process ends ----
+// In host code the array's name is only a handle for hipGetSymbolAddress; its device address, one per
+// device, is looked up once with that device current and is what the kernels are given.
+static __device__ __align__(256) unsigned char scratch[USP_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+usp_status scratch_for_current_device(void** out) {
+  int dev = -1;
+  USP_CHECK_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) {
+    set_error("device ordinal %d is outside [0, %d)", dev, kMaxDevices);
+    return USP_ERR_UNSUPPORTED;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    USP_CHECK_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (ptr == nullptr || (reinterpret_cast<uintptr_t>(ptr) & 255u) != 0) {
+      set_error("the scratch array of device %d has no usable address", dev);
+      return USP_ERR_HIP;
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return USP_OK;
+}
+}  // namespace
+
 extern "C" {
+
+usp_status usp_ring_attn_fwd_noalloc(const usp_attn_desc* desc, const void* q, const void* const* k_chunks,
+                                     const void* const* v_chunks, const float* const* k_scales,
+                                     const float* const* v_scales, const uint8_t* const* key_mask, void* out,
+                                     float* lse, void* compute_stream) {
+  clear_error();
+  Plan p;
+  usp_status st = make_plan(desc, &p);
+  if (st != USP_OK) return st;
+  if ((desc->flags & USP_ATTN_DOUBLE_BUFFER) != 0) {
+    set_error("usp_ring_attn_fwd_noalloc has no copy stream: USP_ATTN_DOUBLE_BUFFER is not available "
+              "(USP_ATTN_FUSED_PREFETCH is)");
+    return USP_ERR_UNSUPPORTED;
+  }
+  if (p.total > (size_t)USP_NOALLOC_SCRATCH_BYTES) {
+    set_error("this call needs %zu bytes of workspace, the built-in scratch holds %zu: use usp_ring_attn_fwd "
+              "with a workspace of the caller's", p.total, (size_t)USP_NOALLOC_SCRATCH_BYTES);
+    return USP_ERR_WORKSPACE;
+  }
+  void* ws = nullptr;
+  if (p.total > 0 && (st = scratch_for_current_device(&ws)) != USP_OK) return st;
+  return ring_attn_fwd_impl(desc, q, k_chunks, v_chunks, k_scales, v_scales, key_mask, out, lse, ws,
+                            p.total > 0 ? (size_t)USP_NOALLOC_SCRATCH_BYTES : 0, compute_stream, nullptr, CallOptions());
+}
 
 const char* usp_last_error(void) { return g_err; }
 const char* usp_version(void) { return "usp-gfx950 0.1"; }

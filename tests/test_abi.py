@@ -133,6 +133,32 @@ def test_workspace_sizes_and_descriptor_checks():
         b.usp_ring_attn_workspace_bytes(d)
 
 
+def test_noalloc_entry_point_limits_without_gpu():
+    """usp_ring_attn_fwd_noalloc refuses, before any HIP call, a descriptor that needs more workspace
+    than its built-in scratch holds, and the side-stream schedule."""
+    from paper_2602_10940_amd import binding as b
+    lib = b.load_library()
+    hdr = open(os.path.join(ROOT, "include", "usp.h")).read()
+    m = re.search(r"#define\s+USP_NOALLOC_SCRATCH_BYTES\s+\((\d+)u\s*<<\s*(\d+)\)", hdr)
+    assert m and (int(m.group(1)) << int(m.group(2))) == b.USP_NOALLOC_SCRATCH_BYTES
+    lens = (ctypes.c_int32 * 2)(4096, 4096)
+    d = b.AttnDesc()
+    d.B, d.H, d.d, d.Sq, d.n_chunks = 1, 24, 128, 4096, 2
+    d.chunk_len = ctypes.cast(lens, ctypes.POINTER(ctypes.c_int32))
+    d.qo_dtype = b.USP_BF16
+    d.kv_dtype = b.USP_FP8_E4M3FN
+    for i, s in enumerate((24 * 4096 * 128, 4096 * 128, 128)):
+        d.q_stride[i] = d.o_stride[i] = s
+    assert b.usp_ring_attn_workspace_bytes(d) > b.USP_NOALLOC_SCRATCH_BYTES
+    assert lib.usp_ring_attn_fwd_noalloc(ctypes.byref(d), None, None, None, None, None, None, None, None, None) == b.USP_ERR_WORKSPACE
+    assert b"scratch" in lib.usp_last_error()
+    d.kv_dtype = b.USP_BF16
+    d.Sq = 256
+    lens[0] = lens[1] = 64
+    d.flags = b.USP_ATTN_DOUBLE_BUFFER
+    assert lib.usp_ring_attn_fwd_noalloc(ctypes.byref(d), None, None, None, None, None, None, None, None, None) == b.USP_ERR_UNSUPPORTED
+
+
 def test_header_is_plain_c():
     """include/usp.h is the boundary: it must compile as C99 and as C++ with nothing but the standard headers."""
     import shutil
