@@ -24,6 +24,31 @@ extern "C" {
 usp_status usp_diag_mfma_rate(int32_t wgs, int32_t iters, int32_t random_data, float* out,
                               uint64_t* clocks, void* stream);
 
+/* The pack kernels cast bf16 rows with a division sequence one correction step shorter than the IEEE
+ * one (Algorithm 1 line 2 fixes a true division).  This runs both over EVERY pair (a, x) of bf16 values
+ * with a > 0 finite as the row's |x| maximum (scale a / 448) and |x| <= a, both signs, and counts:
+ *   counts[0] pairs checked, counts[1] E4M3 codes that differ (must be 0), counts[2] quotients that
+ *   differ in some bit (harmless: never across a rounding boundary), counts[3] values of a whose
+ *   scale lies outside the range the short sequence is used in.
+ * counts: device, 4 x uint64, zeroed by the caller.  Asynchronous on stream. */
+usp_status usp_diag_check_bf16_division(uint64_t* counts, void* stream);
+
+/* What a pack launch over a [rows, 3072] bf16 payload costs before any arithmetic, on the pack's own
+ * grid (one wave per row): kind 0 = nothing at all (x, q, scales may be NULL), 1 = read every row
+ * (its |x| maximum goes to scales[row]), 2 = write rows * 3072 bytes to q.  x: rows * 3072 bf16. */
+usp_status usp_diag_payload_floor(int32_t kind, int32_t rows, const void* x, uint8_t* q, float* scales,
+                                  void* stream);
+
+/* reps back-to-back calls on one stream, issued from C so that the host's per-call cost (a few
+ * microseconds through an interpreter) does not bound what a timing loop measures: call i uses buffer
+ * set i % n_sets of the host arrays of device pointers x, q, scales, y (bf16 [rows, cols] payloads).
+ *   kind 0: usp_fp8_quant(x -> q, scales)     kind 1: usp_fp8_dequant(q, scales -> y)
+ *   kind 2, 3, 4: usp_diag_payload_floor with kind 0, 1, 2 (cols must be 3072)
+ * Time it with events around the call. */
+usp_status usp_diag_repeat_payload_calls(int32_t kind, int32_t reps, int32_t n_sets, int64_t rows, int64_t cols,
+                                         const void* const* x, uint8_t* const* q, float* const* scales,
+                                         void* const* y, void* stream);
+
 /* usp_ring_attn_fwd (same arguments, no copy stream) with the two knobs of the bounded wait that an
  * attention work-group of the one-launch ring makes for a chunk's arrival counter:
  *   arrive_need_extra : added to the count it waits for (> 0: a count that is never reached)

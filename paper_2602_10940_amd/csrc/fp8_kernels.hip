@@ -6,19 +6,20 @@
 // between the absmax reduction and the cast, so every input byte is read from HBM
 // once.  All HBM accesses are 16-byte (or 8-byte) vectors, consecutive lanes touching
 // consecutive addresses.
+#include <type_traits>
+
 #include "usp_common.h"
+#include "fp8_arith.h"
 
 namespace usp {
 namespace {
 
-constexpr float kFp8Max = 448.0f;
 // Launches whose output is smaller than these are written with streaming stores (see store8_nt):
 // the dequantiser's 2- or 4-byte outputs up to 64 MB (measured crossover between 57 and 85 MB), the
 // quantiser's codes, a third of its traffic, up to 256 MB (faster at every size measured, to 114 MB)
 constexpr int64_t kStreamDequantBelowBytes = 64ll << 20;
 constexpr int64_t kStreamQuantBelowBytes = 256ll << 20;
 
-typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 // ---- loads of 8 consecutive elements as fp32 --------------------------------------------
 // kStream: streaming load, for single-pass kernels on launches small next to the L2s (9.5 instead of
@@ -39,64 +40,6 @@ __device__ __forceinline__ void load8(const float* p, float (&v)[8]) {
   float4 b = *reinterpret_cast<const float4*>(p + 4);
   v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
   v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-}
-
-// x / s for many x and one s.  The compiler's IEEE-correct fp32 division is: reciprocal estimate,
-// one Newton step on the reciprocal, then two residual corrections of the quotient (plus operand
-// pre-scaling that only engages for extreme exponents).  Everything that depends on s alone is
-// hoisted here; quotient() is the per-element remainder of that same sequence and returns the
-// correctly rounded quotient whenever the pre-scaling would have been a no-op, which `fast`
-// guarantees for the divisor (|x| <= 448 s bounds the quotient).  Quotients too small to be
-// normal fp32 can differ in their last bits, but they are far below 2^-10 and encode to +-0
-// either way.  Rows outside the fast range use the plain division.
-struct RowDiv {
-  float s, rcp;
-  bool fast;
-};
-__device__ __forceinline__ RowDiv make_rowdiv(float s) {
-  RowDiv d;
-  d.s = s;
-  d.fast = s > 0x1p-60f && s < 0x1p+60f;
-  const float r0 = __builtin_amdgcn_rcpf(s);
-  const float e0 = fmaf(-s, r0, 1.0f);
-  d.rcp = fmaf(e0, r0, r0);
-  return d;
-}
-__device__ __forceinline__ float quotient(float x, const RowDiv& d) {
-  const float q0 = x * d.rcp;
-  const float r0 = fmaf(-d.s, q0, x);
-  const float q1 = fmaf(r0, d.rcp, q0);
-  const float r1 = fmaf(-d.s, q1, x);
-  // s > 0, so the quotient has the sign of x; restoring it keeps -0 (the corrections turn it into +0)
-  return __builtin_copysignf(fmaf(r1, d.rcp, q1), x);
-}
-
-// E4M3 codes of v[i] / s (round to nearest even, saturating).  In the fast range s is a normal
-// number, |v[i]| <= 448 s up to one rounding, so the quotient never reaches the overflow threshold
-// 464 and the hardware convert needs no clamp (inputs are assumed finite).  A denormal s can be
-// far from absmax / 448 in relative terms; that path clamps to +-448 before converting.
-template <bool kFast>
-__device__ __forceinline__ uint2 encode8(const float (&v)[8], const RowDiv& d) {
-  float t[8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i)
-    t[i] = kFast ? quotient(v[i], d) : __builtin_amdgcn_fmed3f(v[i] / d.s, -kFp8Max, kFp8Max);
-  int lo = __builtin_amdgcn_cvt_pk_fp8_f32(t[0], t[1], 0, false);
-  lo = __builtin_amdgcn_cvt_pk_fp8_f32(t[2], t[3], lo, true);
-  int hi = __builtin_amdgcn_cvt_pk_fp8_f32(t[4], t[5], 0, false);
-  hi = __builtin_amdgcn_cvt_pk_fp8_f32(t[6], t[7], hi, true);
-  return make_uint2((uint32_t)lo, (uint32_t)hi);
-}
-
-__device__ __forceinline__ float absmax8(const float (&v)[8], float a) {
-#pragma unroll
-  for (int i = 0; i < 8; ++i) a = fmaxf(a, fabsf(v[i]));
-  return a;
-}
-
-__device__ __forceinline__ float scale_from_absmax(float a) {
-  float s = a / kFp8Max;
-  return s == 0.0f ? 1.0f : s;
 }
 
 // Eight codes to memory; streaming (non-temporal) when the launch is small: see the note at store8_nt.
@@ -166,6 +109,89 @@ __global__ __launch_bounds__(256) void fp8_quant_rows_kernel(const T* __restrict
     for (int i = 0; i < NV; ++i) {
       const int u = l + i * LPR;
       if (row_ok && u < units) put_codes<kNT>(q + obase + (int64_t)u * 8, encode8<false>(v[i], d));
+    }
+  }
+}
+
+// The same for bf16 input, which is the payload type of the method: a row stays in registers as the
+// packed pairs it was loaded as (4 registers per 8 elements instead of 8), its |x| maximum is taken on
+// the bit patterns two elements at a time, and rows in the fast range are cast with the short
+// sequence of fp8_arith.h (5 instead of 8.5 VALU operations per element; the arithmetic, not the
+// memory system, was what the waves of a row spent most of their time on).
+// kFull: every row has exactly LPR * NV units (the FLUX payload: 384 = 64 * 6; K/V rows of one head:
+// 16 = 16 * 1), so no access needs a bounds check, and the |x| maximum goes over the lanes of a row
+// with DPP moves (quad swaps and mirrors inside a row of 16 lanes, scalar reads across the four rows)
+// instead of six exchanges through the LDS crossbar: 9.55 -> 8.97 us on the FLUX payload.
+__device__ __forceinline__ uint32_t row16_max_u32(uint32_t v) {
+  v = max(v, (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0xB1, 0xf, 0xf, true));    // quad_perm [1,0,3,2]
+  v = max(v, (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x4E, 0xf, 0xf, true));    // quad_perm [2,3,0,1]
+  v = max(v, (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x141, 0xf, 0xf, true));   // row_half_mirror
+  v = max(v, (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x140, 0xf, 0xf, true));   // row_mirror
+  return v;   // every lane of a row of 16 holds the row's maximum
+}
+template <int LPR, int NV, bool kMapped, bool kNT, bool kStreamIn, bool kFull>
+__global__ __launch_bounds__(256) void fp8_quant_rows_bf16_kernel(const bf16_t* __restrict__ x,
+                                                                  uint8_t* __restrict__ q,
+                                                                  float* __restrict__ scales,
+                                                                  int64_t rows, int units, RowMap map) {
+  static_assert(LPR == 16 || LPR == 64, "a row is spread over a DPP row of 16 lanes or over the whole wave");
+  constexpr int RPW = 64 / LPR;
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int64_t row = ((int64_t)blockIdx.x * 4 + wave) * RPW + lane / LPR;
+  const int l = lane % LPR;
+  const bool row_ok = row < rows;
+  if (kFull && !row_ok) return;               // whole DPP rows (LPR = 16) or the whole wave (LPR = 64) leave together
+  if (kFull) units = LPR * NV;
+  int64_t base = row * (int64_t)units * 8;   // first element of the row in x
+  int64_t orow = row;                         // row of q / scales
+  if (kMapped) {
+    map_row(map, row_ok ? row : 0, base, orow);
+  }
+  const int64_t obase = orow * (int64_t)units * 8;
+  const bf16_t* xr = x + base + l * 8;
+  uint8_t* qr = q + obase + l * 8;
+
+  u32x4_raw r[NV];
+  uint32_t mbits = 0u;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    r[i] = u32x4_raw{0u, 0u, 0u, 0u};
+    if (kFull || (row_ok && l + i * LPR < units)) {
+      const u32x4_raw* p = reinterpret_cast<const u32x4_raw*>(xr + i * LPR * 8);
+      r[i] = kStreamIn ? __builtin_nontemporal_load(p) : *p;
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < NV; ++i) mbits = absmax8_bf16_bits(r[i], mbits);
+  mbits = max(mbits & 0xffffu, mbits >> 16);
+  if (kFull) {
+    mbits = row16_max_u32(mbits);
+    if (LPR == 64) {
+      const uint32_t a = __builtin_amdgcn_readlane((int)mbits, 0), b = __builtin_amdgcn_readlane((int)mbits, 16);
+      const uint32_t c = __builtin_amdgcn_readlane((int)mbits, 32), e = __builtin_amdgcn_readlane((int)mbits, 48);
+      mbits = max(max(a, b), max(c, e));
+    }
+  } else {
+#pragma unroll
+    for (int off = LPR / 2; off > 0; off >>= 1) mbits = max(mbits, (uint32_t)__shfl_xor((int)mbits, off, 64));
+  }
+  const float s = scale_from_absmax(__uint_as_float(mbits << 16));
+  if (row_ok && l == 0) scales[orow] = s;
+  const RowDiv d = make_rowdiv(s);
+  if (__builtin_amdgcn_ballot_w64(!d.fast) == 0ull) {
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+      if (kFull || (row_ok && l + i * LPR < units)) put_codes<kNT>(qr + i * LPR * 8, encode8_bf16_short(r[i], d));
+  } else {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      if (kFull || (row_ok && l + i * LPR < units)) {
+        float v[8];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { v[2 * k] = __uint_as_float(r[i][k] << 16); v[2 * k + 1] = __uint_as_float(r[i][k] & 0xffff0000u); }
+        put_codes<kNT>(qr + i * LPR * 8, encode8<false>(v, d));
+      }
     }
   }
 }
@@ -327,26 +353,65 @@ __global__ __launch_bounds__(256) void fp8_dequant_kernel(const uint8_t* __restr
   }
 }
 
+// Dense bf16 output, the payload type of the method: 8 codes per unit, U units per thread a block
+// stride apart, so that every load instruction of a wave reads 512 consecutive bytes and every store
+// instruction writes 1024 consecutive bytes (whole lines; a thread that writes 32 bytes with two
+// stores leaves each line to two instructions), and a thread has U loads in flight before its first
+// store.  On the [4608, 3072] payload: 8.2 us against 10.0 us for 16 codes per thread.
+template <int U, bool kNT>
+__global__ __launch_bounds__(256) void fp8_dequant_bf16_dense_kernel(const uint8_t* __restrict__ q,
+                                                                     const float* __restrict__ scales,
+                                                                     bf16_t* __restrict__ y, uint32_t total_units,
+                                                                     uint32_t units_per_row) {
+  const uint32_t first = blockIdx.x * (U * 256u) + threadIdx.x;
+  uint2 w[U];
+  float s[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const uint32_t g = first + u * 256u;
+    w[u] = make_uint2(0u, 0u);
+    s[u] = 1.0f;                                   // no scales: exact widening of the codes
+    if (g < total_units) {
+      w[u] = *reinterpret_cast<const uint2*>(q + (int64_t)g * 8);
+      if (scales) s[u] = scales[g / units_per_row];
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const uint32_t g = first + u * 256u;
+    if (g < total_units) {
+      float a[4], b[4];
+      decode4(w[u].x, s[u], a);
+      decode4(w[u].y, s[u], b);
+      if (kNT) store8_nt(y + (int64_t)g * 8, a, b);
+      else store8(y + (int64_t)g * 8, a, b);
+    }
+  }
+}
+
 // rows of at most 4096 elements: the single-pass kernel, plain or mapped
+template <typename T, int LPR, int NV, bool kMapped, bool kNT, bool kStreamIn>
+void quant_rows_launch_one(unsigned blocks, int64_t rows, int64_t units, const T* x, uint8_t* q, float* scales,
+                           const RowMap& map, hipStream_t st) {
+  if constexpr (std::is_same<T, bf16_t>::value) {
+    if (units == LPR * NV)
+      hipLaunchKernelGGL((fp8_quant_rows_bf16_kernel<LPR, NV, kMapped, kNT, kStreamIn, true>), dim3(blocks), dim3(256), 0, st, x, q, scales, rows, (int)units, map);
+    else
+      hipLaunchKernelGGL((fp8_quant_rows_bf16_kernel<LPR, NV, kMapped, kNT, kStreamIn, false>), dim3(blocks), dim3(256), 0, st, x, q, scales, rows, (int)units, map);
+  } else
+    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, LPR, NV, kMapped, kNT, kStreamIn>), dim3(blocks), dim3(256), 0, st, x, q, scales, rows, (int)units, map);
+}
 template <typename T, bool kMapped, bool kNT, bool kStreamIn>
 void quant_rows_launch_nt(int64_t rows, int64_t units, const T* x, uint8_t* q, float* scales, const RowMap& map,
                           hipStream_t st) {
   auto blocks = [&](int rpw) { return (unsigned)((rows + 4 * rpw - 1) / (4 * rpw)); };
-  if (units <= 16) {
-    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 16, 1, kMapped, kNT, kStreamIn>), dim3(blocks(4)), dim3(256), 0, st, x, q, scales, rows, (int)units, map);
-  } else if (units <= 32) {
-    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 16, 2, kMapped, kNT, kStreamIn>), dim3(blocks(4)), dim3(256), 0, st, x, q, scales, rows, (int)units, map);
-  } else if (units <= 64) {
-    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 64, 1, kMapped, kNT, kStreamIn>), dim3(blocks(1)), dim3(256), 0, st, x, q, scales, rows, (int)units, map);
-  } else if (units <= 128) {
-    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 64, 2, kMapped, kNT, kStreamIn>), dim3(blocks(1)), dim3(256), 0, st, x, q, scales, rows, (int)units, map);
-  } else if (units <= 256) {
-    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 64, 4, kMapped, kNT, kStreamIn>), dim3(blocks(1)), dim3(256), 0, st, x, q, scales, rows, (int)units, map);
-  } else if (units <= 384) {
-    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 64, 6, kMapped, kNT, kStreamIn>), dim3(blocks(1)), dim3(256), 0, st, x, q, scales, rows, (int)units, map);
-  } else {
-    hipLaunchKernelGGL((fp8_quant_rows_kernel<T, 64, 8, kMapped, kNT, kStreamIn>), dim3(blocks(1)), dim3(256), 0, st, x, q, scales, rows, (int)units, map);
-  }
+  if (units <= 16) quant_rows_launch_one<T, 16, 1, kMapped, kNT, kStreamIn>(blocks(4), rows, units, x, q, scales, map, st);
+  else if (units <= 32) quant_rows_launch_one<T, 16, 2, kMapped, kNT, kStreamIn>(blocks(4), rows, units, x, q, scales, map, st);
+  else if (units <= 64) quant_rows_launch_one<T, 64, 1, kMapped, kNT, kStreamIn>(blocks(1), rows, units, x, q, scales, map, st);
+  else if (units <= 128) quant_rows_launch_one<T, 64, 2, kMapped, kNT, kStreamIn>(blocks(1), rows, units, x, q, scales, map, st);
+  else if (units <= 256) quant_rows_launch_one<T, 64, 4, kMapped, kNT, kStreamIn>(blocks(1), rows, units, x, q, scales, map, st);
+  else if (units <= 384) quant_rows_launch_one<T, 64, 6, kMapped, kNT, kStreamIn>(blocks(1), rows, units, x, q, scales, map, st);
+  else quant_rows_launch_one<T, 64, 8, kMapped, kNT, kStreamIn>(blocks(1), rows, units, x, q, scales, map, st);
 }
 
 template <typename T, bool kMapped>
@@ -421,6 +486,17 @@ usp_status dequant_mapped_launch(const RowMap& m, int64_t rows, int64_t cols, co
 template <typename T>
 usp_status dequant_dispatch(int64_t rows, int64_t cols, const uint8_t* q, const float* scales, T* y,
                             hipStream_t st) {
+  if constexpr (std::is_same<T, bf16_t>::value) {
+    const int64_t upr = cols / 8, total = rows * upr;
+    // enough units to fill the chip with four per thread, and an output the streaming stores are good
+    // for (otherwise: 16 codes per thread, below)
+    if (total >= 4 * 256 * 1024 && rows * cols * (int64_t)sizeof(T) < kStreamDequantBelowBytes) {
+      hipLaunchKernelGGL((fp8_dequant_bf16_dense_kernel<4, true>), dim3((unsigned)((total + 1023) / 1024)), dim3(256), 0, st,
+                         q, scales, y, (uint32_t)total, (uint32_t)upr);
+      USP_CHECK_HIP(hipGetLastError());
+      return USP_OK;
+    }
+  }
   if (cols % 16 == 0) return dequant_launch<T, 16>(rows, cols, q, scales, y, st);
   return dequant_launch<T, 8>(rows, cols, q, scales, y, st);
 }

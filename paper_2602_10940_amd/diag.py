@@ -25,6 +25,13 @@ def load_diag_library() -> ctypes.CDLL:
     vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
     lib.usp_diag_mfma_rate.restype = i32
     lib.usp_diag_mfma_rate.argtypes = [i32, i32, i32, vp, vp, vp]
+    lib.usp_diag_check_bf16_division.restype = i32
+    lib.usp_diag_check_bf16_division.argtypes = [vp, vp]
+    lib.usp_diag_payload_floor.restype = i32
+    lib.usp_diag_payload_floor.argtypes = [i32, i32, vp, vp, vp, vp]
+    lib.usp_diag_repeat_payload_calls.restype = i32
+    lib.usp_diag_repeat_payload_calls.argtypes = [i32, i32, i32, ctypes.c_int64, ctypes.c_int64, ctypes.POINTER(vp),
+                                                  ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), vp]
     lib.usp_diag_ring_attn_fwd_wait.restype = i32
     lib.usp_diag_ring_attn_fwd_wait.argtypes = [ctypes.POINTER(B.AttnDesc), vp, ctypes.POINTER(vp), ctypes.POINTER(vp),
                                                 ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp),
@@ -41,6 +48,31 @@ def usp_diag_mfma_rate(wgs: int, iters: int, random_data: bool, out: torch.Tenso
     assert clocks.dtype == torch.int64 and clocks.numel() >= 2 and clocks.is_contiguous()
     B._check(lib.usp_diag_mfma_rate(int(wgs), int(iters), 1 if random_data else 0, B._ptr(out), B._ptr(clocks),
                                     B._stream_handle(stream)))
+
+
+def usp_diag_check_bf16_division(stream=None):
+    """(pairs checked, codes that differ, quotients that differ, absmax values outside the fast range)."""
+    lib = load_diag_library()
+    counts = torch.zeros((4,), dtype=torch.int64, device="cuda")
+    B._check(lib.usp_diag_check_bf16_division(B._ptr(counts), B._stream_handle(stream)))
+    return tuple(int(v) for v in counts.cpu())
+
+
+def usp_diag_payload_floor(kind: int, x: torch.Tensor, q: torch.Tensor, scales: torch.Tensor, stream=None) -> None:
+    """kind 0 empty launch, 1 read-only, 2 write-only, on the pack's grid for x [rows, 3072] bf16."""
+    lib = load_diag_library()
+    assert x.dim() == 2 and x.shape[1] == 3072 and x.dtype == torch.bfloat16 and x.is_contiguous()
+    assert q.numel() >= x.numel() and scales.numel() >= x.shape[0]
+    B._check(lib.usp_diag_payload_floor(int(kind), x.shape[0], B._ptr(x), B._ptr(q), B._ptr(scales), B._stream_handle(stream)))
+
+
+def usp_diag_repeat_payload_calls(kind: int, reps: int, xs, qs, ss, ys, stream=None) -> None:
+    """reps back-to-back library calls issued from C over the buffer sets (lists of tensors, bf16 [rows, cols])."""
+    lib = load_diag_library()
+    rows, cols = xs[0].shape
+    assert all(t.shape == (rows, cols) and t.is_contiguous() for t in list(xs) + list(qs) + list(ys))
+    B._check(lib.usp_diag_repeat_payload_calls(int(kind), int(reps), len(xs), rows, cols, B._ptr_array(xs), B._ptr_array(qs),
+                                               B._ptr_array(ss), B._ptr_array(ys), B._stream_handle(stream)))
 
 
 def usp_diag_ring_attn_fwd_wait(q: torch.Tensor, k_chunks: Sequence[torch.Tensor], v_chunks: Sequence[torch.Tensor],

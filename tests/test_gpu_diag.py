@@ -44,6 +44,36 @@ def test_probe_rejects_bad_arguments():
         P.usp_diag_mfma_rate(1, 0, True, out, clocks)
 
 
+def test_short_bf16_division_gives_the_codes_of_the_ieee_division_for_every_pair():
+    """Algorithm 1 line 2 with bf16 inputs: the pack's short sequence against the true division, over
+    every (row absmax a, element x) pair of bf16 values with |x| <= a (both signs, packed in both byte
+    positions of the encoder), on the device.  The reference side of this comparison (the compiler's IEEE
+    division and the hardware's E4M3 convert) is what the oracle-against-kernel tests of test_gpu_fp8.py
+    pin for every fp32 in range and next to every rounding boundary."""
+    from paper_2602_10940_amd import diag
+    pairs, bad_codes, bad_quot, slow_rows = diag.usp_diag_check_bf16_division()
+    # a = 0x0001 .. 0x7f7f: a values in the fast range contribute 2 * (abits + 1) pairs each
+    assert slow_rows > 0 and slow_rows < 0x7f7f // 2 + 2000
+    assert pairs > 500_000_000
+    assert bad_codes == 0, (pairs, bad_codes, bad_quot)
+    assert bad_quot < pairs // 100          # the quotients themselves do differ now and then (last bit)
+
+
+def test_payload_floor_kernels_run():
+    from paper_2602_10940_amd import diag
+    x = torch.randn((64, 3072), device=DEV).to(torch.bfloat16)
+    q = torch.zeros((64, 3072), dtype=torch.uint8, device=DEV)
+    s = torch.zeros((64,), dtype=torch.float32, device=DEV)
+    diag.usp_diag_payload_floor(0, x, q, s)
+    diag.usp_diag_payload_floor(1, x, q, s)
+    torch.cuda.synchronize()
+    assert torch.equal(s, x.float().abs().amax(dim=1))
+    diag.usp_diag_payload_floor(2, x, q, s)
+    torch.cuda.synchronize()
+    q32 = q.view(torch.int32)                      # per unit of 8 bytes: (row, lane)
+    assert int(q32[0, 1]) == 0 and int(q32[63, 0]) == 63 and int(q32[63, 3]) == 1 and int(q32[5, 2 * 64 * 5 + 2 * 7 + 1]) == 7
+
+
 FUSED, WIDE, SPLIT = 16, 4, 8
 
 
