@@ -98,9 +98,9 @@ typedef enum {
  * [B,H,chunk_len[r],d] array" (the only way to describe dense chunks of unequal length).
  */
 typedef struct usp_attn_desc {
-  int32_t B, H, d;          /* B*H at most 65535.  d: a multiple of 8 up to 256.  bf16 Q with d = 128 runs on the matrix-core
-                               kernels, and so does bf16 Q with d = 64 (on copies of K and V padded to
-                               d = 128 in the workspace); every other combination on a slower general kernel */
+  int32_t B, H, d;          /* B*H at most 65535.  d: a multiple of 8 up to 256.  bf16 Q with d = 128 or d = 64 runs on the
+                               matrix-core kernels (K and V read in place); every other combination on a slower
+                               general kernel */
   int32_t Sq;               /* tokens of the local Q shard */
   int32_t n_chunks;         /* ring degree W >= 1 */
   const int32_t* chunk_len; /* HOST array [n_chunks] */
@@ -115,8 +115,8 @@ typedef struct usp_attn_desc {
 
 /*
  * Bytes of device workspace usp_ring_attn_fwd needs for this descriptor
- * (0 is possible, e.g. one f32 chunk; bf16 with d = 128 always asks for a little, about
- * 1/16 of a K chunk; bf16 with d = 64 for twice its K and V on top).  Returns (size_t)-1 if the descriptor is invalid.
+ * (0 is possible, e.g. one f32 chunk; bf16 with d = 128 or 64 always asks for a little, 1 KB per
+ * 64 keys of a head).  Returns (size_t)-1 if the descriptor is invalid.
  */
 size_t usp_ring_attn_workspace_bytes(const usp_attn_desc* desc);
 
@@ -133,13 +133,11 @@ size_t usp_ring_attn_workspace_bytes(const usp_attn_desc* desc);
  *   v_chunks   same for V.  With USP_ATTN_DOUBLE_BUFFER or USP_ATTN_FUSED_PREFETCH the chunks
  *              after the first (and their scales) are only read by the transfers, so they may
  *              also sit in pinned host memory that the device can address (hipHostMalloc): the
- *              transfers then cross the host link, which stands in for a slow ring link.  (Not with
- *              bf16 Q and d = 64: every chunk is first padded to d = 128 by a kernel on
- *              compute_stream, which reads it where it is.)
+ *              transfers then cross the host link, which stands in for a slow ring link.
  *   k_scales / v_scales   NULL unless kv_dtype is FP8: HOST arrays of device pointers,
  *              chunk r -> float [B,H,chunk_len[r]] dense, one scale per (b,h,token)
  *              (value = code * scale, as produced by usp_fp8_quant on the
- *              [B*H*chunk_len, d] view when the chunk is dense).  With bf16 Q and d = 128
+ *              [B*H*chunk_len, d] view when the chunk is dense).  With bf16 Q and d = 128 or 64
  *              K enters exactly (codes, scale applied to the fp32 scores) and V as
  *              bf16(code * scale); otherwise both products are taken in fp32.
  *   key_mask   NULL, or HOST array of n_chunks device pointers (entries may be NULL):

@@ -15,8 +15,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ_DIR = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libusp.so")
 
-SOURCES = ["usp_api.hip", "fp8_kernels.hip", "merge_kernel.hip", "attn_generic.hip", "attn_mfma.hip",
-           "layout_kernels.hip"]
+SOURCES = ["usp_api.hip", "fp8_kernels.hip", "merge_kernel.hip", "attn_generic.hip", "attn_mfma.hip"]
 # libusp_diag.so: the MFMA-rate probe of the benchmark and a test hook, outside the library's ABI
 DIAG_LIB = os.path.join(PKG, "libusp_diag.so")
 DIAG_SOURCES = [os.path.join("diag", "usp_diag.hip")]

@@ -99,13 +99,14 @@ __device__ __forceinline__ void finish_and_store_direct(const AttnStep& s, f32x1
   }
   if (invalid) { c_cur = __builtin_nanf(""); lse_new = c_cur; }
   if (!valid) return;
-  float* accp = s.acc ? s.acc + row * kD : nullptr;
+  float* accp = s.acc ? s.acc + row * (s.half_d ? 64 : kD) : nullptr;   // half_d: 64-wide rows everywhere
   bf16_t* outp = (bf16_t*)s.out + b * s.os[0] + h * s.os[1] + (int64_t)qi * s.os[2];
 #pragma unroll
   for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
     for (int i4 = 0; i4 < 4; ++i4) {
       const int dcol = 32 * dt + 8 * i4 + 4 * g;
+      if (s.half_d && dt >= 2) continue;   // half_d: rows are 64 wide
       float o[4];
 #pragma unroll
       for (int e = 0; e < 4; ++e) o[e] = oacc[dt][4 * i4 + e] * c_cur;
@@ -116,7 +117,7 @@ __device__ __forceinline__ void finish_and_store_direct(const AttnStep& s, f32x1
       }
       if (s.mode == 1 || s.mode == 2)
         *reinterpret_cast<float4*>(accp + dcol) = make_float4(o[0], o[1], o[2], o[3]);
-      else if (!s.half_d || dt < 2)   // half_d: the output rows are 64 wide (columns 64..127 are zero)
+      else
         *reinterpret_cast<uint2*>(outp + dcol) = make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
     }
   if (g == 0) s.lse[row] = lse_new;
@@ -167,29 +168,28 @@ __device__ __forceinline__ void finish_and_store(const AttnStep& s, f32x16 (&oac
   // rows: lane (r2, c) handles head dims 4c .. 4c+3 of rows 2*it + r2
   const int r2 = lane >> 5, c = lane & 31;
   const int rows_valid = min(kQPerWave, s.Sq - q0);       // <= 0: nothing to store
+  const int accP = s.half_d ? 64 : kD;                    // floats per row of the carried O
 #pragma unroll 4
   for (int it = 0; it < kQPerWave / 2; ++it) {
     const int r = 2 * it + r2;
-    if (r >= rows_valid) continue;
+    if (r >= rows_valid || (s.half_d && c >= 16)) continue;   // half_d: rows are 64 wide
     const f32x4 v = *reinterpret_cast<const f32x4*>(epi + r * kEpiPitch + c * 16);
     const float cc = info[2 * r], wp = info[2 * r + 1];
     float o[4] = {v[0] * cc, v[1] * cc, v[2] * cc, v[3] * cc};
     const int64_t row = row0 + q0 + r;
     if (s.mode >= 2) {
-      const float4 p = *reinterpret_cast<const float4*>(s.acc + row * kD + 4 * c);
+      const float4 p = *reinterpret_cast<const float4*>(s.acc + row * accP + 4 * c);
       o[0] = fmaf(wp, p.x, o[0]); o[1] = fmaf(wp, p.y, o[1]);
       o[2] = fmaf(wp, p.z, o[2]); o[3] = fmaf(wp, p.w, o[3]);
     }
     if (s.mode == 1 || s.mode == 2)
-      *reinterpret_cast<float4*>(s.acc + row * kD + 4 * c) = make_float4(o[0], o[1], o[2], o[3]);
+      *reinterpret_cast<float4*>(s.acc + row * accP + 4 * c) = make_float4(o[0], o[1], o[2], o[3]);
     else {
       bf16_t* outp = (bf16_t*)s.out + b * s.os[0] + h * s.os[1] + (int64_t)(q0 + r) * s.os[2];
       // the final output is not read again here: a streaming store leaves no dirty line for the
       // end of the kernel to write back (the fp32 carry above is re-read by the next step and stays cached)
-      if (!s.half_d || c < 16) {   // half_d: the output rows are 64 wide (columns 64..127 are zero)
-        const u32x2 v = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
-        __builtin_nontemporal_store(v, reinterpret_cast<u32x2*>(outp + 4 * c));
-      }
+      const u32x2 v = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
+      __builtin_nontemporal_store(v, reinterpret_cast<u32x2*>(outp + 4 * c));
     }
   }
 }
@@ -413,17 +413,24 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
   // rows 8w..8w+7 of every tile.  split: only the group in its softmax phase loads, wave w its own
   // rows 8w..8w+7 and those of its partner w^4, 32 rows away (same swizzle: 32 is a multiple of
   // 16).  Per-lane byte offsets inside a tile are fixed; the tile base pointers advance as scalars.
-  const int dma_r0 = 8 * wave + (lane >> 4), dma_r1 = dma_r0 + 4;
-  const int dma_p = lane & 15;
+  // kHalfD (head dimension 64): rows are 128 bytes in global memory and in LDS, so one instruction moves
+  // 8 rows (8 lanes each) and a wave's share of a tile is a single load per tensor; the swizzles are
+  //   K: piece c (of 8) of key r sits at piece c ^ ((r >> 1) & 7)   (two rows share a sweep of the banks)
+  //   V: the 64-byte half h of key r sits at half h ^ ((r >> 1) & 1)
+  constexpr int RB = kHalfD ? 128 : kRowB;   // bytes per K / V row in LDS
+  const int dma_r0 = 8 * wave + (kHalfD ? (lane >> 3) : (lane >> 4)), dma_r1 = dma_r0 + 4;
+  const int dma_p = kHalfD ? (lane & 7) : (lane & 15);
   const uint32_t rowB = (uint32_t)(s.ks[2] * 2);   // bytes between keys in global memory
   const int64_t tileB = (int64_t)kTile * rowB;
-  const uint32_t ksw0 = (dma_p ^ (dma_r0 & 15)) << 4, ksw1 = (dma_p ^ (dma_r1 & 15)) << 4;
-  const uint32_t vsw = (dma_p ^ ((dma_r0 & 3) << 2)) << 4;   // (r0 + 4) & 3 == r0 & 3
+  const uint32_t ksw0 = kHalfD ? (uint32_t)((dma_p ^ ((dma_r0 >> 1) & 7)) << 4) : (uint32_t)((dma_p ^ (dma_r0 & 15)) << 4);
+  const uint32_t ksw1 = (dma_p ^ (dma_r1 & 15)) << 4;
+  const uint32_t vsw = kHalfD ? (uint32_t)((dma_p ^ (((dma_r0 >> 1) & 1) << 2)) << 4)
+                              : (uint32_t)((dma_p ^ ((dma_r0 & 3) << 2)) << 4);   // (r0 + 4) & 3 == r0 & 3
   const uint32_t kg0 = dma_r0 * rowB + ksw0, kg1 = dma_r1 * rowB + ksw1;
   const uint32_t vg0 = dma_r0 * rowB + vsw, vg1 = dma_r1 * rowB + vsw;
   const uint32_t lds_base = (uint32_t)(uintptr_t)smem_raw;
-  const uint32_t lds_k = __builtin_amdgcn_readfirstlane(lds_base + 8 * wave * kRowB);
-  const uint32_t lds_v = __builtin_amdgcn_readfirstlane(lds_base + kStages * kTileB + 8 * wave * kRowB);
+  const uint32_t lds_k = __builtin_amdgcn_readfirstlane(lds_base + 8 * wave * RB);
+  const uint32_t lds_v = __builtin_amdgcn_readfirstlane(lds_base + kStages * kTileB + 8 * wave * RB);
   const int pair_rows = kSplit ? (grpA ? 32 : -32) : 0;
   // rows past the end of a ragged last tile re-read its last valid row (finite data; their P is 0)
   auto row_off = [&](int r, int tile_idx) -> uint32_t {
@@ -431,18 +438,20 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
     return (uint32_t)r * rowB;
   };
   auto issue_k_half = [&](const unsigned char* tile, int tile_idx, int stage, int half, bool pair) {
+    if (kHalfD && half) return;               // one load covers the wave's 8 rows
     const int dr = pair ? pair_rows : 0;
     uint32_t off = half ? kg1 : kg0;
     if (kExt && tile_idx == tail_tile) { off = row_off((half ? dma_r1 : dma_r0) + dr, tile_idx) + (half ? ksw1 : ksw0); }
     else tile += (int64_t)dr * rowB;
-    lds_dma16(tile, off, lds_k + dr * kRowB + stage * kTileB + half * 4 * kRowB);
+    lds_dma16(tile, off, lds_k + dr * RB + stage * kTileB + half * 4 * RB);
   };
   auto issue_v_half = [&](const unsigned char* tile, int tile_idx, int stage, int half, bool pair) {
+    if (kHalfD && half) return;
     const int dr = pair ? pair_rows : 0;
     uint32_t off = half ? vg1 : vg0;
     if (kExt && tile_idx == tail_tile) { off = row_off((half ? dma_r1 : dma_r0) + dr, tile_idx) + vsw; }
     else tile += (int64_t)dr * rowB;
-    lds_dma16(tile, off, lds_v + dr * kRowB + stage * kTileB + half * 4 * kRowB);
+    lds_dma16(tile, off, lds_v + dr * RB + stage * kTileB + half * 4 * RB);
   };
   // extended path: the four 64-float vectors of a tile's record, one per wave of the loading group
   const unsigned char* extb = kExt ? (const unsigned char*)(s.ext + (int64_t)bh_ * nt_all * (kExtTileB / 4)) : nullptr;
@@ -557,17 +566,28 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
   typedef const __attribute__((address_space(3))) unsigned char* lds_cptr;
   lds_cptr k_rd[8], v_rd[4];
   {
-    const int k_rd_row = n * kRowB;
-    const int k_rd_x = (g ^ (n & 15)) << 4;
     const int tr_i = (lane >> 2) & 3, tr_cc = lane & 3, tr_dh = (lane >> 4) & 1;
-    const int v_rd_row = (4 * g + tr_i) * kRowB + ((2 * tr_dh + (tr_cc >> 1)) << 4) + 8 * (tr_cc & 1);
-    const int v_rd_x = tr_i << 6;
+    if (!kHalfD) {
+      const int k_rd_row = n * RB;
+      const int k_rd_x = (g ^ (n & 15)) << 4;
+      const int v_rd_row = (4 * g + tr_i) * RB + ((2 * tr_dh + (tr_cc >> 1)) << 4) + 8 * (tr_cc & 1);
+      const int v_rd_x = tr_i << 6;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks)
-      k_rd[ks] = (lds_cptr)(uintptr_t)(lds_base + k_rd_row + ((32 * ks) ^ k_rd_x));
+      for (int ks = 0; ks < 8; ++ks)
+        k_rd[ks] = (lds_cptr)(uintptr_t)(lds_base + k_rd_row + ((32 * ks) ^ k_rd_x));
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-      v_rd[dt] = (lds_cptr)(uintptr_t)(lds_base + kStages * kTileB + v_rd_row + ((dt << 6) ^ v_rd_x));
+      for (int dt = 0; dt < 4; ++dt)
+        v_rd[dt] = (lds_cptr)(uintptr_t)(lds_base + kStages * kTileB + v_rd_row + ((dt << 6) ^ v_rd_x));
+    } else {
+      // 128-byte rows: K piece 2*ks + g of key n; V bytes 64*dt + 32*tr_dh + 8*tr_cc of key 4*g + tr_i
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks)
+        k_rd[ks] = (lds_cptr)(uintptr_t)(lds_base + n * RB + ((((2 * ks + g) & 7) ^ ((n >> 1) & 7)) << 4));
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+        v_rd[dt] = (lds_cptr)(uintptr_t)(lds_base + kStages * kTileB + (4 * g + tr_i) * RB +
+                                         ((((dt & 1) << 6) + 32 * tr_dh + 8 * tr_cc) ^ (((tr_i >> 1) & 1) << 6)));
+    }
   }
   // extended path: this lane's keys of a tile are rows 32*kt + 8*a + 4*g + (0..3), a = 0..3
   const lds_cptr x_rd = (lds_cptr)(uintptr_t)(lds_ext + 16 * g);
@@ -577,7 +597,7 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
 #pragma unroll
     for (int ks = ks_lo; ks < ks_lo + 4; ++ks) {
       const bf16x8 a = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(
-          k_rd[ks] + stage * kTileB + 32 * kt * kRowB);
+          k_rd[ks] + stage * kTileB + 32 * kt * RB);
       sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], sacc[kt], 0, 0, 0);
     }
   };
@@ -588,13 +608,13 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
   // The order is written out and pinned (sched_barrier after every MFMA and the reads issued behind
   // it) rather than left to the instruction scheduler, whose choice changes with the code around it.
   auto v_operand = [&](int stage, int blk, int dt) -> bf16x8 {
-    const u32x2 lo = lds_read_tr3(v_rd[dt] + stage * kTileB + 16 * blk * kRowB);
-    const u32x2 hi = lds_read_tr3(v_rd[dt] + stage * kTileB + (16 * blk + 8) * kRowB);
+    const u32x2 lo = lds_read_tr3(v_rd[dt] + stage * kTileB + 16 * blk * RB);
+    const u32x2 hi = lds_read_tr3(v_rd[dt] + stage * kTileB + (16 * blk + 8) * RB);
     return __builtin_bit_cast(bf16x8, u32x4{lo[0], lo[1], hi[0], hi[1]});
   };
   auto k_operand = [&](int stage, int blk, int i) -> bf16x8 {   // block blk: keys 32 * (blk >> 1) .., head dims 64 * (blk & 1) + 16 * i ..
     return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(
-        k_rd[4 * (blk & 1) + i] + stage * kTileB + 32 * (blk >> 1) * kRowB);
+        k_rd[4 * (blk & 1) + i] + stage * kTileB + 32 * (blk >> 1) * RB);
   };
   constexpr int kDT = kHalfD ? 2 : 4;   // 32-wide slices of the head dimension that P.V produces
   auto MM_full = [&](int sv, int sk) {
@@ -916,8 +936,9 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
     auto phase_barrier = [&](int wait_mode, bool needed = true) {   // 0: no wait, 1: all but the last full batch, 2: vmcnt(0)
       __builtin_amdgcn_sched_barrier(0);
       if (wait_mode == 1) {
-        if (kExt && grpA) __builtin_amdgcn_s_waitcnt(0x0F75);   // vmcnt(5)
-        else __builtin_amdgcn_s_waitcnt(0x0F74);                // vmcnt(4)
+        // a full batch is 4 loads (2 with 128-byte rows), plus the record's in the group that loads it
+        if (kExt && grpA) __builtin_amdgcn_s_waitcnt(kHalfD ? 0x0F73 : 0x0F75);   // vmcnt(3) / vmcnt(5)
+        else __builtin_amdgcn_s_waitcnt(kHalfD ? 0x0F72 : 0x0F74);                // vmcnt(2) / vmcnt(4)
       } else if (wait_mode == 2) __builtin_amdgcn_s_waitcnt(0x0F70);
       if (needed) __builtin_amdgcn_s_barrier();
       __builtin_amdgcn_sched_barrier(0);
@@ -1098,7 +1119,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_pp_mixed_kernel(AttnStep s) 
 }  // namespace
 
 bool attn_mfma_supported(const AttnStep& s) {
-  return s.qo_dtype == USP_BF16 && s.kv_dtype == USP_BF16 && s.d == kD && s.Sq > 0;
+  return s.qo_dtype == USP_BF16 && s.kv_dtype == USP_BF16 && (s.d == kD || (s.d == 64 && s.half_d)) && s.Sq > 0;
 }
 
 size_t attn_mfma_ext_bytes(int B, int H, int Sc) {
@@ -1123,7 +1144,7 @@ usp_status launch_attn_fp8_chunk_prepare(const AttnStep& s, int c, bool reset_ar
     set_error("FP8 chunk preparation needs a step over several FP8 chunks with its records");
     return USP_ERR_INVALID_ARG;
   }
-  const int64_t units = (int64_t)s.B * s.H * s.chunk[c].Sc * 8;      // 16 codes each
+  const int64_t units = (int64_t)s.B * s.H * s.chunk[c].Sc * (s.d / 16);   // 16 codes each
   const int64_t blocks = (units + 255) / 256;                          // one unit per thread while the chunk is small
   hipLaunchKernelGGL(attn_fp8_chunk_prepare_kernel, dim3((unsigned)(blocks < 1 ? 1 : blocks > 8192 ? 8192 : blocks)), dim3(256),
                      0, st, s, c, reset_arrive ? 1 : 0);

@@ -93,7 +93,8 @@ __device__ __forceinline__ void fp8_chunk_prepare(const AttnStep& s, int c, int6
     if (i < c) tile0 += s.chunk[i].Sc / 64;
     nt_total += s.chunk[i].Sc / 64;
   }
-  const int64_t rows = (int64_t)s.B * s.H * ch.Sc;      // (head, token) rows of 128 codes
+  const int64_t rows = (int64_t)s.B * s.H * ch.Sc;      // (head, token) rows of d = 128 or 64 codes
+  const int ush = s.d == 64 ? 2 : 3;                    // log2 of the 16-code units per row
   const uint4* kc = (const uint4*)ch.k_src;
   const uint4* vc = (const uint4*)ch.v_src;
   uint4* kd = (uint4*)ch.k;
@@ -104,16 +105,16 @@ __device__ __forceinline__ void fp8_chunk_prepare(const AttnStep& s, int c, int6
     put16<kDeviceScope>(vd + 2 * u, decode8_bf16(b.x, b.y, vs));
     put16<kDeviceScope>(vd + 2 * u + 1, decode8_bf16(b.z, b.w, vs));
   };
-  const int64_t units = rows * 8;
+  const int64_t units = rows << ush;
   int64_t u = first;
   for (; u + 3 * stride < units; u += 4 * stride) {     // the loads of four units in flight per lane
     const uint4 a0 = kc[u], b0 = vc[u], a1 = kc[u + stride], b1 = vc[u + stride];
     const uint4 a2 = kc[u + 2 * stride], b2 = vc[u + 2 * stride], a3 = kc[u + 3 * stride], b3 = vc[u + 3 * stride];
-    const float s0 = ch.v_scale_src[u >> 3], s1 = ch.v_scale_src[(u + stride) >> 3];
-    const float s2 = ch.v_scale_src[(u + 2 * stride) >> 3], s3 = ch.v_scale_src[(u + 3 * stride) >> 3];
+    const float s0 = ch.v_scale_src[u >> ush], s1 = ch.v_scale_src[(u + stride) >> ush];
+    const float s2 = ch.v_scale_src[(u + 2 * stride) >> ush], s3 = ch.v_scale_src[(u + 3 * stride) >> ush];
     emit(u, a0, b0, s0); emit(u + stride, a1, b1, s1); emit(u + 2 * stride, a2, b2, s2); emit(u + 3 * stride, a3, b3, s3);
   }
-  for (; u < units; u += stride) emit(u, kc[u], vc[u], ch.v_scale_src[u >> 3]);
+  for (; u < units; u += stride) emit(u, kc[u], vc[u], ch.v_scale_src[u >> ush]);
   const float scale2 = s.scale * 1.44269504088896340736f;
   const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
   for (int64_t u = first; u < rows / 4; u += stride) {  // chunk lengths are multiples of 64

@@ -70,10 +70,6 @@ struct Plan {
   bool ext = false;
   bool multi_rec = false;               // room for the records of a one-launch ring over bf16 chunks with key masks
   size_t off_multi_rec = 0;
-  // bf16 with d = 64: zero-padded to d = 128 copies in the workspace (Q, O, K | V of every chunk),
-  // then the d = 128 path on those with a workspace of its own behind them
-  bool pad64 = false;
-  size_t off_pad_o = 0, off_pad_kv = 0, off_pad_inner = 0, inner_total = 0;
   size_t total = 0;
 };
 
@@ -90,25 +86,7 @@ bool o_dense(const usp_attn_desc* d) {
          d->o_stride[0] == (int64_t)d->H * d->Sq * d->d;
 }
 
-// The descriptor of the d = 128 call that stands in for a bf16 d = 64 call: dense padded K/V chunks,
-// the scale of the original head dimension.  Q and O stay where they are, 64 wide (the kernels read
-// and write only those columns when AttnStep::half_d is set); only with the merge as a separate
-// kernel, which works on dense 128-wide rows, O goes through a padded copy (padded_o).
-bool padded_o(const usp_attn_desc* d) { return (d->flags & USP_ATTN_UNFUSED_MERGE) != 0 && d->n_chunks > 1; }
-usp_attn_desc padded_desc(const usp_attn_desc* d) {
-  usp_attn_desc in = *d;
-  in.d = 128;
-  const int64_t dense[3] = {(int64_t)d->H * d->Sq * 128, (int64_t)d->Sq * 128, 128};
-  for (int i = 0; i < 3; ++i) {
-    if (padded_o(d)) in.o_stride[i] = dense[i];
-    in.kv_stride[i] = 0;
-  }
-  in.softmax_scale = d->softmax_scale > 0.0f ? d->softmax_scale : 0.125f;   // 1 / sqrt(64)
-  return in;
-}
-
-// half_d: the descriptor is the d = 128 stand-in of a bf16 d = 64 call (CallOptions::half_d)
-usp_status make_plan(const usp_attn_desc* d, Plan* p, bool half_d = false) {
+usp_status make_plan(const usp_attn_desc* d, Plan* p) {
   USP_CHECK_ARG(d != nullptr, "desc is NULL");
   USP_CHECK_ARG(d->B > 0 && d->H > 0 && d->Sq > 0, "B, H, Sq must be positive (B=%d H=%d Sq=%d)", d->B, d->H, d->Sq);
   USP_CHECK_ARG(d->d > 0 && d->d % 8 == 0 && d->d <= 256, "d must be a multiple of 8 in [8, 256] (got %d)", d->d);
@@ -127,11 +105,8 @@ usp_status make_plan(const usp_attn_desc* d, Plan* p, bool half_d = false) {
     const int64_t kal = d->kv_dtype == USP_F32 ? 4 : d->kv_dtype == USP_BF16 ? 8 : 16;
     USP_CHECK_ARG(d->kv_stride[i] >= 0 && d->kv_stride[i] % kal == 0, "kv_stride[%d]=%lld must be a non-negative multiple of %lld", i, (long long)d->kv_stride[i], (long long)kal);
   }
-  {
-    const int qo_cols = half_d ? 64 : d->d;   // inside the stand-in call for d = 64, Q and O rows are 64 wide
-    USP_CHECK_ARG(d->q_stride[2] >= qo_cols && d->o_stride[2] >= qo_cols && (kv_auto(d) || d->kv_stride[2] >= d->d),
-                  "token strides must be >= d");
-  }
+  USP_CHECK_ARG(d->q_stride[2] >= d->d && d->o_stride[2] >= d->d && (kv_auto(d) || d->kv_stride[2] >= d->d),
+                "token strides must be >= d");
   p->W = d->n_chunks;
   p->max_len = 0;
   for (int r = 0; r < p->W; ++r) {
@@ -145,27 +120,10 @@ usp_status make_plan(const usp_attn_desc* d, Plan* p, bool half_d = false) {
   p->fp8 = d->kv_dtype == USP_FP8_E4M3FN;
   USP_CHECK_ARG(!((d->flags & USP_ATTN_DOUBLE_BUFFER) && (d->flags & USP_ATTN_FUSED_PREFETCH)),
                 "USP_ATTN_DOUBLE_BUFFER and USP_ATTN_FUSED_PREFETCH exclude each other");
-  p->pad64 = d->qo_dtype == USP_BF16 && (d->kv_dtype == USP_BF16 || d->kv_dtype == USP_FP8_E4M3FN) && d->d == 64;
-  if (p->pad64) {
-    const usp_attn_desc in = padded_desc(d);
-    Plan ip;
-    const usp_status st = make_plan(&in, &ip, true);
-    if (st != USP_OK) return st;
-    p->rows_q = (size_t)d->B * d->H * d->Sq;
-    size_t off = 0;
-    if (padded_o(d)) { p->off_pad_o = off; off += align_up(p->rows_q * 128 * 2); }
-    p->off_pad_kv = off;
-    for (int r = 0; r < p->W; ++r) off += 2 * align_up((size_t)d->B * d->H * d->chunk_len[r] * 128 * elt_size(d->kv_dtype));
-    p->off_pad_inner = off; off += ip.total;
-    p->inner_total = ip.total;
-    p->total = off;
-    p->valid = true;
-    return USP_OK;
-  }
   p->dbuf = (d->flags & (USP_ATTN_DOUBLE_BUFFER | USP_ATTN_FUSED_PREFETCH)) != 0 && p->W > 1;
   p->fused_pf = p->dbuf && (d->flags & USP_ATTN_FUSED_PREFETCH) != 0;
   p->unfused = (d->flags & USP_ATTN_UNFUSED_MERGE) != 0 && p->W > 1;
-  p->mfma = d->qo_dtype == USP_BF16 && d->d == 128;
+  p->mfma = d->qo_dtype == USP_BF16 && (d->d == 128 || d->d == 64);   // the matrix-core kernels: 256- or 128-byte K / V rows
   p->dequant_stage = p->fp8 && p->mfma;
   if (p->fp8 || p->dbuf) {
     for (int r = 0; r < p->W; ++r)
@@ -455,7 +413,7 @@ usp_status usp::ring_attn_fwd_impl(const usp_attn_desc* desc, const void* q, con
                                    float* lse, void* workspace, size_t workspace_bytes, void* compute_stream,
                                    void* copy_stream, const CallOptions& opt) {
   Plan p;
-  usp_status st = make_plan(desc, &p, opt.half_d);
+  usp_status st = make_plan(desc, &p);
   if (st != USP_OK) return st;
   USP_CHECK_ARG(q && out && lse && k_chunks && v_chunks, "q, out, lse, k_chunks or v_chunks is NULL");
   USP_CHECK_ARG(aligned16(q) && aligned16(out), "q and out must be 16-byte aligned");
@@ -479,30 +437,6 @@ usp_status usp::ring_attn_fwd_impl(const usp_attn_desc* desc, const void* q, con
 
   char* ws = (char*)workspace;
   const int d = desc->d;
-  if (p.pad64) {
-    const usp_attn_desc in = padded_desc(desc);
-    const bool pad_o = padded_o(desc);
-    std::vector<const void*> kp(p.W), vp(p.W);
-    size_t off = p.off_pad_kv;
-    for (int r = 0; r < p.W; ++r) {
-      const int len = desc->chunk_len[r];
-      const int kv_es = (int)elt_size(desc->kv_dtype);
-      const size_t bytes = align_up((size_t)desc->B * desc->H * len * 128 * kv_es);
-      kp[r] = ws + off; vp[r] = ws + off + bytes;
-      if (len > 0) {
-        const int64_t dense[3] = {(int64_t)desc->H * len * 64, (int64_t)len * 64, 64};
-        const int64_t* ks = kv_auto(desc) ? dense : desc->kv_stride;
-        if ((st = launch_pad64(k_chunks[r], ws + off, v_chunks[r], ws + off + bytes, desc->B, desc->H, len, ks, kv_es, cs)) != USP_OK) return st;
-      }
-      off += 2 * bytes;
-    }
-    CallOptions inner = opt;
-    inner.half_d = true;
-    st = ring_attn_fwd_impl(&in, q, kp.data(), vp.data(), k_scales, v_scales, key_mask, pad_o ? (void*)(ws + p.off_pad_o) : out, lse,
-                            p.inner_total ? ws + p.off_pad_inner : nullptr, p.inner_total, compute_stream, copy_stream, inner);
-    if (st != USP_OK || !pad_o) return st;
-    return launch_unpad64(ws + p.off_pad_o, out, desc->B, desc->H, desc->Sq, desc->o_stride, cs);
-  }
   const float scale = desc->softmax_scale > 0.0f ? desc->softmax_scale : 1.0f / sqrtf((float)d);
   const size_t kv_es = elt_size(desc->kv_dtype);
 
@@ -581,7 +515,7 @@ usp_status usp::ring_attn_fwd_impl(const usp_attn_desc* desc, const void* q, con
       AttnStep a;
       memset(&a, 0, sizeof(a));
       a.B = desc->B; a.H = desc->H; a.d = d; a.Sq = desc->Sq;
-      a.qo_dtype = desc->qo_dtype; a.half_d = opt.half_d ? 1 : 0; a.kv_dtype = desc->kv_dtype;
+      a.qo_dtype = desc->qo_dtype; a.half_d = d == 64 ? 1 : 0; a.kv_dtype = desc->kv_dtype;
       a.q = q; a.out = out; a.lse = lse; a.scale = scale; a.mode = 0;
       for (int i = 0; i < 3; ++i) { a.qs[i] = desc->q_stride[i]; a.ks[i] = desc->kv_stride[i]; a.os[i] = desc->o_stride[i]; }
       if (kv_auto(desc)) a.ks[2] = d;
@@ -627,7 +561,7 @@ usp_status usp::ring_attn_fwd_impl(const usp_attn_desc* desc, const void* q, con
       AttnStep a;
       memset(&a, 0, sizeof(a));
       a.B = desc->B; a.H = desc->H; a.d = d; a.Sq = desc->Sq;
-      a.qo_dtype = desc->qo_dtype; a.half_d = opt.half_d ? 1 : 0; a.kv_dtype = USP_BF16;   // what the attention work-groups read
+      a.qo_dtype = desc->qo_dtype; a.half_d = d == 64 ? 1 : 0; a.kv_dtype = USP_BF16;   // what the attention work-groups read
       a.q = q; a.out = out; a.lse = lse; a.scale = scale; a.mode = 0;
       for (int i = 0; i < 3; ++i) { a.qs[i] = desc->q_stride[i]; a.os[i] = desc->o_stride[i]; }
       a.ks[2] = d;
@@ -683,7 +617,7 @@ usp_status usp::ring_attn_fwd_impl(const usp_attn_desc* desc, const void* q, con
     AttnStep a;
     memset(&a, 0, sizeof(a));
     a.B = desc->B; a.H = desc->H; a.d = d; a.Sq = desc->Sq; a.Sc = len;
-    a.qo_dtype = desc->qo_dtype; a.half_d = opt.half_d ? 1 : 0; a.kv_dtype = desc->kv_dtype;
+    a.qo_dtype = desc->qo_dtype; a.half_d = d == 64 ? 1 : 0; a.kv_dtype = desc->kv_dtype;
     a.q = q; a.k = kp; a.v = vp; a.k_scale = ksp; a.v_scale = vsp;
     a.key_mask = key_mask ? key_mask[r] : nullptr;
     for (int i = 0; i < 3; ++i) { a.qs[i] = desc->q_stride[i]; a.ks[i] = desc->kv_stride[i]; a.os[i] = desc->o_stride[i]; }

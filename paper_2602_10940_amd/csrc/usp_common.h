@@ -91,8 +91,8 @@ struct AttnStep {
   int mode;
   int variant;               // matrix-core kernels: 0 = pick by grid size, 1 = 256-query work-groups, 2 = key-split, 4 = mixed
   int mix_halves;            // mixed launch: blocks per XCD run as two key-split halves (set by the launcher)
-  int half_d;                // matrix-core kernels: d = 64 held as d = 128: columns 64..127 of K and V are zero, the
-                             // rows of Q and of `out` are 64 wide (acc stays 128 wide)
+  int half_d;                // matrix-core kernels: d = 64: the rows of Q, K, V, `out` and acc are 64 wide (128 bytes), the kernels
+                             // run their head-dimension loops over half the slices
   float* acc;                // fp32 [B,H,Sq,d] dense carried O (modes 1-3)
   void* out;                 // qo_dtype by os strides (modes 0, 3)
   float* lse;                // fp32 [B,H,Sq] dense
@@ -167,11 +167,6 @@ usp_status launch_attn_arrive_reset(int* arrive, hipStream_t st);
 // per-tile records (AttnStep::ext, [B*H][tiles in ring order]) of a step over several bf16 chunks some of
 // which have a key mask (Chunk::mask_src, multi_masked); precedes the attention launch on the stream
 usp_status launch_attn_multi_records(const AttnStep& s, hipStream_t st);
-// [B,H,S,64] (bf16: elt_bytes 2, E4M3 codes: 1) by (B,H,token) strides in elements <-> dense [B,H,S,128]
-// with zero columns 64..127
-usp_status launch_pad64(const void* k_src, void* k_dst, const void* v_src, void* v_dst, int B, int H, int S,
-                        const int64_t stride[3], int elt_bytes, hipStream_t st);   // K and V of one chunk in one launch
-usp_status launch_unpad64(const void* src, void* dst, int B, int H, int S, const int64_t stride[3], hipStream_t st);
 // chunk c of a step over several FP8 chunks decoded by a launch of its own; reset_arrive: the same
 // launch zeroes the arrival counters (it precedes the attention launch on the stream)
 usp_status launch_attn_fp8_chunk_prepare(const AttnStep& s, int c, bool reset_arrive, hipStream_t st);
@@ -179,8 +174,6 @@ usp_status launch_attn_fp8_chunk_prepare(const AttnStep& s, int c, bool reset_ar
 
 // What usp_ring_attn_fwd does, with the knobs the ABI does not carry.
 struct CallOptions {
-  bool half_d = false;        // the d = 128 call stands in for a bf16 d = 64 call: columns 64..127 of K and V are
-                              // zero padding, Q and O rows are 64 wide (the matrix-core kernels skip the MFMAs on zeros)
   int arrive_need_extra = 0;  // see AttnStep (tests of the give-up path only)
   int arrive_polls = 0;
 };

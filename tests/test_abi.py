@@ -119,10 +119,10 @@ def test_workspace_sizes_and_descriptor_checks():
     assert b.usp_ring_attn_workspace_bytes(d) == fp8 + one_launch
     d.n_chunks = 1; d.flags = 0; d.kv_dtype = b.USP_BF16
     assert b.usp_ring_attn_workspace_bytes(d) == recs
-    d.d = 64                              # bf16 d = 64: zero-padded K | V, then the d = 128 call's own
+    d.d = 64                              # bf16 d = 64 runs on the matrix-core kernels in place: nothing but the records
     for i, s in enumerate((24 * 1152 * 64, 1152 * 64, 64)):
         d.q_stride[i] = d.o_stride[i] = s
-    assert b.usp_ring_attn_workspace_bytes(d) == 2 * rows * 128 * 2 + recs
+    assert b.usp_ring_attn_workspace_bytes(d) == recs
     d.qo_dtype = d.kv_dtype = b.USP_F32                                    # generic kernel: nothing
     for i, s in enumerate((24 * 1152 * 64, 1152 * 64, 64)):
         d.q_stride[i] = d.o_stride[i] = s
