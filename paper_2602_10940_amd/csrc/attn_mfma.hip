@@ -1,16 +1,22 @@
-// bf16 MFMA attention step for gfx950 (head dimension 128): for one KV chunk,
+// bf16 MFMA attention step for gfx950 (head dimension 128 or 64): for one KV chunk,
 //   O_r = softmax(Q K^T * scale) V,   lse_r = log sum_j exp(q.k_j * scale)
 // (FastUSP section 2.2 and 2.2.2), with the carried (O, lse) of earlier chunks folded in
 // by the merge equations of section 3.4 in the epilogue.
 //
-// Shape of the computation (all choices are for 64-wide wavefronts and the 32x32x16 bf16
-// MFMA, whose operands hold 8 consecutive contraction-index values per lane):
-//   * A work-group owns 256 queries of one (batch, head); each of its 8 waves owns 32.
+// Shape of the computation (all choices are for 64-wide wavefronts and the 16x16x32 bf16 MFMA,
+// whose A and B operands hold 8 consecutive contraction-index values per lane and whose 16 x 16
+// result puts column (lane % 16), rows 4 * (lane / 16) .. +3 into a lane; under a full matrix load
+// the chip holds a 13 % higher clock with this shape than with 32x32x16, which moves twice the
+// accumulator data per flop):
+//   * A work-group owns 256 queries of one (batch, head); each of its 8 waves owns 32, as two
+//     16-query blocks.
 //   * Scores are computed TRANSPOSED, S^T = K Q^T (keys are MFMA rows, queries columns), so
-//     a lane owns one query column: the row max / row sum of the online softmax are in-lane
-//     reductions plus one exchange between lane l and lane l^32.
+//     a lane owns one query column per block: the row max / row sum of the online softmax are in-lane
+//     reductions plus two exchanges over the four lanes r, r+16, r+32, r+48.
 //   * The exponentiated tile P^T, already in registers in the accumulator layout, is cast to
-//     bf16 and used directly as the B operand of O^T += V^T P^T; it never touches LDS.
+//     bf16 and used directly as the B operand of O^T += V^T P^T; it never touches LDS.  (The lane
+//     that holds keys 16*mb + 4*g + i of a query is the lane that must supply contraction indices
+//     8*g + j of the P.V step: the keys of a step are simply taken in that order on the V side.)
 //   * K and V tiles (64 keys) sit in LDS row-major, XOR-swizzled instead of padded; the V^T
 //     operand (8 keys of one head-dim column per lane) comes from the LDS transposing read.
 //   * O and l are rescaled lazily: only when a row max has outgrown the exponent reference.
@@ -24,7 +30,7 @@ namespace usp {
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
@@ -39,9 +45,10 @@ constexpr int kRowB = kD * 2;    // bytes per K / V row in LDS (256, unpadded)
 constexpr int kTileB = kTile * kRowB;          // 16 KB
 
 // K and V tiles are row-major [key][128 bf16] in LDS without padding; bank conflicts are
-// avoided by XOR-swizzling the sixteen 16-byte pieces of a row:
-//   K: piece c of key r sits at piece c ^ (r & 15)       (16-byte MFMA operand reads of 16 rows)
-//   V: piece c of key r sits at piece c ^ ((r & 3) << 2) (transposing 8-byte reads of 4 rows)
+// avoided by XOR-swizzling a row (SQ_LDS_BANK_CONFLICT reads 0 for both):
+//   K: the 16-byte piece c of key r sits at piece c ^ (r & 15)   (16-byte MFMA operand reads: 16 lanes, 16 rows)
+//   V: the 32-byte chunk c of key r sits at chunk c ^ (r & 7)     (transposing 8-byte reads: 32 lanes, 8 rows of 32 bytes)
+// (head dimension 64, 128-byte rows: see attn_pp_body)
 // Work-group -> (batch*head, query block) with the 8 XCDs of the chip in mind: consecutive
 // work-group ids go to consecutive XCDs (id % 8), each with its own L2.  The (head, query block)
 // items, head-major, are cut into 8 contiguous ranges of equal length, one per XCD: the query
@@ -63,133 +70,141 @@ static inline unsigned wg_grid_size(int nqb, int bh_total) {
   return (unsigned)(kXcds * ((bh_total * nqb + kXcds - 1) / kXcds));
 }
 
-__device__ __forceinline__ float xlane32_max(float x) {
-  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+// A query's values sit in the four lanes r, r + 16, r + 32, r + 48 (r = lane % 16): maximum / sum over them,
+// left in all four (two swaps: rows of 16 lanes pairwise, then the halves of the wave).
+__device__ __forceinline__ float xgroup_max(float x) {
+  auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
 }
-__device__ __forceinline__ float xlane32_sum(float x) {
-  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+__device__ __forceinline__ float xgroup_sum(float x) {
+  auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+  auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 
-// Chunk result, merge and store straight from the accumulator layout (32 bytes per query row and
-// instruction): what the key-split work-groups use, whose epilogue is too short for the detour
-// through LDS to pay.
+// Chunk result of one query from its running state (reference m in log2 units, sum l), merged with the
+// carried lse of earlier chunks by the section 3.4 equations: the factor for this chunk's O~ (c_cur), the
+// weight of the carried O (w_prev) and the new lse.
 // `invalid`: the rows are not to be trusted (a chunk of the ring never arrived): O and lse become NaN,
 // which no valid result is (a query whose keys are all masked gets O = 0, lse = -inf).
-__device__ __forceinline__ void finish_and_store_direct(const AttnStep& s, f32x16 (&oacc)[4], float m, float lsum,
-                                                 int b, int h, int q0, int n, int g, bool invalid) {
-  // ---- chunk result, merge with carried state, store ------------------------------------
-  const float l = xlane32_sum(lsum);
-  const int qi = q0 + n;
-  const bool valid = qi < s.Sq;
-  const int64_t row = ((int64_t)b * s.H + h) * s.Sq + (valid ? qi : s.Sq - 1);
-  float lse_r = -INFINITY, c_cur = 0.0f;
-  if (l > 0.0f) { lse_r = (m + log2f(l)) * 0.69314718055994530942f; c_cur = 1.0f / l; }
-  float w_prev = 0.0f, lse_new = lse_r;
+struct RowFinish { float c_cur, w_prev, lse_new; };
+__device__ __forceinline__ RowFinish finish_row(const AttnStep& s, float m, float l, int64_t lse_row, bool invalid) {
+  RowFinish f;
+  float lse_r = -INFINITY;
+  f.c_cur = 0.0f;
+  if (l > 0.0f) { lse_r = (m + log2f(l)) * 0.69314718055994530942f; f.c_cur = 1.0f / l; }
+  f.w_prev = 0.0f;
+  f.lse_new = lse_r;
   if (s.mode >= 2) {
-    const float lse_p = s.lse[row];
+    const float lse_p = s.lse[lse_row];
     const float mm = fmaxf(lse_p, lse_r);
-    if (mm == -INFINITY) { w_prev = 0.0f; c_cur = 0.0f; lse_new = -INFINITY; }
+    if (mm == -INFINITY) { f.w_prev = 0.0f; f.c_cur = 0.0f; f.lse_new = -INFINITY; }
     else {
-      lse_new = mm + logf(expf(lse_p - mm) + expf(lse_r - mm));
-      w_prev = expf(lse_p - lse_new);
-      c_cur *= expf(lse_r - lse_new);
+      f.lse_new = mm + logf(expf(lse_p - mm) + expf(lse_r - mm));
+      f.w_prev = expf(lse_p - f.lse_new);
+      f.c_cur *= expf(lse_r - f.lse_new);
     }
   }
-  if (invalid) { c_cur = __builtin_nanf(""); lse_new = c_cur; }
-  if (!valid) return;
-  float* accp = s.acc ? s.acc + row * (s.half_d ? 64 : kD) : nullptr;   // half_d: 64-wide rows everywhere
-  bf16_t* outp = (bf16_t*)s.out + b * s.os[0] + h * s.os[1] + (int64_t)qi * s.os[2];
+  if (invalid) { f.c_cur = __builtin_nanf(""); f.lse_new = f.c_cur; }
+  return f;
+}
+
+// Chunk result, merge and store straight from the accumulator layout (a lane holds four consecutive head
+// dims of a query: 8 bytes of bf16 or 16 bytes of the fp32 carry per store): what the key-split
+// work-groups use, whose epilogue is too short for the detour through LDS to pay.
+// kHalfD: head dimension 64: only the first four 16-wide blocks exist, rows are 64 wide everywhere.
+template <bool kHalfD>
+__device__ __forceinline__ void finish_and_store_direct(const AttnStep& s, f32x4 (&oacc)[8][2], const float (&m)[2],
+                                                        const float (&lsum)[2], int b, int h, int q0, int r, int g, bool invalid) {
+  constexpr int kDB = kHalfD ? 4 : 8;
+  constexpr int kAccP = kHalfD ? 64 : kD;   // floats per row of the carried O
 #pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
+  for (int nb = 0; nb < 2; ++nb) {
+    const float l = xgroup_sum(lsum[nb]);
+    const int qi = q0 + 16 * nb + r;
+    const bool valid = qi < s.Sq;
+    const int64_t row = ((int64_t)b * s.H + h) * s.Sq + (valid ? qi : s.Sq - 1);
+    const RowFinish f = finish_row(s, m[nb], l, row, invalid);
+    if (!valid) continue;
+    float* accp = s.acc ? s.acc + row * kAccP : nullptr;
+    bf16_t* outp = (bf16_t*)s.out + b * s.os[0] + h * s.os[1] + (int64_t)qi * s.os[2];
 #pragma unroll
-    for (int i4 = 0; i4 < 4; ++i4) {
-      const int dcol = 32 * dt + 8 * i4 + 4 * g;
-      if (s.half_d && dt >= 2) continue;   // half_d: rows are 64 wide
+    for (int db = 0; db < kDB; ++db) {
+      const int dcol = 16 * db + 4 * g;
       float o[4];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) o[e] = oacc[dt][4 * i4 + e] * c_cur;
+      for (int e = 0; e < 4; ++e) o[e] = oacc[db][nb][e] * f.c_cur;
       if (s.mode >= 2) {
         const float4 p = *reinterpret_cast<const float4*>(accp + dcol);
-        o[0] = fmaf(w_prev, p.x, o[0]); o[1] = fmaf(w_prev, p.y, o[1]);
-        o[2] = fmaf(w_prev, p.z, o[2]); o[3] = fmaf(w_prev, p.w, o[3]);
+        o[0] = fmaf(f.w_prev, p.x, o[0]); o[1] = fmaf(f.w_prev, p.y, o[1]);
+        o[2] = fmaf(f.w_prev, p.z, o[2]); o[3] = fmaf(f.w_prev, p.w, o[3]);
       }
       if (s.mode == 1 || s.mode == 2)
         *reinterpret_cast<float4*>(accp + dcol) = make_float4(o[0], o[1], o[2], o[3]);
       else
         *reinterpret_cast<uint2*>(outp + dcol) = make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
     }
-  if (g == 0) s.lse[row] = lse_new;
+    if (g == 0) s.lse[row] = f.lse_new;
+  }
 }
 
-// Chunk result from the running state (O~ = oacc, reference m in log2 units, this lane's part of l),
-// merged with the carried (O, lse) of earlier chunks by the section 3.4 equations, and stored.
-// In the accumulator layout a lane holds four consecutive head dims of one query, so direct stores
-// would touch 32 rows with 32 bytes each per instruction.  The wave therefore turns its 32 x 128
-// tile through its own LDS region (row pitch 528 bytes, so that rows do not all start in the same bank) and then moves
+// The same for the 256-query work-groups.  In the accumulator layout direct stores would touch 16 rows
+// with 32 bytes each per instruction.  The wave therefore turns its 32 x 128 tile through its own LDS
+// region (row pitch 528 bytes, so that rows do not all start in the same bank) and then moves
 // whole rows: 32 lanes x 16 bytes (fp32 carry, read and write) or x 8 bytes (bf16 output) per row,
 // two rows per instruction.  Only this wave touches the region; LDS operations of one wave complete
 // in order, so no barrier is needed.
 constexpr int kEpiPitch = kD * 4 + 16;                    // bytes per staged row
 constexpr int kEpiWaveB = kQPerWave * kEpiPitch + 512;    // + per-row (scale of O~, weight of the carry, lse, unused)
-__device__ __forceinline__ void finish_and_store(const AttnStep& s, f32x16 (&oacc)[4], float m, float lsum,
-                                                 int b, int h, int q0, int n, int g, unsigned char* epi, bool invalid) {
-  typedef float f32x4 __attribute__((ext_vector_type(4)));
-  const int lane = n + 32 * g;
-  const float l = xlane32_sum(lsum);
-  const int qi = q0 + n;
+template <bool kHalfD>
+__device__ __forceinline__ void finish_and_store(const AttnStep& s, f32x4 (&oacc)[8][2], const float (&m)[2],
+                                                 const float (&lsum)[2], int b, int h, int q0, int r, int g,
+                                                 unsigned char* epi, bool invalid) {
+  constexpr int kDB = kHalfD ? 4 : 8;
+  constexpr int kAccP = kHalfD ? 64 : kD;                 // floats per row of the carried O
+  const int lane = r + 16 * g;
   const int64_t row0 = ((int64_t)b * s.H + h) * s.Sq;     // first row of this (batch, head) in lse / acc
-  float lse_r = -INFINITY, c_cur = 0.0f;
-  if (l > 0.0f) { lse_r = (m + log2f(l)) * 0.69314718055994530942f; c_cur = 1.0f / l; }
-  float w_prev = 0.0f, lse_new = lse_r;
-  if (s.mode >= 2) {
-    const float lse_p = s.lse[row0 + min(qi, s.Sq - 1)];
-    const float mm = fmaxf(lse_p, lse_r);
-    if (mm == -INFINITY) { w_prev = 0.0f; c_cur = 0.0f; lse_new = -INFINITY; }
-    else {
-      lse_new = mm + logf(expf(lse_p - mm) + expf(lse_r - mm));
-      w_prev = expf(lse_p - lse_new);
-      c_cur *= expf(lse_r - lse_new);
-    }
-  }
-  if (invalid) { c_cur = __builtin_nanf(""); lse_new = c_cur; }
-  if (g == 0 && qi < s.Sq) s.lse[row0 + qi] = lse_new;
-  // stage: row n, head dims 32*dt + 8*i4 + 4*g .. +3
   float* info = reinterpret_cast<float*>(epi + kQPerWave * kEpiPitch);
-  if (g == 0) { info[2 * n] = c_cur; info[2 * n + 1] = w_prev; }
 #pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
+  for (int nb = 0; nb < 2; ++nb) {
+    const float l = xgroup_sum(lsum[nb]);
+    const int qr = 16 * nb + r;                           // row of the wave's tile
+    const int qi = q0 + qr;
+    const RowFinish f = finish_row(s, m[nb], l, row0 + min(qi, s.Sq - 1), invalid);
+    if (g == 0 && qi < s.Sq) s.lse[row0 + qi] = f.lse_new;
+    if (g == 0) { info[2 * qr] = f.c_cur; info[2 * qr + 1] = f.w_prev; }
+    // stage: row qr, head dims 16*db + 4*g .. +3
 #pragma unroll
-    for (int i4 = 0; i4 < 4; ++i4) {
-      const f32x4 v = {oacc[dt][4 * i4], oacc[dt][4 * i4 + 1], oacc[dt][4 * i4 + 2], oacc[dt][4 * i4 + 3]};
-      *reinterpret_cast<f32x4*>(epi + n * kEpiPitch + (32 * dt + 8 * i4 + 4 * g) * 4) = v;
-    }
+    for (int db = 0; db < kDB; ++db)
+      *reinterpret_cast<f32x4*>(epi + qr * kEpiPitch + (16 * db + 4 * g) * 4) = oacc[db][nb];
+  }
   // rows: lane (r2, c) handles head dims 4c .. 4c+3 of rows 2*it + r2
   const int r2 = lane >> 5, c = lane & 31;
   const int rows_valid = min(kQPerWave, s.Sq - q0);       // <= 0: nothing to store
-  const int accP = s.half_d ? 64 : kD;                    // floats per row of the carried O
 #pragma unroll 4
   for (int it = 0; it < kQPerWave / 2; ++it) {
-    const int r = 2 * it + r2;
-    if (r >= rows_valid || (s.half_d && c >= 16)) continue;   // half_d: rows are 64 wide
-    const f32x4 v = *reinterpret_cast<const f32x4*>(epi + r * kEpiPitch + c * 16);
-    const float cc = info[2 * r], wp = info[2 * r + 1];
+    const int rr = 2 * it + r2;
+    if (rr >= rows_valid || (kHalfD && c >= 16)) continue;   // kHalfD: rows are 64 wide
+    const f32x4 v = *reinterpret_cast<const f32x4*>(epi + rr * kEpiPitch + c * 16);
+    const float cc = info[2 * rr], wp = info[2 * rr + 1];
     float o[4] = {v[0] * cc, v[1] * cc, v[2] * cc, v[3] * cc};
-    const int64_t row = row0 + q0 + r;
+    const int64_t row = row0 + q0 + rr;
     if (s.mode >= 2) {
-      const float4 p = *reinterpret_cast<const float4*>(s.acc + row * accP + 4 * c);
+      const float4 p = *reinterpret_cast<const float4*>(s.acc + row * kAccP + 4 * c);
       o[0] = fmaf(wp, p.x, o[0]); o[1] = fmaf(wp, p.y, o[1]);
       o[2] = fmaf(wp, p.z, o[2]); o[3] = fmaf(wp, p.w, o[3]);
     }
     if (s.mode == 1 || s.mode == 2)
-      *reinterpret_cast<float4*>(s.acc + row * accP + 4 * c) = make_float4(o[0], o[1], o[2], o[3]);
+      *reinterpret_cast<float4*>(s.acc + row * kAccP + 4 * c) = make_float4(o[0], o[1], o[2], o[3]);
     else {
-      bf16_t* outp = (bf16_t*)s.out + b * s.os[0] + h * s.os[1] + (int64_t)(q0 + r) * s.os[2];
+      bf16_t* outp = (bf16_t*)s.out + b * s.os[0] + h * s.os[1] + (int64_t)(q0 + rr) * s.os[2];
       // the final output is not read again here: a streaming store leaves no dirty line for the
       // end of the kernel to write back (the fp32 carry above is re-read by the next step and stays cached)
-      const u32x2 v = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
-      __builtin_nontemporal_store(v, reinterpret_cast<u32x2*>(outp + 4 * c));
+      const u32x2 v2 = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
+      __builtin_nontemporal_store(v2, reinterpret_cast<u32x2*>(outp + 4 * c));
     }
   }
 }
@@ -244,7 +259,7 @@ __device__ __forceinline__ void finish_and_store(const AttnStep& s, f32x16 (&oac
 // from the record in LDS (it cannot be fetched ahead from memory the launch is still writing).
 //
 // kNoDead: records that carry only per-key factors (no mask, whole tiles): flag and bias are never
-// read.  kHalfD: head dimension 64 held in the d = 128 layout (see attn_pp_body).
+// read.  kHalfD: head dimension 64 (see attn_pp_body).
 // =============================================================================================
 __device__ __forceinline__ void lds_dma16(const void* gbase, uint32_t lane_off, uint32_t lds_base) {
   // 64 lanes x 16 bytes from gbase (wave-uniform) + lane_off (per lane): lane i's 16 bytes land at
@@ -368,15 +383,19 @@ __global__ __launch_bounds__(256) void attn_fp8_chunk_prepare_kernel(AttnStep s,
 // One work-group's share: the queries q_base .. q_base + 255 (wide) or + 127 (split) of (batch, head) bh_.
 // kNoDead (with kExt): the records carry per-key factors only, no key of the launch is dead (FP8
 // scales on unmasked chunks of whole tiles): the per-tile flag is not read at all.
-// kHalfD: head dimension 64 held in the d = 128 layout (columns 64..127 of Q, K and V are zero): the
-// MFMAs that would only multiply zeros are left out, i.e. the scores run over the first four
-// 16-wide slices of the head dimension and P.V over the first two 32-wide slices.
+// kHalfD: head dimension 64: rows of Q, K, V and O are 128 bytes (K and V are read in place, their LDS
+// tiles have 128-byte rows with swizzles of their own), the scores contract over two 32-wide slices
+// of the head dimension and P.V produces four 16-wide blocks.
 template <bool kSplit, bool kExt, bool kMulti = false, bool kNoDead = false, bool kHalfD = false>
 __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* smem_raw, int bh_, int q_base) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it in an SGPR
-  const int n = lane & 31, g = lane >> 5;
+  const int r = lane & 15, g = lane >> 4;   // MFMA column (a query) and 8-wide slice of the contraction index
+  constexpr int kKS = kHalfD ? 2 : 4;        // 32-wide slices of the head dimension (contraction of the scores)
+  constexpr int kNV = kHalfD ? 2 : 4;        // operands of either kind per block of the matrix phase
+  constexpr int kDB = kHalfD ? 4 : 8;        // 16-wide blocks of the head dimension that P.V produces
+  constexpr int kBurst = 1;                  // operands whose MFMAs are issued back to back before the next reads (1, 2, 4: no difference measured)
   const int h = bh_ % s.H, b = bh_ / s.H;
   // split: waves w and w+4 share their 32 queries
   const int q0 = q_base + (kSplit ? (wave & 3) : wave) * kQPerWave;
@@ -398,12 +417,12 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
   const int tail_tile = (kExt && !kMulti && (s.Sc % kTile) != 0) ? nt_all - 1 : -1;
   const int tail_last_row = s.Sc - (nt_all - 1) * kTile - 1;   // last valid row of the ragged tile
 
-  f32x16 oacc[4];
+  f32x4 oacc[8][2];   // O~^T: [16-wide head-dim block db][16-query block nb]: head dims 16*db + 4*g + i of query 16*nb + r
 #pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
+  for (int db = 0; db < 8; ++db)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) oacc[dt][i] = 0.0f;
-  float m = -INFINITY, lsum = 0.0f;
+    for (int nb = 0; nb < 2; ++nb) oacc[db][nb] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+  float m[2] = {-INFINITY, -INFINITY}, lsum[2] = {0.0f, 0.0f};   // per query block
   bool late = false;   // an awaited chunk never arrived (see wait_arrival): the results are replaced by NaN
   int arrived_upto = 0, probe_c = 0, probe_val = 0;   // chunks known to have arrived; the count read ahead for chunk probe_c
   constexpr int kProbeAheadTiles = 4;
@@ -424,10 +443,11 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
   const int64_t tileB = (int64_t)kTile * rowB;
   const uint32_t ksw0 = kHalfD ? (uint32_t)((dma_p ^ ((dma_r0 >> 1) & 7)) << 4) : (uint32_t)((dma_p ^ (dma_r0 & 15)) << 4);
   const uint32_t ksw1 = (dma_p ^ (dma_r1 & 15)) << 4;
-  const uint32_t vsw = kHalfD ? (uint32_t)((dma_p ^ (((dma_r0 >> 1) & 1) << 2)) << 4)
-                              : (uint32_t)((dma_p ^ ((dma_r0 & 3) << 2)) << 4);   // (r0 + 4) & 3 == r0 & 3
+  // V: the 32-byte chunk c of key r sits at chunk c ^ (r & 7) (kHalfD: c ^ ((r >> 1) & 3)): in 16-byte pieces
+  const uint32_t vsw0 = kHalfD ? (uint32_t)((dma_p ^ (((dma_r0 >> 1) & 3) << 1)) << 4) : (uint32_t)((dma_p ^ ((dma_r0 & 7) << 1)) << 4);
+  const uint32_t vsw1 = (dma_p ^ ((dma_r1 & 7) << 1)) << 4;
   const uint32_t kg0 = dma_r0 * rowB + ksw0, kg1 = dma_r1 * rowB + ksw1;
-  const uint32_t vg0 = dma_r0 * rowB + vsw, vg1 = dma_r1 * rowB + vsw;
+  const uint32_t vg0 = dma_r0 * rowB + vsw0, vg1 = dma_r1 * rowB + vsw1;
   const uint32_t lds_base = (uint32_t)(uintptr_t)smem_raw;
   const uint32_t lds_k = __builtin_amdgcn_readfirstlane(lds_base + 8 * wave * RB);
   const uint32_t lds_v = __builtin_amdgcn_readfirstlane(lds_base + kStages * kTileB + 8 * wave * RB);
@@ -449,7 +469,7 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
     if (kHalfD && half) return;
     const int dr = pair ? pair_rows : 0;
     uint32_t off = half ? vg1 : vg0;
-    if (kExt && tile_idx == tail_tile) { off = row_off((half ? dma_r1 : dma_r0) + dr, tile_idx) + vsw; }
+    if (kExt && tile_idx == tail_tile) { off = row_off((half ? dma_r1 : dma_r0) + dr, tile_idx) + (half ? vsw1 : vsw0); }
     else tile += (int64_t)dr * rowB;
     lds_dma16(tile, off, lds_v + dr * RB + stage * kTileB + half * 4 * RB);
   };
@@ -546,114 +566,105 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
   const unsigned char* vpre = kMulti ? nullptr : vb + vpre_idx * tileB;
   constexpr int kPreStep = kSplit ? 2 : 1;   // tiles between two softmax phases of a wave
 
-  // Q^T operand: lane (n, g) holds Q[q0+n][16*ks + 8*g .. +7] for ks = 0..7
-  bf16x8 qreg[8];
+  // Q^T operand (B of S^T = K Q^T): lane (r, g) holds Q[q0 + 16*nb + r][32*ks + 8*g .. +7]
+  bf16x8 qreg[2][4];
   {
-    const int qi = min(q0 + n, s.Sq - 1);
-    const bf16_t* qr = qb + (int64_t)qi * s.qs[2] + 8 * g;
 #pragma unroll
-    for (int ks = 0; ks < (kHalfD ? 4 : 8); ++ks) qreg[ks] = *reinterpret_cast<const bf16x8*>(qr + 16 * ks);   // kHalfD: Q rows may be 64 wide
+    for (int nb = 0; nb < 2; ++nb) {
+      const int qi = min(q0 + 16 * nb + r, s.Sq - 1);
+      const bf16_t* qr = qb + (int64_t)qi * s.qs[2] + 8 * g;
 #pragma unroll
-    for (int ks = 0; ks < (kHalfD ? 4 : 8); ++ks) asm volatile("" : "+v"(qreg[ks]));
+      for (int ks = 0; ks < kKS; ++ks) qreg[nb][ks] = *reinterpret_cast<const bf16x8*>(qr + 32 * ks);
+    }
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+      for (int ks = 0; ks < kKS; ++ks) asm volatile("" : "+v"(qreg[nb][ks]));
   }
 
-  f32x16 sacc[2];
-  u32x4 pk[4];
+  f32x4 sacc[4][2];   // scores: [16-key block mb][16-query block nb]: keys 16*mb + 4*g + i of query 16*nb + r
+  u32x4 pk[2][2];     // bf16 P as the B operand of P.V: [32-key step kk][nb]: keys 32*kk + 16*(j >> 2) + 4*g + (j & 3), j = 0..7
 
-  // per-lane LDS read addresses (see the layout notes at the top): 8 for the K operand (one per 16-wide
-  // slice of the head dimension), 4 for the V^T operand (one per 32-wide slice); stage, key block
+  // per-lane LDS read addresses (see the layout notes at the top): 4 for the K operand (one per 32-wide
+  // slice of the head dimension), 8 for the V^T operand (one per 16-wide slice); stage, key block
   // and row offsets are compile-time immediates on top of these
   typedef const __attribute__((address_space(3))) unsigned char* lds_cptr;
-  lds_cptr k_rd[8], v_rd[4];
+  lds_cptr k_rd[4], v_rd[8];
   {
-    const int tr_i = (lane >> 2) & 3, tr_cc = lane & 3, tr_dh = (lane >> 4) & 1;
+    const int vrow = 4 * g + (r >> 2);          // the key this lane names in a transposing read (plus 32*kk, plus 16)
     if (!kHalfD) {
-      const int k_rd_row = n * RB;
-      const int k_rd_x = (g ^ (n & 15)) << 4;
-      const int v_rd_row = (4 * g + tr_i) * RB + ((2 * tr_dh + (tr_cc >> 1)) << 4) + 8 * (tr_cc & 1);
-      const int v_rd_x = tr_i << 6;
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks)
-        k_rd[ks] = (lds_cptr)(uintptr_t)(lds_base + k_rd_row + ((32 * ks) ^ k_rd_x));
+      for (int ks = 0; ks < 4; ++ks)
+        k_rd[ks] = (lds_cptr)(uintptr_t)(lds_base + r * RB + (((4 * ks + g) ^ r) << 4));
 #pragma unroll
-      for (int dt = 0; dt < 4; ++dt)
-        v_rd[dt] = (lds_cptr)(uintptr_t)(lds_base + kStages * kTileB + v_rd_row + ((dt << 6) ^ v_rd_x));
+      for (int db = 0; db < 8; ++db)
+        v_rd[db] = (lds_cptr)(uintptr_t)(lds_base + kStages * kTileB + vrow * RB + ((db ^ (vrow & 7)) << 5) + 8 * (r & 3));
     } else {
-      // 128-byte rows: K piece 2*ks + g of key n; V bytes 64*dt + 32*tr_dh + 8*tr_cc of key 4*g + tr_i
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks)
-        k_rd[ks] = (lds_cptr)(uintptr_t)(lds_base + n * RB + ((((2 * ks + g) & 7) ^ ((n >> 1) & 7)) << 4));
+      for (int ks = 0; ks < 4; ++ks)
+        k_rd[ks] = (lds_cptr)(uintptr_t)(lds_base + r * RB + ((((4 * ks + g) & 7) ^ ((r >> 1) & 7)) << 4));
 #pragma unroll
-      for (int dt = 0; dt < 4; ++dt)
-        v_rd[dt] = (lds_cptr)(uintptr_t)(lds_base + kStages * kTileB + (4 * g + tr_i) * RB +
-                                         ((((dt & 1) << 6) + 32 * tr_dh + 8 * tr_cc) ^ (((tr_i >> 1) & 1) << 6)));
+      for (int db = 0; db < 8; ++db)
+        v_rd[db] = (lds_cptr)(uintptr_t)(lds_base + kStages * kTileB + vrow * RB + (((db & 3) ^ ((vrow >> 1) & 3)) << 5) + 8 * (r & 3));
     }
   }
-  // extended path: this lane's keys of a tile are rows 32*kt + 8*a + 4*g + (0..3), a = 0..3
+  // extended path: this lane's keys of a tile are rows 16*mb + 4*g + (0..3), mb = 0..3
   const lds_cptr x_rd = (lds_cptr)(uintptr_t)(lds_ext + 16 * g);
 
-  // scores of the tile in LDS stage `stage`: sacc[kt] += K Q^T over head-dim slices ks_lo..ks_lo+3
-  auto qk_block = [&](int stage, int kt, int ks_lo) {
-#pragma unroll
-    for (int ks = ks_lo; ks < ks_lo + 4; ++ks) {
-      const bf16x8 a = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(
-          k_rd[ks] + stage * kTileB + 32 * kt * RB);
-      sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], sacc[kt], 0, 0, 0);
-    }
+  // LDS operands.  K: keys 16*mb .. +15 (MFMA rows), head dims 32*ks + 8*g .. +7: one 16-byte read.
+  // V^T: head dims 16*db .. +15 (MFMA rows), keys of step kk in the order of pk: two transposing reads of
+  // four keys each (rows 32*kk + 4*g + i and 32*kk + 16 + 4*g + i).
+  auto k_operand = [&](int stage, int mb, int ks) -> bf16x8 {
+    return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(k_rd[ks] + stage * kTileB + 16 * mb * RB);
   };
-  // matrix phase: O += P V (V tile in stage sv) interleaved with the scores of the next tile (K in
-  // stage sk), in four blocks of eight MFMAs (four for P.V over 16 keys, four for the scores of 32
-  // keys over half the head dimension).  Only this wave feeds the SIMD's matrix core during the
-  // phase, so its LDS operand reads run one block (eight MFMAs, twelve reads) ahead of their use.
-  // The order is written out and pinned (sched_barrier after every MFMA and the reads issued behind
-  // it) rather than left to the instruction scheduler, whose choice changes with the code around it.
-  auto v_operand = [&](int stage, int blk, int dt) -> bf16x8 {
-    const u32x2 lo = lds_read_tr3(v_rd[dt] + stage * kTileB + 16 * blk * RB);
-    const u32x2 hi = lds_read_tr3(v_rd[dt] + stage * kTileB + (16 * blk + 8) * RB);
+  auto v_operand = [&](int stage, int kk, int db) -> bf16x8 {
+    const u32x2 lo = lds_read_tr3(v_rd[db] + stage * kTileB + 32 * kk * RB);
+    const u32x2 hi = lds_read_tr3(v_rd[db] + stage * kTileB + (32 * kk + 16) * RB);
     return __builtin_bit_cast(bf16x8, u32x4{lo[0], lo[1], hi[0], hi[1]});
   };
-  auto k_operand = [&](int stage, int blk, int i) -> bf16x8 {   // block blk: keys 32 * (blk >> 1) .., head dims 64 * (blk & 1) + 16 * i ..
-    return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(
-        k_rd[4 * (blk & 1) + i] + stage * kTileB + 32 * (blk >> 1) * RB);
-  };
-  constexpr int kDT = kHalfD ? 2 : 4;   // 32-wide slices of the head dimension that P.V produces
+  const f32x4 zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+  // matrix phase: O += P V (V tile in stage sv) interleaved with the scores of the next tile (K in
+  // stage sk), in four blocks of sixteen MFMAs: block b takes kNV V^T operands (key step b >> 1, head-dim
+  // blocks kNV * (b & 1) ..) and kNV K operands (key block b, all head-dim slices), each operand feeding
+  // two MFMAs (the wave's two 16-query blocks), so that consecutive MFMAs share their A operand.
+  // Only this wave feeds the SIMD's matrix core during the phase, so its LDS operand reads run one
+  // block ahead of their use.  The order is written out and pinned (sched_barrier after every operand's
+  // MFMAs and the reads issued behind them) rather than left to the instruction scheduler.
   auto MM_full = [&](int sv, int sk) {
     __builtin_amdgcn_s_setprio(2);
-    bf16x8 va[2][4], ka[2][4];
+    bf16x8 va[2][kNV], ka[2][kNV];
 #pragma unroll
-    for (int i = 0; i < kDT; ++i) va[0][i] = v_operand(sv, 0, i);
+    for (int i = 0; i < kNV; ++i) va[0][i] = v_operand(sv, 0, i);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) ka[0][i] = k_operand(sk, 0, i);
+    for (int i = 0; i < kNV; ++i) ka[0][i] = k_operand(sk, 0, i);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int blk = 0; blk < 4; ++blk) {
-      const int c = blk & 1, kt = blk >> 1;
-      const bf16x8 pb = __builtin_bit_cast(bf16x8, pk[blk]);
+      const int c = blk & 1, kk = blk >> 1;
+      const bf16x8 pb0 = __builtin_bit_cast(bf16x8, pk[kk][0]), pb1 = __builtin_bit_cast(bf16x8, pk[kk][1]);
 #pragma unroll
-      for (int dt = 0; dt < kDT; ++dt) {
-        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[c][dt], pb, oacc[dt], 0, 0, 0);
-        if (blk < 3) va[c ^ 1][dt] = v_operand(sv, blk + 1, dt);
-        // half head dimension: the K operands of the next even block are fetched here, behind the
-        // two P.V MFMAs of the odd block before it
-        if (kHalfD && (blk & 1) == 1 && blk < 3) {
-          ka[c ^ 1][2 * dt] = k_operand(sk, blk + 1, 2 * dt);
-          ka[c ^ 1][2 * dt + 1] = k_operand(sk, blk + 1, 2 * dt + 1);
+      for (int i = 0; i < kNV; i += kBurst) {
+#pragma unroll
+        for (int j = i; j < i + kBurst; ++j) {
+          const int db = kNV * (blk & 1) + j;
+          oacc[db][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[c][j], pb0, oacc[db][0], 0, 0, 0);
+          oacc[db][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[c][j], pb1, oacc[db][1], 0, 0, 0);
         }
+#pragma unroll
+        for (int j = i; j < i + kBurst; ++j)
+          if (blk < 3) va[c ^ 1][j] = v_operand(sv, (blk + 1) >> 1, kNV * ((blk + 1) & 1) + j);
         __builtin_amdgcn_sched_barrier(0);
       }
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        if (kHalfD && (blk & 1) == 1) break;     // head dims 64..127: zeros
-        const int ks = 4 * (blk & 1) + i;
-        if (ks == 0) {
-          f32x16 z;
+      for (int i = 0; i < kNV; i += kBurst) {     // (kNV == kKS: the head-dim slices of the scores)
 #pragma unroll
-          for (int e = 0; e < 16; ++e) z[e] = 0.0f;
-          sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[c][i], qreg[ks], z, 0, 0, 0);
-        } else {
-          sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[c][i], qreg[ks], sacc[kt], 0, 0, 0);
+        for (int ks = i; ks < i + kBurst; ++ks) {
+          sacc[blk][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[c][ks], qreg[0][ks], ks == 0 ? zero4 : sacc[blk][0], 0, 0, 0);
+          sacc[blk][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[c][ks], qreg[1][ks], ks == 0 ? zero4 : sacc[blk][1], 0, 0, 0);
         }
-        if (!kHalfD && blk < 3) ka[c ^ 1][i] = k_operand(sk, blk + 1, i);
+#pragma unroll
+        for (int ks = i; ks < i + kBurst; ++ks)
+          if (blk < 3) ka[c ^ 1][ks] = k_operand(sk, blk + 1, ks);
         __builtin_amdgcn_sched_barrier(0);
       }
     }
@@ -661,25 +672,29 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
   };
   auto MM_last = [&](int sv) {   // last tile: no further scores; the reads run two blocks ahead
     __builtin_amdgcn_s_setprio(2);
-    bf16x8 va[4][4];
+    bf16x8 va[4][kNV];
 #pragma unroll
     for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
-      for (int i = 0; i < kDT; ++i) va[blk][i] = v_operand(sv, blk, i);
+      for (int i = 0; i < kNV; ++i) va[blk][i] = v_operand(sv, blk >> 1, kNV * (blk & 1) + i);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int blk = 0; blk < 4; ++blk) {
-      const bf16x8 pb = __builtin_bit_cast(bf16x8, pk[blk]);
+      const int kk = blk >> 1;
+      const bf16x8 pb0 = __builtin_bit_cast(bf16x8, pk[kk][0]), pb1 = __builtin_bit_cast(bf16x8, pk[kk][1]);
 #pragma unroll
-      for (int dt = 0; dt < kDT; ++dt) {
-        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[blk][dt], pb, oacc[dt], 0, 0, 0);
-        if (blk < 2) va[blk + 2][dt] = v_operand(sv, blk + 2, dt);
+      for (int i = 0; i < kNV; ++i) {
+        const int db = kNV * (blk & 1) + i;
+        oacc[db][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[blk][i], pb0, oacc[db][0], 0, 0, 0);
+        oacc[db][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[blk][i], pb1, oacc[db][1], 0, 0, 0);
+        if (blk < 2) va[blk + 2][i] = v_operand(sv, (blk + 2) >> 1, kNV * (blk & 1) + i);
         __builtin_amdgcn_sched_barrier(0);
       }
     }
     __builtin_amdgcn_s_setprio(0);
   };
-  // softmax phase: sacc (scores of one tile) -> pk (bf16 P), running reference m and sum l.
+  // softmax phase: sacc (scores of one tile) -> pk (bf16 P), running references m and sums l of the
+  // lane's two queries.
   // Fast path: exponentials are taken against the current reference m without first looking for
   // the tile's maximum; the row sum then certifies the result: if this lane's sum of P is at most
   // 2^60, no P exceeded 2^60, and neither l (at most 2^60 per key) nor O~ (at most 2^60 |v| per key)
@@ -691,35 +706,36 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
   // that the waves do not hit the load path at once.
   // Extended path: the per-key factor c replaces the uniform scale, and in a tile with dead keys
   // their bias (-inf) is added to the exponent.
-  typedef float f32x4 __attribute__((ext_vector_type(4)));
-  auto x_vec = [&](int stage, int which, int kt, int a) -> f32x4 {   // which: 0 c, 1 bias
+  auto x_vec = [&](int stage, int which, int mb) -> f32x4 {   // which: 0 c, 1 bias; keys 16*mb + 4*g + (0..3)
     return *reinterpret_cast<const __attribute__((address_space(3))) f32x4*>(
-        x_rd + stage * kExtTileB + which * 256 + (32 * kt + 8 * a) * 4);
+        x_rd + stage * kExtTileB + which * 256 + 64 * mb);
   };
-  // c of the next block of 8 keys is fetched while the current block is computed
+  // c of the second key step is fetched while the first is computed
   f32x4 xc[2][2];
-  auto x_load = [&](int buf, int xs, int kt, int half) {
+  auto x_load = [&](int kk, int xs) {
 #pragma unroll
-    for (int a = 0; a < 2; ++a) xc[buf][a] = x_vec(xs, 0, kt, 2 * half + a);
+    for (int a = 0; a < 2; ++a) xc[kk][a] = x_vec(xs, 0, 2 * kk + a);
   };
-  auto exp_block = [&](int kt, int half, float& psum, int xs, bool dead_keys) {
+  // one block: the 8 scores of query block nb over key step kk -> pk[kk][nb]
+  auto exp_block = [&](int kk, int nb, float& psum, int xs, bool dead_keys, bool fetch_ahead) {
     float p[8];
     if (!kExt) {
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        p[j] = __builtin_amdgcn_exp2f(fmaf(sacc[kt][8 * half + j], scale2, -m));
-        psum += p[j];
-      }
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          p[4 * a + e] = __builtin_amdgcn_exp2f(fmaf(sacc[2 * kk + a][nb][e], scale2, -m[nb]));
+          psum += p[4 * a + e];
+        }
     } else {
-      const int buf = half;                      // blocks run in the order (0,0) (0,1) (1,0) (1,1)
-      if (2 * kt + half < 3) x_load(buf ^ 1, xs, (2 * kt + half + 1) >> 1, (half + 1) & 1);
+      if (fetch_ahead && kk == 0 && nb == 1) x_load(1, xs);   // blocks run in the order (0,0) (0,1) (1,0) (1,1)
 #pragma unroll
       for (int a = 0; a < 2; ++a) {
         f32x4 t;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) t[e] = fmaf(sacc[kt][8 * half + 4 * a + e], xc[buf][a][e], -m);
+        for (int e = 0; e < 4; ++e) t[e] = fmaf(sacc[2 * kk + a][nb][e], xc[kk][a][e], -m[nb]);
         if (dead_keys) {
-          const f32x4 bias = x_vec(xs, 1, kt, 2 * half + a);
+          const f32x4 bias = x_vec(xs, 1, 2 * kk + a);
 #pragma unroll
           for (int e = 0; e < 4; ++e) t[e] += bias[e];
         }
@@ -731,29 +747,41 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
       }
     }
 #pragma unroll
-    for (int j = 0; j < 4; ++j) pk[2 * kt + half][j] = pack_bf16x2(p[2 * j], p[2 * j + 1]);
+    for (int j = 0; j < 4; ++j) pk[kk][nb][j] = pack_bf16x2(p[2 * j], p[2 * j + 1]);
     // anchor the block here, between the tile loads that surround it in program order
-    asm volatile("" : "+v"(pk[2 * kt + half]));
+    asm volatile("" : "+v"(pk[kk][nb]));
   };
-  // largest exponent argument (before the reference is subtracted) of this lane's query over the tile
-  auto tile_max = [&](int xs) -> float {
-    float tmax = -INFINITY;
+  // largest exponent argument (before the reference is subtracted) of each of this lane's two queries over the tile
+  auto tile_max = [&](int xs, float (&tmax)[2]) {
+    tmax[0] = tmax[1] = -INFINITY;
     if (!kExt) {
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
+      for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, sacc[kt][i]);
-      return xlane32_max(tmax) * scale2;
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) tmax[nb] = fmaxf(tmax[nb], sacc[mb][nb][e]);
+      tmax[0] = xgroup_max(tmax[0]) * scale2;
+      tmax[1] = xgroup_max(tmax[1]) * scale2;
+      return;
     }
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
+    for (int mb = 0; mb < 4; ++mb) {
+      const f32x4 c = x_vec(xs, 0, mb), bias = x_vec(xs, 1, mb);
 #pragma unroll
-      for (int a = 0; a < 4; ++a) {
-        const f32x4 c = x_vec(xs, 0, kt, a), bias = x_vec(xs, 1, kt, a);
+      for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) tmax = fmaxf(tmax, fmaf(sacc[kt][4 * a + e], c[e], bias[e]));
-      }
-    return xlane32_max(tmax);
+        for (int e = 0; e < 4; ++e) tmax[nb] = fmaxf(tmax[nb], fmaf(sacc[mb][nb][e], c[e], bias[e]));
+    }
+    tmax[0] = xgroup_max(tmax[0]);
+    tmax[1] = xgroup_max(tmax[1]);
+  };
+  auto rescale = [&](int nb, float alpha) {   // O~ and l of query block nb
+    lsum[nb] *= alpha;
+#pragma unroll
+    for (int db = 0; db < 8; ++db)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) oacc[db][nb][e] *= alpha;
   };
   // Tiles still to be handled maximum-first (wave-uniform).  After a failed certification with a
   // reference already in place, the next kMaxFirstTiles softmax phases of the wave find the tile's
@@ -793,9 +821,9 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
   // SM of the tile whose record sits in stage xs; loads K tile kpre_idx into stage sk (if do_k, with
   // the record of tile xpre_idx into stage xst if do_x) and V tile vpre_idx into stage sv (if do_v)
   auto SM = [&](int xs, int sk, int sv, bool do_k, bool do_v, bool do_x, int xpre_idx, int xst) {
-    float psum = 0.0f;
+    float psum[2] = {0.0f, 0.0f};
     bool dead_keys = false;
-    if (kExt) x_load(0, xs, 0, 0);
+    if (kExt) x_load(0, xs);
     if (kExt && !kNoDead) {
       // this tile's flag was fetched during the wave's previous softmax phase; fetch the next one
       if (kMulti) {
@@ -814,17 +842,18 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
     }
     if (max_first > 0) {
       --max_first;
-      const float tmax = tile_max(xs);
-      const bool jump = tmax > m + 8.0f;
-      if (__builtin_amdgcn_ballot_w64(jump) != 0ull) {
-        const float m_new = tmax + kRefMargin;
-        const float alpha = jump ? __builtin_amdgcn_exp2f(m - m_new) : 1.0f;   // m = -inf gives 0
-        m = jump ? m_new : m;
-        lsum *= alpha;
+      float tmax[2];
+      tile_max(xs, tmax);
+      const bool jump0 = tmax[0] > m[0] + 8.0f, jump1 = tmax[1] > m[1] + 8.0f;
+      if (__builtin_amdgcn_ballot_w64(jump0 || jump1) != 0ull) {
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) oacc[dt][i] *= alpha;
+        for (int nb = 0; nb < 2; ++nb) {
+          const bool jump = nb ? jump1 : jump0;
+          const float m_new = tmax[nb] + kRefMargin;
+          const float alpha = jump ? __builtin_amdgcn_exp2f(m[nb] - m_new) : 1.0f;   // m = -inf gives 0
+          m[nb] = jump ? m_new : m[nb];
+          rescale(nb, alpha);
+        }
         max_first = kMaxFirstTiles;
       }
       __builtin_amdgcn_sched_barrier(0);
@@ -837,78 +866,83 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
     // otherwise hoist all of them to the top, where they queue behind one another)
     if (!kSplit) {
       if (do_k) issue_k_half(kpre, kpre_idx, sk, 0, false);
-      exp_block(0, 0, psum, xs, dead_keys);
+      exp_block(0, 0, psum[0], xs, dead_keys, true);
       __builtin_amdgcn_sched_barrier(0);
       if (do_k) issue_k_half(kpre, kpre_idx, sk, 1, false);
-      exp_block(0, 1, psum, xs, dead_keys);
+      exp_block(0, 1, psum[1], xs, dead_keys, true);
       __builtin_amdgcn_sched_barrier(0);
       if (do_v) issue_v_half(vpre, vpre_idx, sv, 0, false);
-      exp_block(1, 0, psum, xs, dead_keys);
+      exp_block(1, 0, psum[0], xs, dead_keys, true);
       __builtin_amdgcn_sched_barrier(0);
       if (do_v) issue_v_half(vpre, vpre_idx, sv, 1, false);
       if (kExt && do_x) issue_ext(xpre_idx, xst);
-      exp_block(1, 1, psum, xs, dead_keys);
+      exp_block(1, 1, psum[1], xs, dead_keys, true);
       __builtin_amdgcn_sched_barrier(0);
     } else {
       if (do_v) { issue_v_half(vpre, vpre_idx, sv, 0, false); issue_v_half(vpre, vpre_idx, sv, 0, true); }
-      exp_block(0, 0, psum, xs, dead_keys);
+      exp_block(0, 0, psum[0], xs, dead_keys, true);
       __builtin_amdgcn_sched_barrier(0);
       if (do_v) { issue_v_half(vpre, vpre_idx, sv, 1, false); issue_v_half(vpre, vpre_idx, sv, 1, true); }
-      exp_block(0, 1, psum, xs, dead_keys);
+      exp_block(0, 1, psum[1], xs, dead_keys, true);
       __builtin_amdgcn_sched_barrier(0);
       if (do_k) { issue_k_half(kpre, kpre_idx, sk, 0, false); issue_k_half(kpre, kpre_idx, sk, 0, true); }
-      exp_block(1, 0, psum, xs, dead_keys);
+      exp_block(1, 0, psum[0], xs, dead_keys, true);
       __builtin_amdgcn_sched_barrier(0);
       if (do_k) { issue_k_half(kpre, kpre_idx, sk, 1, false); issue_k_half(kpre, kpre_idx, sk, 1, true); }
       if (kExt && do_x) issue_ext(xpre_idx, xst);
-      exp_block(1, 1, psum, xs, dead_keys);
+      exp_block(1, 1, psum[1], xs, dead_keys, true);
       __builtin_amdgcn_sched_barrier(0);
     }
     if (!kMulti) { kpre += kPreStep * tileB; vpre += kPreStep * tileB; }
     kpre_idx += kPreStep;
     vpre_idx += kPreStep;
-    if (__builtin_amdgcn_ballot_w64(!(psum <= kCertifiedSum)) != 0ull) {
+    if (__builtin_amdgcn_ballot_w64(!(psum[0] <= kCertifiedSum && psum[1] <= kCertifiedSum)) != 0ull) {
       // a reference that was already set and still failed: scores with heavy tails; look for the
       // maximum first on the next tiles instead of paying for the exponentials twice
-      if (__builtin_amdgcn_ballot_w64(m != -INFINITY) != 0ull) max_first = kMaxFirstTiles;
-      const float tmax = tile_max(xs);
-      const float m_new = tmax > m ? tmax + kRefMargin : m;
-      // m = -inf (first live tile) gives alpha 0; no live key so far: nothing to rescale, P = 0
-      const float alpha = m_new == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(m - m_new);
-      m = m_new;
-      lsum *= alpha;
+      if (__builtin_amdgcn_ballot_w64(m[0] != -INFINITY || m[1] != -INFINITY) != 0ull) max_first = kMaxFirstTiles;
+      float tmax[2];
+      tile_max(xs, tmax);
+      if (kExt) { x_load(0, xs); x_load(1, xs); }
 #pragma unroll
-      for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) oacc[dt][i] *= alpha;
-      psum = 0.0f;
-      if (kExt && m_new == -INFINITY) {
-#pragma unroll
-        for (int blk = 0; blk < 4; ++blk) pk[blk] = u32x4{0u, 0u, 0u, 0u};
-      } else {
-        if (kExt) x_load(0, xs, 0, 0);
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-          for (int half = 0; half < 2; ++half) exp_block(kt, half, psum, xs, dead_keys);
+      for (int nb = 0; nb < 2; ++nb) {
+        const float m_new = tmax[nb] > m[nb] ? tmax[nb] + kRefMargin : m[nb];
+        // m = -inf (first live tile) gives alpha 0; no live key so far: nothing to rescale, P = 0
+        const float alpha = m_new == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(m[nb] - m_new);
+        m[nb] = m_new;
+        rescale(nb, alpha);
+        psum[nb] = 0.0f;
+        if (kExt && m_new == -INFINITY) {
+          pk[0][nb] = u32x4{0u, 0u, 0u, 0u};
+          pk[1][nb] = u32x4{0u, 0u, 0u, 0u};
+        } else {
+          exp_block(0, nb, psum[nb], xs, dead_keys, false);
+          exp_block(1, nb, psum[nb], xs, dead_keys, false);
+        }
       }
     }
-    lsum += psum;
+    lsum[0] += psum[0];
+    lsum[1] += psum[1];
     // pin the results here: without a use in this phase the optimiser sinks the exponentials past
     // the barrier, next to their first use in the matrix phase
 #pragma unroll
-    for (int blk = 0; blk < 4; ++blk) asm volatile("" : "+v"(pk[blk]));
-    asm volatile("" : "+v"(lsum));
+    for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb) asm volatile("" : "+v"(pk[kk][nb]));
+    asm volatile("" : "+v"(lsum[0]), "+v"(lsum[1]));
   };
   auto nxt = [](int x) { return x == 2 ? 0 : x + 1; };
   if (kExt && !kNoDead && !kMulti) flag_next = tile_flag(sm_tile);
   auto first_scores = [&](int stage) {
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
+    for (int mb = 0; mb < 4; ++mb) {
+      sacc[mb][0] = zero4;
+      sacc[mb][1] = zero4;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) sacc[kt][i] = 0.0f;
-      qk_block(stage, kt, 0);
-      if (!kHalfD) qk_block(stage, kt, 4);
+      for (int ks = 0; ks < kKS; ++ks) {
+        const bf16x8 a = k_operand(stage, mb, ks);
+        sacc[mb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qreg[0][ks], sacc[mb][0], 0, 0, 0);
+        sacc[mb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qreg[1][ks], sacc[mb][1], 0, 0, 0);
+      }
     }
   };
 
@@ -1030,33 +1064,39 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
     // all tile reads are behind the last barrier, so the tile buffers are reused for the exchange:
     // float slot i of wave w, lane l sits at x[(w * 66 + i) * 64 + l]
     float* xch = reinterpret_cast<float*>(smem_raw);
+    constexpr int kSlots = 8 * 2 * 4 + 4;   // O~, the two references, the two sums
     if (!grpA) {
-      float* dst = xch + ((wave - 4) * 66) * 64 + lane;
+      float* dst = xch + ((wave - 4) * kSlots) * 64 + lane;
 #pragma unroll
-      for (int dt = 0; dt < 4; ++dt)
+      for (int db = 0; db < kDB; ++db)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) dst[(16 * dt + i) * 64] = oacc[dt][i];
-      dst[64 * 64] = m;
-      dst[65 * 64] = lsum;
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) dst[((db * 2 + nb) * 4 + e) * 64] = oacc[db][nb][e];
+      dst[64 * 64] = m[0]; dst[65 * 64] = m[1];
+      dst[66 * 64] = lsum[0]; dst[67 * 64] = lsum[1];
     }
     __syncthreads();
     if (!grpA) return;
-    const float* src = xch + (wave * 66) * 64 + lane;
-    const float mB = src[64 * 64], lB = src[65 * 64];
-    const float mm = fmaxf(m, mB);
-    const float wa = (mm == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(m - mm);
-    const float wb = (mm == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(mB - mm);
+    const float* src = xch + (wave * kSlots) * 64 + lane;
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
+    for (int nb = 0; nb < 2; ++nb) {
+      const float mB = src[(64 + nb) * 64], lB = src[(66 + nb) * 64];
+      const float mm = fmaxf(m[nb], mB);
+      const float wa = (mm == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(m[nb] - mm);
+      const float wb = (mm == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(mB - mm);
 #pragma unroll
-      for (int i = 0; i < 16; ++i) oacc[dt][i] = wa * oacc[dt][i] + wb * src[(16 * dt + i) * 64];
-    lsum = wa * lsum + wb * lB;
-    m = mm;
+      for (int db = 0; db < kDB; ++db)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) oacc[db][nb][e] = wa * oacc[db][nb][e] + wb * src[((db * 2 + nb) * 4 + e) * 64];
+      lsum[nb] = wa * lsum[nb] + wb * lB;
+      m[nb] = mm;
+    }
   }
 
   // every tile read of the work-group is behind a barrier here (the one after the last matrix phase)
-  if (kSplit) finish_and_store_direct(s, oacc, m, lsum, b, h, q0, n, g, kMulti && late);
-  else finish_and_store(s, oacc, m, lsum, b, h, q0, n, g, smem_raw + wave * kEpiWaveB, kMulti && late);
+  if (kSplit) finish_and_store_direct<kHalfD>(s, oacc, m, lsum, b, h, q0, r, g, kMulti && late);
+  else finish_and_store<kHalfD>(s, oacc, m, lsum, b, h, q0, r, g, smem_raw + wave * kEpiWaveB, kMulti && late);
 }
 
 template <bool kSplit, bool kExt, bool kMulti = false, bool kNoDead = false, bool kHalfD = false>
