@@ -221,30 +221,42 @@ def main() -> int:
     # standalone merge (the second line under Algorithm 2) on the flux1024_r4 state: 27648 rows x 128,
     # rotating over 8 buffer sets (8 x 21.5 MB x ... beyond what one launch touches, inside the cache)
     mrows = 24 * 1152
-    mo1 = [torch.randn((mrows, 128), device=dev).to(torch.bfloat16) for _ in range(8)]
-    mo2 = [torch.randn((mrows, 128), device=dev).to(torch.bfloat16) for _ in range(8)]
-    ml1 = [torch.randn((mrows,), device=dev) for _ in range(8)]
-    ml2 = [torch.randn((mrows,), device=dev) for _ in range(8)]
+    mo1 = [torch.randn((mrows, 128), device=dev).to(torch.bfloat16) for _ in range(24)]
+    mo2 = [torch.randn((mrows, 128), device=dev).to(torch.bfloat16) for _ in range(24)]
+    ml1 = [torch.randn((mrows,), device=dev) for _ in range(24)]
+    ml2 = [torch.randn((mrows,), device=dev) for _ in range(24)]
     mo = [torch.empty_like(x) for x in mo1]
     ml = [torch.empty_like(x) for x in ml1]
-    t_merge = per_launch(lambda i: P.usp_lse_merge(mo1[i % 8], ml1[i % 8], mo2[i % 8], ml2[i % 8], mo[i % 8], ml[i % 8]))
+    def merge_c(reps=480, rounds=3):
+        D.usp_diag_repeat_merge_calls(48, mo1, ml1, mo2, ml2, mo, ml)
+        ts = []
+        for _ in range(rounds):
+            a, b = _events(2)
+            a.record()
+            D.usp_diag_repeat_merge_calls(reps, mo1, ml1, mo2, ml2, mo, ml)
+            b.record()
+            torch.cuda.synchronize()
+            ts.append(a.elapsed_time(b) / reps)
+        return float(np.median(ts))
+    t_merge = merge_c()
     merge_bytes = mrows * 128 * 3 * 2 + mrows * 12
     del mo1, mo2, ml1, ml2, mo, ml
 
     # what the matrix cores sustain with nothing else issued: one work-group of 8 waves per CU doing
     # back-to-back 32x32x16 bf16 MFMAs on register operands, ~1 ms per launch (the chip lowers its
     # clock under a full matrix-core load, and by how much depends on the operand data)
-    def mfma_probe(random_data):
+    def mfma_probe(random_data, shape=0):
         n_cu = torch.cuda.get_device_properties(dev).multi_processor_count
         iters = 1000
         pout = torch.empty((n_cu * 512,), dtype=torch.float32, device=dev)
         pclk = torch.zeros((2,), dtype=torch.int64, device=dev)
-        t = per_launch(lambda i: D.usp_diag_mfma_rate(n_cu, iters, random_data, pout, pclk), reps=20, rounds=3)
+        t = per_launch(lambda i: D.usp_diag_mfma_rate(n_cu, iters, random_data, pout, pclk, shape=shape), reps=20, rounds=3)
         cyc, ticks = [int(v) for v in pclk.cpu()]
         fl = n_cu * 8 * iters * 32 * 32768.0
         return {"tflops": round(fl / (t * 1e-3) * 1e-12, 1), "shader_mhz": round(cyc / max(ticks, 1) * 100.0),
                 "frac_of_bf16_peak": round(fl / (t * 1e-3) * 1e-12 / PEAK_BF16_TFLOPS, 4)}
     probe_rand, probe_const = mfma_probe(True), mfma_probe(False)
+    probe_rand16 = mfma_probe(True, shape=1)
 
     traffic = measured_traffic("flux1024_u", "attn_pp_kernel<wide,plain>")
     flops = wl.attn_flops()
@@ -297,16 +309,39 @@ def main() -> int:
                                  "gbs": round((R * C * 3 + 4) / (t_quant_pt * 1e-3) * 1e-9, 1),
                                  "note": "the payload as one row (one scale): absmax pass + cast pass, input read twice, cache-warm"},
         "lse_merge": {"us": round(t_merge * 1e3, 2), "gbs": round(merge_bytes / (t_merge * 1e-3) * 1e-9, 1),
-                      "bytes": merge_bytes, "note": "flux1024_r4 state [27648,128] bf16, cache-warm (21 MB per launch)"},
+                      "bytes": merge_bytes, "frac_of_hbm_peak": round(merge_bytes / (t_merge * 1e-3) * 1e-9 / PEAK_HBM_GBS, 4),
+                      "note": "flux1024_r4 state [27648,128] bf16, 24 buffer sets (0.5 GB), calls issued from C"},
         "roofline": {"bound": "mfma", "achieved": round(attn_tflops, 1), "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4),
                      "traffic": traffic["bytes"] if traffic else None, "traffic_detail": traffic,
                      "kernel": "attn_pp_kernel<wide, plain>", "flops_per_launch": flops},
         "mfma_sustained": {"random_operands": probe_rand, "constant_operands": probe_const,
-                           "note": "MFMA-only probe on every CU (libusp_diag.so, usp_diag_mfma_rate): the rate and clock the chip "
-                                   "holds under a full matrix-core load; the published peak assumes 2400 MHz"},
+                           "random_operands_16x16x32": probe_rand16,
+                           "note": "MFMA-only probe on every CU (libusp_diag.so, usp_diag_mfma_rate; 32x32x16 unless named "
+                                   "otherwise): the rate and clock the chip holds under a full matrix-core load; the "
+                                   "published peak assumes 2400 MHz"},
     }
     result["roofline"]["frac_of_sustained_mfma"] = round(attn_tflops / probe_rand["tflops"], 4)
+    result["roofline"]["frac_of_sustained_mfma_16x16x32"] = round(attn_tflops / probe_rand16["tflops"], 4)
+    # the same launch on all-zero Q, K, V: the work and its schedule are unchanged, the matrix cores'
+    # datapaths do not toggle, and the chip holds a higher clock: what the kernel's schedule is worth
+    # when power does not bound it
+    zq = torch.zeros_like(q)
+    for _ in range(400):
+        P.usp_ring_attn_fwd(zq, [zq], [zq], softmax_scale=scale, out=out, lse=lse, workspace=ws)
+    torch.cuda.synchronize()
+    za, zb = _events(2)
+    za.record()
+    for _ in range(1000):
+        P.usp_ring_attn_fwd(zq, [zq], [zq], softmax_scale=scale, out=out, lse=lse, workspace=ws)
+    zb.record()
+    torch.cuda.synchronize()
+    t_zero = za.elapsed_time(zb) / 1000
+    result["attn_zero_operands"] = {"ms": round(t_zero, 4), "tflops": round(flops / (t_zero * 1e-3) * 1e-12, 1),
+                                    "frac_of_bf16_peak": round(flops / (t_zero * 1e-3) * 1e-12 / PEAK_BF16_TFLOPS, 4),
+                                    "note": "same launch, all-zero operands (no toggling in the matrix datapaths): the "
+                                            "difference to attn.ms is the clock the chip gives up under the load"}
+    del zq
 
     if args.calibrate_copy:
         ca = torch.ones((64 << 20,), dtype=torch.int32, device=dev)

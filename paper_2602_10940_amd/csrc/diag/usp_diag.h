@@ -14,14 +14,15 @@ extern "C" {
 
 /* The dense bf16 MFMA rate the device sustains when nothing else is issued: the measured ceiling
  * that the attention kernels' rate can be read against.  wgs work-groups of 8 waves each execute
- * iters * 32 MFMAs (32x32x16, fp32 accumulate, 32768 flop each) per wave on operands held in
- * registers: pseudo-random values in [-1, 1] if random_data != 0, constants otherwise (the clock the
- * chip holds under load depends on the data).
+ * iters * 32 * 32768 flop of MFMAs per wave (shape 0: 32 of 32x32x16; shape 1: 64 of 16x16x32, the
+ * shape the attention kernels use; fp32 accumulate) on operands held in registers: pseudo-random
+ * values in [-1, 1] if random_data != 0, constants otherwise (the clock the chip holds under load
+ * depends on the data and on the shape).
  *   out    : device, wgs * 512 floats, receives per-thread sums (so the work cannot be dropped)
  *   clocks : device, 2 x uint64: shader cycles and 100 MHz ticks that work-group 0 spent in its
  *            loop (their ratio x 100 = shader clock in MHz)
  * Asynchronous on stream.  Limits: 1 <= wgs <= 65536, 1 <= iters <= 1000000. */
-usp_status usp_diag_mfma_rate(int32_t wgs, int32_t iters, int32_t random_data, float* out,
+usp_status usp_diag_mfma_rate(int32_t wgs, int32_t iters, int32_t random_data, int32_t shape, float* out,
                               uint64_t* clocks, void* stream);
 
 /* The pack kernels cast bf16 rows with a division sequence one correction step shorter than the IEEE
@@ -48,6 +49,11 @@ usp_status usp_diag_payload_floor(int32_t kind, int32_t rows, const void* x, uin
 usp_status usp_diag_repeat_payload_calls(int32_t kind, int32_t reps, int32_t n_sets, int64_t rows, int64_t cols,
                                          const void* const* x, uint8_t* const* q, float* const* scales,
                                          void* const* y, void* stream);
+
+/* The same for usp_lse_merge on bf16 [rows, d] states: call i uses set i % n_sets of the host arrays. */
+usp_status usp_diag_repeat_merge_calls(int32_t reps, int32_t n_sets, int64_t rows, int32_t d, const void* const* o1,
+                                       const float* const* lse1, const void* const* o2, const float* const* lse2,
+                                       void* const* o_out, float* const* lse_out, void* stream);
 
 /* usp_ring_attn_fwd (same arguments, no copy stream) with the two knobs of the bounded wait that an
  * attention work-group of the one-launch ring makes for a chunk's arrival counter:

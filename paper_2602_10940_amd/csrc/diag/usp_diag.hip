@@ -22,9 +22,12 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int kProbeThreads = 512;       // 8 waves, two per SIMD, as in the attention kernels
 constexpr int kProbeMfmaPerIter = 32;
 
-// Every wave runs iters * 32 MFMAs (32x32x16, fp32 accumulate) on four A and four B operands held
-// in registers; consecutive instructions take different operands, and four accumulators are in
-// flight per wave.  Work-group 0 records the shader cycles and the 100 MHz ticks of its loop.
+// Every wave runs iters * 32 * 32768 flop of MFMAs on four A and four B operands held in registers
+// (32x32x16: 32 instructions per iteration on four accumulators; 16x16x32: 64 on eight); consecutive
+// instructions take different operands.  Work-group 0 records the shader cycles and the 100 MHz ticks
+// of its loop.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+template <int kShape>
 __global__ __launch_bounds__(kProbeThreads) void mfma_rate_kernel(int iters, int random_data, float* out,
                                                                  unsigned long long* clocks) {
   bf16x8 a[4], b[4];
@@ -36,21 +39,36 @@ __global__ __launch_bounds__(kProbeThreads) void mfma_rate_kernel(int iters, int
       h = h * 1664525u + 1013904223u;
       b[u][i] = (__bf16)(random_data ? ((int)(h >> 16) % 2001 - 1000) * 0.001f : 0.5f);
     }
-  f32x16 c[4];
-  for (int j = 0; j < 4; ++j)
-    for (int i = 0; i < 16; ++i) c[j][i] = 0.0f;
+  float sum = 0.0f;
   const unsigned long long t0 = __builtin_readcyclecounter(), r0 = __builtin_amdgcn_s_memrealtime();
-  for (int it = 0; it < iters; ++it) {
+  if (kShape == 0) {
+    f32x16 c[4];
+    for (int j = 0; j < 4; ++j)
+      for (int i = 0; i < 16; ++i) c[j][i] = 0.0f;
+    for (int it = 0; it < iters; ++it) {
 #pragma unroll
-    for (int u = 0; u < kProbeMfmaPerIter / 4; ++u)
+      for (int u = 0; u < kProbeMfmaPerIter / 4; ++u)
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-        c[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[(u + j) & 3], b[j], c[j], 0, 0, 0);
+        for (int j = 0; j < 4; ++j)
+          c[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[(u + j) & 3], b[j], c[j], 0, 0, 0);
+    }
+    for (int j = 0; j < 4; ++j)
+      for (int i = 0; i < 16; ++i) sum += c[j][i];
+  } else {
+    f32x4 c[8];
+    for (int j = 0; j < 8; ++j)
+      for (int i = 0; i < 4; ++i) c[j][i] = 0.0f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int u = 0; u < kProbeMfmaPerIter / 4; ++u)
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          c[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[(u + j) & 3], b[j & 3], c[j], 0, 0, 0);
+    }
+    for (int j = 0; j < 8; ++j)
+      for (int i = 0; i < 4; ++i) sum += c[j][i];
   }
   const unsigned long long t1 = __builtin_readcyclecounter(), r1 = __builtin_amdgcn_s_memrealtime();
-  float sum = 0.0f;
-  for (int j = 0; j < 4; ++j)
-    for (int i = 0; i < 16; ++i) sum += c[j][i];
   out[(size_t)blockIdx.x * kProbeThreads + threadIdx.x] = sum;   // keeps the work alive
   if (blockIdx.x == 0 && threadIdx.x == 0) { clocks[0] = t1 - t0; clocks[1] = r1 - r0; }
 }
@@ -124,14 +142,19 @@ using namespace usp;
 
 extern "C" {
 
-usp_status usp_diag_mfma_rate(int32_t wgs, int32_t iters, int32_t random_data, float* out, uint64_t* clocks,
-                              void* stream) {
+usp_status usp_diag_mfma_rate(int32_t wgs, int32_t iters, int32_t random_data, int32_t shape, float* out,
+                              uint64_t* clocks, void* stream) {
   clear_error();
   USP_CHECK_ARG(wgs >= 1 && wgs <= 65536, "wgs=%d out of range [1, 65536]", wgs);
   USP_CHECK_ARG(iters >= 1 && iters <= 1000000, "iters=%d out of range [1, 1000000]", iters);
   USP_CHECK_ARG(out != nullptr && clocks != nullptr, "out or clocks is NULL");
-  hipLaunchKernelGGL(mfma_rate_kernel, dim3((unsigned)wgs), dim3(kProbeThreads), 0, (hipStream_t)stream, iters,
-                     random_data, out, reinterpret_cast<unsigned long long*>(clocks));
+  USP_CHECK_ARG(shape == 0 || shape == 1, "shape=%d must be 0 (32x32x16) or 1 (16x16x32)", shape);
+  if (shape == 0)
+    hipLaunchKernelGGL(mfma_rate_kernel<0>, dim3((unsigned)wgs), dim3(kProbeThreads), 0, (hipStream_t)stream, iters,
+                       random_data, out, reinterpret_cast<unsigned long long*>(clocks));
+  else
+    hipLaunchKernelGGL(mfma_rate_kernel<1>, dim3((unsigned)wgs), dim3(kProbeThreads), 0, (hipStream_t)stream, iters,
+                       random_data, out, reinterpret_cast<unsigned long long*>(clocks));
   USP_CHECK_HIP(hipGetLastError());
   return USP_OK;
 }
@@ -173,6 +196,20 @@ usp_status usp_diag_repeat_payload_calls(int32_t kind, int32_t reps, int32_t n_s
       USP_CHECK_ARG(cols == 3072 && rows <= (1 << 24), "the floor kernels take [rows, 3072] payloads");
       st = usp_diag_payload_floor(kind - 2, (int32_t)rows, x[j], q[j], scales[j], stream);
     }
+    if (st != USP_OK) return st;
+  }
+  return USP_OK;
+}
+
+usp_status usp_diag_repeat_merge_calls(int32_t reps, int32_t n_sets, int64_t rows, int32_t d, const void* const* o1,
+                                       const float* const* lse1, const void* const* o2, const float* const* lse2,
+                                       void* const* o_out, float* const* lse_out, void* stream) {
+  clear_error();
+  USP_CHECK_ARG(reps >= 1 && reps <= (1 << 20) && n_sets >= 1, "reps or n_sets out of range");
+  USP_CHECK_ARG(o1 && lse1 && o2 && lse2 && o_out && lse_out, "a buffer array is NULL");
+  for (int i = 0; i < reps; ++i) {
+    const int j = i % n_sets;
+    const usp_status st = usp_lse_merge(rows, d, USP_BF16, o1[j], lse1[j], o2[j], lse2[j], o_out[j], lse_out[j], stream);
     if (st != USP_OK) return st;
   }
   return USP_OK;

@@ -13,17 +13,20 @@ struct MergeW {
   float w1, w2, lse;
 };
 
+// Base-2 hardware exponential and logarithm (1 ulp each): the sum lies in [1, 2], so lse carries an
+// absolute error of about 1e-7, and a weight's relative error is that of one exponential.
 __device__ __forceinline__ MergeW merge_weights(float a, float b) {
+  constexpr float kLog2e = 1.44269504088896340736f, kLn2 = 0.69314718055994530942f;
   MergeW r;
   const float m = fmaxf(a, b);
   if (m == -INFINITY) {  // neither side saw a key
     r.w1 = 0.0f; r.w2 = 0.0f; r.lse = -INFINITY;
     return r;
   }
-  const float sum = expf(a - m) + expf(b - m);
-  r.lse = m + logf(sum);
-  r.w1 = expf(a - r.lse);
-  r.w2 = expf(b - r.lse);
+  const float sum = __builtin_amdgcn_exp2f((a - m) * kLog2e) + __builtin_amdgcn_exp2f((b - m) * kLog2e);
+  r.lse = m + __builtin_amdgcn_logf(sum) * kLn2;
+  r.w1 = __builtin_amdgcn_exp2f((a - r.lse) * kLog2e);
+  r.w2 = __builtin_amdgcn_exp2f((b - r.lse) * kLog2e);
   return r;
 }
 
@@ -32,11 +35,12 @@ __device__ __forceinline__ void ld8(const float* p, float (&v)[8]) {
   v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
 }
 __device__ __forceinline__ void ld8(const bf16_t* p, float (&v)[8]) {
-  uint4 r = *reinterpret_cast<const uint4*>(p);
-  v[0] = __uint_as_float(r.x << 16); v[1] = __uint_as_float(r.x & 0xffff0000u);
-  v[2] = __uint_as_float(r.y << 16); v[3] = __uint_as_float(r.y & 0xffff0000u);
-  v[4] = __uint_as_float(r.z << 16); v[5] = __uint_as_float(r.z & 0xffff0000u);
-  v[6] = __uint_as_float(r.w << 16); v[7] = __uint_as_float(r.w & 0xffff0000u);
+  typedef uint32_t u32x4_m __attribute__((ext_vector_type(4)));
+  const u32x4_m r = __builtin_nontemporal_load(reinterpret_cast<const u32x4_m*>(p));   // read once: streaming
+  v[0] = __uint_as_float(r[0] << 16); v[1] = __uint_as_float(r[0] & 0xffff0000u);
+  v[2] = __uint_as_float(r[1] << 16); v[3] = __uint_as_float(r[1] & 0xffff0000u);
+  v[4] = __uint_as_float(r[2] << 16); v[5] = __uint_as_float(r[2] & 0xffff0000u);
+  v[6] = __uint_as_float(r[3] << 16); v[7] = __uint_as_float(r[3] & 0xffff0000u);
 }
 __device__ __forceinline__ void st8(float* p, const float (&v)[8]) {
   *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);

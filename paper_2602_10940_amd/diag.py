@@ -24,7 +24,7 @@ def load_diag_library() -> ctypes.CDLL:
     lib = ctypes.CDLL(DIAG_LIB_PATH)
     vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
     lib.usp_diag_mfma_rate.restype = i32
-    lib.usp_diag_mfma_rate.argtypes = [i32, i32, i32, vp, vp, vp]
+    lib.usp_diag_mfma_rate.argtypes = [i32, i32, i32, i32, vp, vp, vp]
     lib.usp_diag_check_bf16_division.restype = i32
     lib.usp_diag_check_bf16_division.argtypes = [vp, vp]
     lib.usp_diag_payload_floor.restype = i32
@@ -32,6 +32,8 @@ def load_diag_library() -> ctypes.CDLL:
     lib.usp_diag_repeat_payload_calls.restype = i32
     lib.usp_diag_repeat_payload_calls.argtypes = [i32, i32, i32, ctypes.c_int64, ctypes.c_int64, ctypes.POINTER(vp),
                                                   ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), vp]
+    lib.usp_diag_repeat_merge_calls.restype = i32
+    lib.usp_diag_repeat_merge_calls.argtypes = [i32, i32, ctypes.c_int64, i32] + [ctypes.POINTER(vp)] * 6 + [vp]
     lib.usp_diag_ring_attn_fwd_wait.restype = i32
     lib.usp_diag_ring_attn_fwd_wait.argtypes = [ctypes.POINTER(B.AttnDesc), vp, ctypes.POINTER(vp), ctypes.POINTER(vp),
                                                 ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp),
@@ -41,12 +43,12 @@ def load_diag_library() -> ctypes.CDLL:
 
 
 def usp_diag_mfma_rate(wgs: int, iters: int, random_data: bool, out: torch.Tensor, clocks: torch.Tensor,
-                       stream=None) -> None:
+                       stream=None, shape: int = 0) -> None:
     """out: f32 device tensor of wgs*512 elements; clocks: int64 device tensor of 2 (shader cycles, 100 MHz ticks)."""
     lib = load_diag_library()
     assert out.dtype == torch.float32 and out.numel() >= wgs * 512 and out.is_contiguous()
     assert clocks.dtype == torch.int64 and clocks.numel() >= 2 and clocks.is_contiguous()
-    B._check(lib.usp_diag_mfma_rate(int(wgs), int(iters), 1 if random_data else 0, B._ptr(out), B._ptr(clocks),
+    B._check(lib.usp_diag_mfma_rate(int(wgs), int(iters), 1 if random_data else 0, int(shape), B._ptr(out), B._ptr(clocks),
                                     B._stream_handle(stream)))
 
 
@@ -73,6 +75,14 @@ def usp_diag_repeat_payload_calls(kind: int, reps: int, xs, qs, ss, ys, stream=N
     assert all(t.shape == (rows, cols) and t.is_contiguous() for t in list(xs) + list(qs) + list(ys))
     B._check(lib.usp_diag_repeat_payload_calls(int(kind), int(reps), len(xs), rows, cols, B._ptr_array(xs), B._ptr_array(qs),
                                                B._ptr_array(ss), B._ptr_array(ys), B._stream_handle(stream)))
+
+
+def usp_diag_repeat_merge_calls(reps: int, o1, l1, o2, l2, o, l, stream=None) -> None:
+    """reps back-to-back usp_lse_merge calls issued from C over the buffer sets (lists of bf16 [rows, d] / f32 [rows])."""
+    lib = load_diag_library()
+    rows, d = o1[0].shape
+    B._check(lib.usp_diag_repeat_merge_calls(int(reps), len(o1), rows, d, B._ptr_array(o1), B._ptr_array(l1), B._ptr_array(o2),
+                                             B._ptr_array(l2), B._ptr_array(o), B._ptr_array(l), B._stream_handle(stream)))
 
 
 def usp_diag_ring_attn_fwd_wait(q: torch.Tensor, k_chunks: Sequence[torch.Tensor], v_chunks: Sequence[torch.Tensor],

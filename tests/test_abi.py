@@ -61,8 +61,8 @@ def test_diag_library_is_separate_from_the_abi():
     from paper_2602_10940_amd import diag
     dl = diag.load_diag_library()
     lib.usp_last_error.restype = ctypes.c_char_p
-    assert dl.usp_diag_mfma_rate(0, 10, 1, None, None, None) == -1         # wgs out of range
-    assert dl.usp_diag_mfma_rate(4, 10, 1, None, None, None) == -1         # NULL buffers
+    assert dl.usp_diag_mfma_rate(0, 10, 1, 0, None, None, None) == -1         # wgs out of range
+    assert dl.usp_diag_mfma_rate(4, 10, 1, 0, None, None, None) == -1         # NULL buffers
     assert b"NULL" in lib.usp_last_error()
     src = open(os.path.join(ROOT, "paper_2602_10940_amd", "csrc", "diag", "usp_diag.h")).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)

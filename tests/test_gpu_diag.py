@@ -10,15 +10,17 @@ from tests.gpu_util import DEV
 pytestmark = pytest.mark.gpu
 
 
-def test_probe_constant_operands_sum_exactly():
+@pytest.mark.parametrize("shape", [0, 1])
+def test_probe_constant_operands_sum_exactly(shape):
     from paper_2602_10940_amd import diag as P
     wgs, iters = 6, 10
     out = torch.full((wgs * 512,), -1.0, dtype=torch.float32, device=DEV)
     clocks = torch.zeros((2,), dtype=torch.int64, device=DEV)
-    P.usp_diag_mfma_rate(wgs, iters, False, out, clocks)
+    P.usp_diag_mfma_rate(wgs, iters, False, out, clocks, shape=shape)
     torch.cuda.synchronize()
-    # A = 1, B = 0.5: one MFMA adds 16 * 0.5 to each of a lane's 16 accumulator elements; an accumulator
-    # takes 8 MFMAs per iteration; a thread sums its 4 accumulators
+    # A = 1, B = 0.5.  32x32x16: one MFMA adds 16 * 0.5 to each of a lane's 16 accumulator elements; an
+    # accumulator takes 8 MFMAs per iteration; a thread sums its 4 accumulators.  16x16x32: 32 * 0.5 to each
+    # of 4 elements, 8 MFMAs per accumulator and iteration, 8 accumulators: the same total
     want = 4 * 16 * 8 * 8.0 * iters
     assert torch.all(out == want), (out.min().item(), out.max().item(), want)
     cyc, ticks = [int(v) for v in clocks.cpu()]
