@@ -243,7 +243,13 @@ __global__ __launch_bounds__(256) void fp8_absmax_chunks_kernel(const T* __restr
   const int64_t u0 = (int64_t)blockIdx.x * chunk_units, u1 = min(u0 + chunk_units, units);
   const T* xr = x + row * units * 8;
   float a = 0.0f;
-  for (int64_t u = u0 + threadIdx.x; u < u1; u += 256) {
+  int64_t u = u0 + threadIdx.x;
+  for (; u + 768 < u1; u += 1024) {      // four loads in flight per thread
+    float v0[8], v1[8], v2[8], v3[8];
+    load8(xr + u * 8, v0); load8(xr + (u + 256) * 8, v1); load8(xr + (u + 512) * 8, v2); load8(xr + (u + 768) * 8, v3);
+    a = absmax8(v0, a); a = absmax8(v1, a); a = absmax8(v2, a); a = absmax8(v3, a);
+  }
+  for (; u < u1; u += 256) {
     float v[8];
     load8(xr + u * 8, v);
     a = absmax8(v, a);
@@ -265,10 +271,21 @@ __global__ __launch_bounds__(256) void fp8_quant_chunks_kernel(const T* __restri
   const int64_t u0 = (int64_t)blockIdx.x * chunk_units, u1 = min(u0 + chunk_units, units);
   const int64_t base = row * units * 8;
   const RowDiv d = make_rowdiv(scale_from_absmax(absmax[row]));
-  for (int64_t u = u0 + threadIdx.x; u < u1; u += 256) {
+  auto cast = [&](const float (&v)[8]) -> uint2 { return d.fast ? encode8<true>(v, d) : encode8<false>(v, d); };
+  int64_t u = u0 + threadIdx.x;
+  for (; u + 768 < u1; u += 1024) {      // four loads in flight per thread
+    float v0[8], v1[8], v2[8], v3[8];
+    load8(x + base + u * 8, v0); load8(x + base + (u + 256) * 8, v1);
+    load8(x + base + (u + 512) * 8, v2); load8(x + base + (u + 768) * 8, v3);
+    *reinterpret_cast<uint2*>(q + base + u * 8) = cast(v0);
+    *reinterpret_cast<uint2*>(q + base + (u + 256) * 8) = cast(v1);
+    *reinterpret_cast<uint2*>(q + base + (u + 512) * 8) = cast(v2);
+    *reinterpret_cast<uint2*>(q + base + (u + 768) * 8) = cast(v3);
+  }
+  for (; u < u1; u += 256) {
     float v[8];
     load8(x + base + u * 8, v);
-    *reinterpret_cast<uint2*>(q + base + u * 8) = d.fast ? encode8<true>(v, d) : encode8<false>(v, d);
+    *reinterpret_cast<uint2*>(q + base + u * 8) = cast(v);
   }
 }
 __global__ void fp8_scales_from_absmax_kernel(float* scales, int64_t rows) {
@@ -440,7 +457,13 @@ usp_status quant_dispatch(int64_t rows, int64_t cols, const T* x, uint8_t* q, fl
     const dim3 grid((unsigned)((units + chunk_units - 1) / chunk_units), (unsigned)rows);
     const unsigned rb = (unsigned)((rows + 255) / 256);
     hipLaunchKernelGGL(fp8_fill_kernel, dim3(rb), dim3(256), 0, st, scales, rows, 0.0f);
-    hipLaunchKernelGGL((fp8_absmax_chunks_kernel<T>), grid, dim3(256), 0, st, x, scales, units, chunk_units);
+    // the maximum pass ends in one atomic per block on the row's word, and those serialise (about 10 ns
+    // each): at most 512 blocks over all rows
+    int64_t a_per_row = (512 + rows - 1) / rows;
+    int64_t a_units = (units + a_per_row - 1) / a_per_row;
+    a_units = (a_units + 1023) / 1024 * 1024;
+    const dim3 a_grid((unsigned)((units + a_units - 1) / a_units), (unsigned)rows);
+    hipLaunchKernelGGL((fp8_absmax_chunks_kernel<T>), a_grid, dim3(256), 0, st, x, scales, units, a_units);
     hipLaunchKernelGGL((fp8_quant_chunks_kernel<T>), grid, dim3(256), 0, st, x, q, scales, units, chunk_units);
     hipLaunchKernelGGL(fp8_scales_from_absmax_kernel, dim3(rb), dim3(256), 0, st, scales, rows);
   }
