@@ -92,3 +92,32 @@ def test_limits_are_errors_with_nothing_enqueued():
     assert e.value.status == -3 and "scratch" in str(e.value)
     torch.cuda.synchronize()
     assert float(out.float().abs().sum()) == 0.0 and float(lse.abs().sum()) == 0.0
+
+
+@pytest.mark.parametrize("flags", [0, FUSED, STEPWISE])
+def test_replays_from_a_hip_graph(flags):
+    """The caller this entry point names: the call recorded into a HIP graph (nothing may allocate under
+    capture).  Replays, with eager calls of another shape on the same scratch in between, must
+    reproduce the eager result bit for bit."""
+    import paper_2602_10940_amd as P
+    _, r = _inputs(76, 1, 3, 260, (192, 128, 64), masked=(300, 340))
+    _, other = _inputs(77, 1, 2, 100, (64, 128))
+    out = torch.empty_like(r["q"])
+    lse = torch.empty(r["q"].shape[:3], dtype=torch.float32, device=DEV)
+    o2 = torch.empty_like(other["q"])
+    l2 = torch.empty(other["q"].shape[:3], dtype=torch.float32, device=DEV)
+    ref_o, ref_l = P.usp_ring_attn_fwd(flags=flags, **r)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            P.usp_ring_attn_fwd_noalloc(out=out, lse=lse, flags=flags, **r)
+    torch.cuda.synchronize()
+    for _ in range(3):
+        out.zero_(); lse.zero_()
+        P.usp_ring_attn_fwd_noalloc(out=o2, lse=l2, flags=flags, **other)   # leaves its state in the scratch
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref_o) and torch.equal(lse, ref_l)
