@@ -380,6 +380,30 @@ __global__ __launch_bounds__(256) void attn_fp8_chunk_prepare_kernel(AttnStep s,
   fp8_chunk_prepare<false>(s, c, (int64_t)blockIdx.x * 256 + threadIdx.x, (int64_t)gridDim.x * 256);
 }
 
+// The same for a step of the launch-per-chunk form (the chunk is s.chunk[0] of a one-chunk description):
+// codes -> bf16 K and V and the per-tile records in one launch instead of three, plus the count of tiles up
+// to the last live key of every batch entry, which the attention kernel of a single chunk stops at.
+__global__ __launch_bounds__(256) void attn_fp8_step_prepare_kernel(AttnStep s, int* n_live) {
+  fp8_chunk_prepare<false>(s, 0, (int64_t)blockIdx.x * 256 + threadIdx.x, (int64_t)gridDim.x * 256);
+  if (blockIdx.x == 0 && threadIdx.x < 64) {
+    const AttnStep::Chunk& ch = s.chunk[0];
+    const int t = threadIdx.x;
+    for (int b = 0; b < s.B; ++b) {
+      int last = ch.Sc - 1;
+      if (ch.mask_src != nullptr) {
+        last = -1;
+        const uint8_t* mask = ch.mask_src + (int64_t)b * ch.Sc;
+#pragma unroll 8
+        for (int k0 = t; k0 < ch.Sc; k0 += 64)
+          if (mask[k0] != 0) last = k0;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) last = max(last, __shfl_xor(last, o, 64));
+      }
+      if (t == 0) n_live[b] = last < 0 ? 0 : last / kTile + 1;
+    }
+  }
+}
+
 // One work-group's share: the queries q_base .. q_base + 255 (wide) or + 127 (split) of (batch, head) bh_.
 // kNoDead (with kExt): the records carry per-key factors only, no key of the launch is dead (FP8
 // scales on unmasked chunks of whole tiles): the per-tile flag is not read at all.
@@ -1188,6 +1212,19 @@ usp_status launch_attn_fp8_chunk_prepare(const AttnStep& s, int c, bool reset_ar
   const int64_t blocks = (units + 255) / 256;                          // one unit per thread while the chunk is small
   hipLaunchKernelGGL(attn_fp8_chunk_prepare_kernel, dim3((unsigned)(blocks < 1 ? 1 : blocks > 8192 ? 8192 : blocks)), dim3(256),
                      0, st, s, c, reset_arrive ? 1 : 0);
+  USP_CHECK_HIP(hipGetLastError());
+  return USP_OK;
+}
+
+usp_status launch_attn_fp8_step_prepare(const AttnStep& s, int* n_live, hipStream_t st) {
+  if (!s.multi_fp8 || s.n_multi != 1 || !s.ext || !n_live || s.chunk[0].Sc <= 0 || s.chunk[0].Sc % kTile != 0) {
+    set_error("FP8 step preparation needs one FP8 chunk of whole tiles with room for its records");
+    return USP_ERR_INVALID_ARG;
+  }
+  const int64_t units = (int64_t)s.B * s.H * s.chunk[0].Sc * (s.d / 16);   // 16 codes each
+  const int64_t blocks = (units + 255) / 256;
+  hipLaunchKernelGGL(attn_fp8_step_prepare_kernel, dim3((unsigned)(blocks < 1 ? 1 : blocks > 8192 ? 8192 : blocks)), dim3(256),
+                     0, st, s, n_live);
   USP_CHECK_HIP(hipGetLastError());
   return USP_OK;
 }

@@ -641,7 +641,30 @@ usp_status usp::ring_attn_fwd_impl(const usp_attn_desc* desc, const void* q, con
       }
     } else a.mode = r == 0 ? 1 : (r == p.W - 1 ? 3 : 2);
 
-    if (p.dequant_stage && len > 0) {
+    bool records_ready = false;
+    if (p.dequant_stage && len > 0 && len % 64 == 0 && aligned16(kp) && aligned16(vp) && aligned16(ksp) && aligned16(vsp) &&
+        ((uintptr_t)a.key_mask & 3u) == 0) {
+      // Algorithm 1 line 4 for a chunk of whole tiles, in one launch: K widened exactly, V dequantised to
+      // bf16(code * scale), the per-tile records (K's scales as per-key factors, the mask) and the live-tile
+      // counts; the same arithmetic as the three launches of the general case below, bit for bit
+      AttnStep m;
+      memset(&m, 0, sizeof(m));
+      m.B = desc->B; m.H = desc->H; m.d = d; m.scale = scale;
+      m.n_multi = 1; m.multi_fp8 = 1;
+      m.ext = (float*)(ws + p.off_ext);
+      AttnStep::Chunk& c = m.chunk[0];
+      c.k = ws + p.off_deq_k; c.v = ws + p.off_deq_v; c.Sc = len;
+      c.ks0 = (int64_t)desc->H * len * d; c.ks1 = (int64_t)len * d;
+      c.k_src = kp; c.v_src = vp; c.k_scale_src = ksp; c.v_scale_src = vsp;
+      c.mask_src = a.key_mask;
+      if ((st = launch_attn_fp8_step_prepare(m, (int*)(ws + p.off_nlive), cs)) != USP_OK) return st;
+      a.k = c.k; a.v = c.v;
+      a.v_scale = nullptr;
+      a.kv_dtype = USP_BF16;
+      a.ext = m.ext;
+      a.n_live = (int*)(ws + p.off_nlive);
+      records_ready = true;
+    } else if (p.dequant_stage && len > 0) {
       // Algorithm 1 line 4.  K: the codes are widened to bf16 exactly here (scale 1) and the MFMA
       // kernel multiplies the fp32 scores by the per-token scales, so the exponents see no rounding
       // beyond the quantisation itself.  V: dequantised to the working precision, bf16(code * scale).
@@ -657,7 +680,7 @@ usp_status usp::ring_attn_fwd_impl(const usp_attn_desc* desc, const void* q, con
       a.k_scale = nullptr; a.v_scale = nullptr;
       a.kv_dtype = USP_BF16;
     }
-    if (attn_mfma_supported(a) && attn_mfma_needs_ext(a)) {
+    if (!records_ready && attn_mfma_supported(a) && attn_mfma_needs_ext(a)) {
       a.ext = (float*)(ws + p.off_ext);
       a.n_live = (int*)(ws + p.off_nlive);
       if ((st = launch_attn_ext_prepare(a, cs)) != USP_OK) return st;

@@ -170,6 +170,9 @@ usp_status launch_attn_multi_records(const AttnStep& s, hipStream_t st);
 // chunk c of a step over several FP8 chunks decoded by a launch of its own; reset_arrive: the same
 // launch zeroes the arrival counters (it precedes the attention launch on the stream)
 usp_status launch_attn_fp8_chunk_prepare(const AttnStep& s, int c, bool reset_arrive, hipStream_t st);
+// One FP8 chunk of a launch-per-chunk step (s describes it as the only chunk of a several-chunk launch): bf16 K
+// and V, the per-tile records and n_live[B] in one launch
+usp_status launch_attn_fp8_step_prepare(const AttnStep& s, int* n_live, hipStream_t st);
 
 
 // What usp_ring_attn_fwd does, with the knobs the ABI does not carry.
