@@ -488,7 +488,7 @@ def ring_leg(P, W, torch, dev, up_bf16, name="flux1024_r4", reps=600):
            "bytes_moved_bf16": 2 * kv_bytes(ks, []), "bytes_moved_fp8": kv_bytes(kq, ksc) + kv_bytes(vq, vsc),
            "compute_over_bf16": round(t8_c / t_c, 3),
            "note": "per-chunk forms: each chunk's codes are widened to bf16 (scales folded into the per-key records) "
-                   "by launches of their own before its attention launch; one launch: copy work-groups of the "
+                   "by a launch of its own before its attention launch; one launch: copy work-groups of the "
                    "attention launch decode chunk r+1 while chunk r is computed on (the plain call and "
                    "USP_ATTN_FUSED_PREFETCH give this same launch)"}
     # the same bf16 ring with a key mask on its last chunk (its last tenth of the keys dead, as padded
