@@ -359,3 +359,28 @@ def test_masked_fp8_ring_many_calls_through_one_workspace():
         torch.cuda.synchronize()
         bad += sum(1 for i, (o, l) in outs if not (torch.equal(o, refs[i][0]) and torch.equal(l, refs[i][1])))
     assert bad == 0, bad
+
+
+def test_fp8_step_preparation_one_launch_and_three_agree():
+    """A chunk of whole tiles with 16-byte aligned scales is prepared by one launch (K widened, V
+    dequantised, records, live-tile counts); scales that are only 4-byte aligned, like a ragged chunk,
+    take the three launches of the general case.  Same arithmetic: the results must be equal bit for bit,
+    with and without a key mask."""
+    wl = W.Workload("fp8_step_prep", 91, 2, 3, 128, 200, (128, 192, 64), "bf16", masked_keys=(250, 330))
+    inp, q, kq, ksc, vq, vsc, kx, vx = _fp8_ring(wl)
+    scale = float(inp.softmax_scale)
+    km = [torch.from_numpy(m).to(DEV) for m in inp.key_mask]
+
+    def shifted(t):   # the same values at an address that is 4 bytes past a 16-byte boundary
+        buf = torch.empty((t.numel() + 4,), dtype=t.dtype, device=DEV)
+        assert buf.data_ptr() % 16 == 0
+        v = buf[1:1 + t.numel()].view(t.shape)
+        v.copy_(t)
+        return v
+
+    for mask in (None, km):
+        ref_o, ref_l = _call(q, kq, ksc, vq, vsc, scale, 64, key_mask=mask)                       # one launch per chunk
+        o, l = _call(q, kq, [shifted(s) for s in ksc], vq, [shifted(s) for s in vsc], scale, 64, key_mask=mask)
+        assert torch.equal(o, ref_o) and torch.equal(l, ref_l)
+    ro, rl = orc.ring_attention(inp.q, kx, vx, scale, inp.key_mask)
+    _assert_parity(host_f64(o), host_f64(l), ro, rl)
