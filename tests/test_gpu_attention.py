@@ -311,8 +311,8 @@ def test_fp8_kv_ring_against_oracle_on_dequantised_values():
 
 
 def test_fp8_kv_d64():
-    """FP8 K/V with head dimension 64 and bf16 Q: codes zero-padded to d = 128 (the zero code is 0.0),
-    then the d = 128 path."""
+    """FP8 K/V with head dimension 64 and bf16 Q: codes widened to bf16 rows of 64, then the matrix-core
+    kernels in their head-dimension-64 form."""
     P = _P()
     rng = np.random.Generator(np.random.PCG64(9))
     B, H, Sq, L, d = 1, 2, 50, 70, 64

@@ -1,6 +1,6 @@
-"""bf16 attention with head dimension 64: the call runs on the d = 128 matrix-core kernels with
-zero-padded copies of Q, K and V (zero columns change neither the scores nor the first 64 columns of
-O).  Parity against the fp64 oracle on the original d = 64 tensors."""
+"""bf16 attention with head dimension 64: the call runs on the matrix-core kernels in their
+head-dimension-64 form (128-byte rows of Q, K, V and O read and written in place).  Parity against the
+fp64 oracle."""
 import numpy as np
 import pytest
 import torch
