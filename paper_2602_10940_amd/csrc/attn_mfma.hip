@@ -920,7 +920,10 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
     if (!kMulti) { kpre += kPreStep * tileB; vpre += kPreStep * tileB; }
     kpre_idx += kPreStep;
     vpre_idx += kPreStep;
-    if (__builtin_amdgcn_ballot_w64(!(psum[0] <= kCertifiedSum && psum[1] <= kCertifiedSum)) != 0ull) {
+    // (per query block: a block all of whose lanes passed keeps its exponentials and its reference)
+    const bool redo0 = __builtin_amdgcn_ballot_w64(!(psum[0] <= kCertifiedSum)) != 0ull;
+    const bool redo1 = __builtin_amdgcn_ballot_w64(!(psum[1] <= kCertifiedSum)) != 0ull;
+    if (redo0 || redo1) {
       // a reference that was already set and still failed: scores with heavy tails; look for the
       // maximum first on the next tiles instead of paying for the exponentials twice
       if (__builtin_amdgcn_ballot_w64(m[0] != -INFINITY || m[1] != -INFINITY) != 0ull) max_first = kMaxFirstTiles;
@@ -929,6 +932,7 @@ __device__ __forceinline__ void attn_pp_body(const AttnStep& s, unsigned char* s
       if (kExt) { x_load(0, xs); x_load(1, xs); }
 #pragma unroll
       for (int nb = 0; nb < 2; ++nb) {
+        if (!(nb ? redo1 : redo0)) continue;
         const float m_new = tmax[nb] > m[nb] ? tmax[nb] + kRefMargin : m[nb];
         // m = -inf (first live tile) gives alpha 0; no live key so far: nothing to rescale, P = 0
         const float alpha = m_new == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(m[nb] - m_new);
